@@ -1,0 +1,201 @@
+/*
+ * zgr.h -- C ABI of the client-side ZGR step (zeroth-order optimisation with
+ * gradient rectification) for one AMD MI355X (gfx950) GPU.
+ *
+ * The calls follow the paper's statement of the problem:
+ *   - objective and two-point estimator: Sec. 4.2, Eq. (9);
+ *   - hybrid perturbation z_h = sqrt(alpha/n) z + sqrt((1-alpha)/m) V z_g: Eq. (10);
+ *   - rectified estimator: Eq. (11);
+ *   - client procedure (perturb, two forward passes, send one scalar) and
+ *     edge-server procedure (regenerate z_h from the seed, update): Algorithm 1;
+ *   - in-place application of the perturbation to the local model: Sec. 4.1,
+ *     workflow step 5.
+ *
+ * Conventions
+ *   - Every pointer marked DEVICE is device memory of the current HIP device,
+ *     owned by the caller, and stays valid for the lifetime of the context.
+ *     Pointers marked HOST are host memory.
+ *   - The library allocates no device memory: parameters, bases, batch and
+ *     workspace all come from the caller.
+ *   - All work is enqueued on the HIP stream given to zgr_init.  zgr_step
+ *     synchronises that stream once (to read the two losses); the other calls
+ *     return after enqueueing unless stated otherwise.
+ *   - Every call returns a zgr_status; nothing throws across the boundary.
+ *     zgr_last_error gives a human-readable message for the last failure.
+ *   - One context per stream; a context is not re-entrant.
+ */
+#ifndef ZGR_H
+#define ZGR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct zgr_ctx zgr_ctx; /* opaque, library-owned host object */
+
+typedef enum {
+  ZGR_OK = 0,
+  ZGR_ERR_NULL = 1,       /* a required pointer is NULL                              */
+  ZGR_ERR_SHAPE = 2,      /* tensor / batch shapes do not fit the model              */
+  ZGR_ERR_DTYPE = 3,      /* unknown or mixed storage types                          */
+  ZGR_ERR_CONFIG = 4,     /* hyper-parameter out of range                            */
+  ZGR_ERR_WORKSPACE = 5,  /* workspace too small or misaligned                       */
+  ZGR_ERR_DEVICE = 6,     /* a HIP call failed                                       */
+  ZGR_ERR_NONFINITE = 7,  /* a loss is NaN/Inf (parameters are still restored)       */
+  ZGR_ERR_STATE = 8       /* call not valid for this context (e.g. no model)         */
+} zgr_status;
+
+typedef enum { ZGR_F32 = 0, ZGR_BF16 = 1 } zgr_dtype;
+
+/* Scaling of Eq. (10).  UNIT multiplies it by sqrt(n) so that the mean
+ * variance per coordinate is 1, the scale of the non-guided z ~ N(0, I):
+ *   a = sqrt(alpha),            b = sqrt((1-alpha) rows / k).
+ * PAPER is the equation as printed with n = rows*cols, m = k*cols:
+ *   a = sqrt(alpha/(rows cols)), b = sqrt((1-alpha)/(k cols)).                 */
+typedef enum { ZGR_SCALE_UNIT = 0, ZGR_SCALE_PAPER = 1 } zgr_scale_mode;
+
+typedef enum { ZGR_ARCH_NONE = -1, ZGR_ARCH_LINEAR_LSQ = 0, ZGR_ARCH_DECODER_LM = 1,
+               ZGR_ARCH_ENCODER_CLS = 2 } zgr_arch;
+
+/* Which model weight a tensor is.  2-D weights are [out, in] row-major. */
+typedef enum {
+  ZGR_ROLE_LSQ_W = 0, ZGR_ROLE_TOK_EMB = 1, ZGR_ROLE_POS_EMB = 2,
+  ZGR_ROLE_LN1_G = 3, ZGR_ROLE_LN1_B = 4,
+  ZGR_ROLE_WQ = 5, ZGR_ROLE_BQ = 6, ZGR_ROLE_WK = 7, ZGR_ROLE_BK = 8, ZGR_ROLE_WV = 9, ZGR_ROLE_BV = 10,
+  ZGR_ROLE_WO = 11, ZGR_ROLE_BO = 12, ZGR_ROLE_LN2_G = 13, ZGR_ROLE_LN2_B = 14,
+  ZGR_ROLE_W1 = 15, ZGR_ROLE_B1 = 16, ZGR_ROLE_W2 = 17, ZGR_ROLE_B2 = 18,
+  ZGR_ROLE_LNF_G = 19, ZGR_ROLE_LNF_B = 20, ZGR_ROLE_CLS_W = 21, ZGR_ROLE_CLS_B = 22,
+  ZGR_ROLE_COUNT = 23
+} zgr_role;
+
+/* One parameter tensor of the model W in R^d (Sec. 4.2). */
+typedef struct {
+  void*        theta;      /* DEVICE, 16-byte aligned, rows*cols elements, row-major, MUTATED IN PLACE */
+  int64_t      rows, cols; /* 1-D tensors: rows = 1                                            */
+  int32_t      dtype;      /* zgr_dtype; all tensors of a context share one                    */
+  uint32_t     tensor_id;  /* < 2^31, unique; enters the Philox counter                        */
+  const float* U;          /* DEVICE, rows x ldu fp32, orthonormal columns; NULL => isotropic  */
+  int32_t      k, ldu;     /* first k columns of U are used (k <= ldu, k <= rows, k <= 64);
+                              a guided tensor needs cols % 4 == 0 (cols % 8 with gauss_bits 16) */
+  int32_t      role;       /* zgr_role                                                         */
+  int32_t      layer;      /* block index, -1 for tensors outside the blocks                   */
+} zgr_tensor;
+
+/* Model whose loss the two forward passes evaluate.  arch = ZGR_ARCH_NONE
+ * gives a context that can only perturb/update (the edge server of Algorithm 1).
+ * Transformer archs: d_model % n_head == 0, head size in {8, 16, 32, 64}; with
+ * bf16 storage d_model and d_ff must be multiples of 64.  Wq, Wk, Wv of a layer
+ * must be adjacent in memory in that order (one [3 d, d] matrix), and so must
+ * bq, bk, bv.  LINEAR_LSQ: one fp32 tensor ZGR_ROLE_LSQ_W [out, in]; the other
+ * fields are ignored.                                                           */
+typedef struct {
+  int32_t arch;            /* zgr_arch                                                         */
+  int32_t n_layer, d_model, n_head, d_ff, vocab, max_pos, n_class;
+  float   ln_eps;
+} zgr_model;
+
+/* Hyper-parameters of Algorithm 1 ("Require" list). */
+typedef struct {
+  uint64_t seed;           /* shared random seed s                                             */
+  float    eps;            /* perturbation scale epsilon                                       */
+  float    alpha;          /* mixing ratio alpha in [0, 1] (weight of the isotropic term)      */
+  int32_t  scale_mode;     /* zgr_scale_mode                                                   */
+  int32_t  gauss_bits;     /* 32: 4 Gaussians per Philox call; 16: 8 per call                  */
+} zgr_config;
+
+/* One mini-batch x_i.  All DEVICE.
+ *   DECODER_LM : x = int32 tokens [batch, seq]; y, lengths unused (targets are x shifted by one).
+ *   ENCODER_CLS: x = int32 tokens [batch, seq]; y = int32 labels [batch]; lengths = int32 [batch],
+ *                keys at positions >= lengths[b] are masked out.
+ *   LINEAR_LSQ : x = fp32 X [batch, in]; y = fp32 Y [batch, out]; seq ignored.                */
+typedef struct {
+  const void*    x;
+  const void*    y;
+  const int32_t* lengths;
+  int32_t        batch, seq;
+} zgr_batch;
+
+typedef struct {           /* HOST */
+  double loss_plus;        /* L(W + eps z_h; x)                                                */
+  double loss_minus;       /* L(W - eps z_h; x)                                                */
+  float  g;                /* (L+ - L-) / (2 eps), the scalar of Eq. (11)                      */
+} zgr_result;
+
+/* Bytes of DEVICE workspace zgr_init needs for this tensor table (only the
+ * shapes, dtype, k of the entries are read; theta and U may be NULL here) and
+ * forward passes of up to max_batch x max_seq tokens.  The workspace must be
+ * 256-byte aligned.  Returns 0 if the arguments are invalid.                   */
+size_t zgr_workspace_bytes(const zgr_model* model, const zgr_tensor* tensors, int32_t n_t,
+                           int32_t max_batch, int32_t max_seq);
+
+/* Creates a context over n_t caller-owned tensors.  Copies the tensor table
+ * and validates it against the model (every role present once per layer,
+ * shapes consistent).  hip_stream is a hipStream_t (NULL = default stream).
+ * On failure *out is NULL unless the status is about the table itself, in
+ * which case no context is made either; the message is then available from
+ * zgr_last_error(NULL).                                                        */
+zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* tensors, int32_t n_t,
+                    const zgr_config* config, void* workspace, size_t workspace_bytes,
+                    int32_t max_batch, int32_t max_seq, void* hip_stream);
+
+/* Guided round: install the basis the cloud sent for one tensor (Algorithm 1,
+ * "broadcast guided perturbation"); U = NULL or k = 0 makes the tensor
+ * isotropic (non-guided round).                                                */
+zgr_status zgr_set_basis(zgr_ctx* ctx, int32_t tensor_index, const float* U, int32_t k, int32_t ldu);
+
+/* Client block of Algorithm 1 for round/step `step` (< 2^32): perturb all
+ * tensors in place by +eps Z, evaluate L+, by -2 eps Z, evaluate L-, restore by
+ * +eps Z, Z regenerated from (seed, step) in each pass.  Fills *out.  On
+ * return the parameters hold their pre-step values up to rounding of the
+ * storage type.  ZGR_ERR_NONFINITE still restores the parameters.              */
+zgr_status zgr_step(zgr_ctx* ctx, uint64_t step, const zgr_batch* batch, zgr_result* out);
+
+/* Edge-server block of Algorithm 1 for one client with weight 1:
+ * theta <- theta - lr g Z(seed, step).  A pure function of (theta, seed, step,
+ * bases, lr*g): valid on a context that never ran the forward passes.  The
+ * product lr*g is formed in fp32.  Asynchronous.                                */
+zgr_status zgr_apply_update(zgr_ctx* ctx, uint64_t step, float g, float lr);
+
+/* theta <- theta + c Z(seed, step) for all tensors: the single pass that
+ * zgr_step and zgr_apply_update are made of.  Asynchronous.                    */
+zgr_status zgr_perturb(zgr_ctx* ctx, uint64_t step, float c);
+
+/* One loss evaluation at the current parameters (synchronises the stream). */
+zgr_status zgr_loss(zgr_ctx* ctx, const zgr_batch* batch, double* loss_out /* HOST */);
+
+void        zgr_destroy(zgr_ctx* ctx);
+const char* zgr_last_error(const zgr_ctx* ctx); /* ctx may be NULL: last error of a failed zgr_init */
+
+/* ---- profiling: HIP-event timing of kernel classes on the context's stream ---- */
+typedef enum { ZGR_K_PERTURB_TILE = 0 /* guided matrices */, ZGR_K_PERTURB_FLAT = 1 /* isotropic tensors */,
+               ZGR_K_GEMM = 2, ZGR_K_ATTN = 3, ZGR_K_NORM = 4, ZGR_K_EMBED = 5, ZGR_K_LOSS = 6,
+               ZGR_K_COUNT = 7 } zgr_kernel_class;
+/* Enables (1) / disables (0) event recording around every launch and clears the totals. */
+zgr_status zgr_profile_enable(zgr_ctx* ctx, int32_t on);
+/* Synchronises the stream and returns accumulated milliseconds and launch
+ * counts per zgr_kernel_class since zgr_profile_enable (HOST arrays of ZGR_K_COUNT). */
+zgr_status zgr_profile_read(zgr_ctx* ctx, double* ms, int64_t* launches);
+
+/* ---- test-only exports: materialise what the fused kernel never stores ---- */
+/* Philox4x32-10 of n counters ON THE DEVICE.  ctr: DEVICE u32 [n,4]; key: HOST u32 [2]; out: DEVICE u32 [n,4]. */
+zgr_status zgr_debug_philox(const uint32_t* ctr, const uint32_t* key, uint32_t* out, int64_t n, void* hip_stream);
+/* Gaussians of flat elements [first, first+n) of one stream: out DEVICE fp32 [n]. */
+zgr_status zgr_debug_gauss(uint64_t seed, uint64_t step, uint32_t tensor_id, int32_t stream, int32_t gauss_bits,
+                           int64_t first, int64_t n, float* out, void* hip_stream);
+/* Z of one tensor as fp32 [rows, cols] (DEVICE), computed by the same code path as the in-place pass. */
+zgr_status zgr_debug_fill_z(zgr_ctx* ctx, int32_t tensor_index, uint64_t step, float* Z);
+/* Per-example losses of the last forward (DEVICE -> HOST copy, synchronises):
+ * LM: [batch*(seq-1)] token losses; CLS: [batch]; LSQ: [batch].  n must match. */
+zgr_status zgr_debug_last_row_losses(zgr_ctx* ctx, float* out /* HOST */, int64_t n);
+/* Radius sqrt(-2 ln u) for all 2^23 (bits=32) or 2^16 (bits=16) values of the radius uniform, and
+ * (cos, sin)(2 pi v) for all 2^24 / 2^16 angle uniforms, as the fused kernel evaluates them. */
+zgr_status zgr_debug_radius_table(int32_t gauss_bits, float* out /* DEVICE */, void* hip_stream);
+zgr_status zgr_debug_cossin_table(int32_t gauss_bits, float* cos_out, float* sin_out /* DEVICE */, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZGR_H */

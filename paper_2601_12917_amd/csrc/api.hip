@@ -1,0 +1,609 @@
+// Host runtime and C ABI of the ZGR step: tensor table, Philox work lists,
+// workspace carving, launch sequencing on the caller's stream, HIP-event
+// profiling.  Follows Algorithm 1 (client block: zgr_step; edge-server block:
+// zgr_apply_update) with the estimator of Eq. (11).
+#include "../../include/zgr.h"
+#include "forward.h"
+#include "internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace zgr;
+
+namespace {
+
+std::string g_init_error;   // message of the last failed zgr_init / context-free call
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Layer {
+  int ln1_g = -1, ln1_b = -1, wq = -1, bq = -1, wk = -1, bk = -1, wv = -1, bv = -1, wo = -1, bo = -1;
+  int ln2_g = -1, ln2_b = -1, w1 = -1, b1 = -1, w2 = -1, b2 = -1;
+};
+
+struct Carve {                 // workspace layout (byte offsets)
+  size_t descs = 0, flat = 0, tiles = 0, dbg = 0;
+  size_t cap_flat = 0, cap_tiles = 0, cap_dbg = 0;   // capacities in items
+  size_t x = 0, h = 0, qkv = 0, ctx = 0, ff = 0, logits = 0, row_loss = 0, targets = 0, loss = 0;
+  size_t total = 0;
+};
+
+struct Prof {
+  bool on = false;
+  std::vector<hipEvent_t> ev;          // pairs
+  std::vector<int> cls;
+  size_t used = 0;                     // pairs in flight
+  double ms[ZGR_K_COUNT] = {};
+  int64_t n[ZGR_K_COUNT] = {};
+};
+
+}  // namespace
+
+struct zgr_ctx {
+  zgr_model model{};
+  zgr_config cfg{};
+  std::vector<zgr_tensor> t;
+  std::vector<TensorDesc> descs;
+  std::vector<WorkItem> flat, tiles;
+  bool lists_dirty = true;
+  int max_k = 0;
+  int dtype = 0;
+  std::vector<Layer> layers;
+  int tok_emb = -1, pos_emb = -1, lnf_g = -1, lnf_b = -1, cls_w = -1, cls_b = -1, lsq_w = -1;
+  unsigned char* ws = nullptr;
+  size_t ws_bytes = 0;
+  Carve cv;
+  int max_batch = 0, max_seq = 0;
+  hipStream_t stream = nullptr;
+  int n_cu = 256;
+  std::string err;
+  Prof prof;
+  int64_t last_rows = 0;       // rows of the last forward's row_loss
+  double host_loss[2] = {0, 0};
+};
+
+namespace {
+
+zgr_status fail(zgr_ctx* c, zgr_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_init_error = buf;
+  return st;
+}
+
+#define HIP_TRY(ctx, expr)                                                                      \
+  do {                                                                                          \
+    hipError_t e__ = (expr);                                                                    \
+    if (e__ != hipSuccess) return fail(ctx, ZGR_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+size_t elem_size(int dtype) { return dtype == ZGR_F32 ? 4 : 2; }
+
+// (a, b) of Z = a G + b U R for one tensor; isotropic tensors get (1, 0).
+void mix_coefficients(const zgr_config& cfg, const zgr_tensor& t, float* a, float* b) {
+  if (!t.U || t.k <= 0) { *a = 1.f; *b = 0.f; return; }
+  const double al = cfg.alpha, rows = (double)t.rows, cols = (double)t.cols, k = (double)t.k;
+  if (cfg.scale_mode == ZGR_SCALE_UNIT) { *a = (float)std::sqrt(al); *b = (float)std::sqrt((1.0 - al) * rows / k); }
+  else { *a = (float)std::sqrt(al / (rows * cols)); *b = (float)std::sqrt((1.0 - al) / (k * cols)); }
+}
+
+int group_size(int bits) { return bits == 32 ? 4 : 8; }
+
+size_t flat_items_of(int64_t numel, int P) {
+  const int64_t groups = (numel + P - 1) / P;
+  return (size_t)((groups + kFlatGroupsPerItem - 1) / kFlatGroupsPerItem);
+}
+int tile_rows_of(int64_t rows) { return rows >= 2 * kTileRowsPerIter ? 2 * kTileRowsPerIter : kTileRowsPerIter; }
+size_t tile_items_of(int64_t rows, int64_t cols, int P) {
+  const int64_t tr = tile_rows_of(rows), tc = 32 * P;
+  return (size_t)(((rows + tr - 1) / tr) * ((cols + tc - 1) / tc));
+}
+
+void append_items(const zgr_tensor& t, int index, bool guided, int P, std::vector<WorkItem>& flat, std::vector<WorkItem>& tiles) {
+  if (!guided) {
+    const int64_t groups = (t.rows * t.cols + P - 1) / P;
+    for (int64_t g0 = 0; g0 < groups; g0 += kFlatGroupsPerItem)
+      flat.push_back({index, (int32_t)std::min<int64_t>(kFlatGroupsPerItem, groups - g0), g0});
+  } else {
+    const int64_t tr = tile_rows_of(t.rows), tc = 32 * P;
+    for (int64_t r0 = 0; r0 < t.rows; r0 += tr)
+      for (int64_t c0 = 0; c0 < t.cols; c0 += tc)
+        tiles.push_back({index, (int32_t)std::min<int64_t>(tr, t.rows - r0), (r0 << 32) | c0});
+  }
+}
+
+bool is_guided(const zgr_tensor& t) { return t.U != nullptr && t.k > 0; }
+
+// Host work lists + descriptors from the tensor table.
+void build_lists(zgr_ctx* c) {
+  const int P = group_size(c->cfg.gauss_bits);
+  c->flat.clear(); c->tiles.clear(); c->descs.resize(c->t.size());
+  c->max_k = 0;
+  for (size_t i = 0; i < c->t.size(); ++i) {
+    const zgr_tensor& t = c->t[i];
+    TensorDesc& d = c->descs[i];
+    d.theta = t.theta; d.U = is_guided(t) ? t.U : nullptr; d.rows = t.rows; d.cols = t.cols; d.id = t.tensor_id;
+    d.k = is_guided(t) ? t.k : 0; d.ldu = t.ldu; d.dtype = t.dtype;
+    mix_coefficients(c->cfg, t, &d.a, &d.b);
+    append_items(t, (int)i, is_guided(t), P, c->flat, c->tiles);
+    if (is_guided(t) && t.k > c->max_k) c->max_k = t.k;
+  }
+  c->lists_dirty = true;
+}
+
+zgr_status check_tensor(zgr_ctx* c, const zgr_tensor& t, int i, int bits, bool need_ptrs) {
+  if (need_ptrs && !t.theta) return fail(c, ZGR_ERR_NULL, "tensor %d: theta is NULL", i);
+  if (t.rows < 1 || t.cols < 1 || t.rows > (int64_t)1 << 31 || t.cols > (int64_t)1 << 31) return fail(c, ZGR_ERR_SHAPE, "tensor %d: bad shape %lld x %lld", i, (long long)t.rows, (long long)t.cols);
+  if (t.dtype != ZGR_F32 && t.dtype != ZGR_BF16) return fail(c, ZGR_ERR_DTYPE, "tensor %d: unknown dtype %d", i, t.dtype);
+  if (t.tensor_id >= 0x80000000u) return fail(c, ZGR_ERR_CONFIG, "tensor %d: tensor_id must be < 2^31", i);
+  if (need_ptrs && ((uintptr_t)t.theta & 15)) return fail(c, ZGR_ERR_SHAPE, "tensor %d: theta must be 16-byte aligned", i);
+  if (t.k < 0) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k < 0", i);
+  if ((t.U || !need_ptrs) && t.k > 0) {
+    if (t.k > kMaxK) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds %d", i, t.k, kMaxK);
+    if (t.k > t.rows) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds rows = %lld", i, t.k, (long long)t.rows);
+    if (t.ldu < t.k) return fail(c, ZGR_ERR_SHAPE, "tensor %d: ldu = %d < k = %d", i, t.ldu, t.k);
+    if (t.cols % group_size(bits)) return fail(c, ZGR_ERR_SHAPE, "tensor %d: a guided tensor needs cols %% %d == 0", i, group_size(bits));
+  }
+  return ZGR_OK;
+}
+
+zgr_status check_config(zgr_ctx* c, const zgr_config& cfg) {
+  if (!(cfg.eps > 0.f) || !std::isfinite(cfg.eps)) return fail(c, ZGR_ERR_CONFIG, "eps must be positive and finite");
+  if (!(cfg.alpha >= 0.f && cfg.alpha <= 1.f)) return fail(c, ZGR_ERR_CONFIG, "alpha must lie in [0, 1]");
+  if (cfg.scale_mode != ZGR_SCALE_UNIT && cfg.scale_mode != ZGR_SCALE_PAPER) return fail(c, ZGR_ERR_CONFIG, "unknown scale_mode");
+  if (cfg.gauss_bits != 32 && cfg.gauss_bits != 16) return fail(c, ZGR_ERR_CONFIG, "gauss_bits must be 32 or 16");
+  return ZGR_OK;
+}
+
+bool is_transformer(int arch) { return arch == ZGR_ARCH_DECODER_LM || arch == ZGR_ARCH_ENCODER_CLS; }
+
+zgr_status check_model(zgr_ctx* c, const zgr_model& m, int dtype) {
+  if (m.arch != ZGR_ARCH_NONE && m.arch != ZGR_ARCH_LINEAR_LSQ && !is_transformer(m.arch)) return fail(c, ZGR_ERR_CONFIG, "unknown arch %d", m.arch);
+  if (m.arch == ZGR_ARCH_LINEAR_LSQ && dtype != ZGR_F32) return fail(c, ZGR_ERR_DTYPE, "the least-squares model is fp32 only");
+  if (!is_transformer(m.arch)) return ZGR_OK;
+  if (m.n_layer < 1 || m.d_model < 1 || m.n_head < 1 || m.d_ff < 1 || m.vocab < 2 || m.max_pos < 1) return fail(c, ZGR_ERR_SHAPE, "bad transformer dimensions");
+  if (m.d_model % m.n_head || !attention_head_dim_supported(m.d_model / m.n_head)) return fail(c, ZGR_ERR_SHAPE, "head size must be 8, 16, 32 or 64");
+  if (dtype == ZGR_BF16 && (m.d_model % 64 || m.d_ff % 64)) return fail(c, ZGR_ERR_SHAPE, "bf16 storage needs d_model and d_ff to be multiples of 64");
+  if (m.arch == ZGR_ARCH_ENCODER_CLS && m.n_class < 2) return fail(c, ZGR_ERR_SHAPE, "n_class must be >= 2");
+  if (!(m.ln_eps > 0.f)) return fail(c, ZGR_ERR_CONFIG, "ln_eps must be positive");
+  return ZGR_OK;
+}
+
+Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int max_seq, int bits) {
+  Carve cv;
+  const int P = group_size(bits);
+  size_t nf = 0, nt = 0, nd = 0;
+  int dtype = n_t > 0 ? t[0].dtype : 0;
+  for (int i = 0; i < n_t; ++i) {
+    const size_t f = flat_items_of(t[i].rows * t[i].cols, P);
+    const size_t tl = (t[i].cols % P == 0) ? tile_items_of(t[i].rows, t[i].cols, P) : 0;
+    nf += f; nt += tl;
+    nd = std::max(nd, std::max(f, tl));
+  }
+  cv.cap_flat = nf; cv.cap_tiles = nt; cv.cap_dbg = nd;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+  cv.descs = take(sizeof(TensorDesc) * (size_t)std::max(n_t, 1));
+  cv.flat = take(sizeof(WorkItem) * std::max<size_t>(nf, 1));
+  cv.tiles = take(sizeof(WorkItem) * std::max<size_t>(nt, 1));
+  cv.dbg = take(sizeof(WorkItem) * std::max<size_t>(nd, 1));
+  cv.loss = take(sizeof(double) * 2);
+  const size_t es = elem_size(dtype);
+  if (is_transformer(m.arch)) {
+    const size_t M = (size_t)max_batch * max_seq, d = m.d_model;
+    cv.x = take(M * d * 4);
+    cv.h = take(M * d * es);
+    cv.qkv = take(M * 3 * d * es);
+    cv.ctx = take(M * d * es);
+    cv.ff = take(M * (size_t)m.d_ff * es);
+    cv.logits = take(m.arch == ZGR_ARCH_DECODER_LM ? M * (size_t)m.vocab * 4 : (size_t)max_batch * m.n_class * 4);
+    cv.row_loss = take(M * 4);
+    cv.targets = take(M * 4);
+  } else if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
+    size_t out = 0;
+    for (int i = 0; i < n_t; ++i) if (t[i].role == ZGR_ROLE_LSQ_W) out = (size_t)t[i].rows;
+    cv.logits = take((size_t)max_batch * out * 4);
+    cv.row_loss = take((size_t)max_batch * 4);
+  }
+  cv.total = off;
+  return cv;
+}
+
+// ---------------------------------------------------------------- profiling
+void prof_harvest(zgr_ctx* c) {
+  Prof& p = c->prof;
+  for (size_t i = 0; i < p.used; ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]) == hipSuccess) { p.ms[p.cls[i]] += ms; p.n[p.cls[i]] += 1; }
+  }
+  p.used = 0;
+}
+
+struct ProfScope {
+  zgr_ctx* c; bool live = false; size_t slot = 0;
+  ProfScope(zgr_ctx* ctx, int cls) : c(ctx) {
+    Prof& p = c->prof;
+    if (!p.on) return;
+    if ((p.used + 1) * 2 > p.ev.size()) {
+      if (p.ev.size() >= 16384) { (void)hipStreamSynchronize(c->stream); prof_harvest(c); }
+      else {
+        for (int i = 0; i < 512; ++i) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) return; p.ev.push_back(e); }
+        p.cls.resize(p.ev.size() / 2);
+      }
+    }
+    slot = p.used++;
+    p.cls[slot] = cls;
+    live = hipEventRecord(p.ev[2 * slot], c->stream) == hipSuccess;
+  }
+  ~ProfScope() { if (live) (void)hipEventRecord(c->prof.ev[2 * slot + 1], c->stream); }
+};
+
+// ---------------------------------------------------------------- perturbation pass
+zgr_status upload_lists(zgr_ctx* c) {
+  if (!c->lists_dirty) return ZGR_OK;
+  HIP_TRY(c, hipMemcpyAsync(c->ws + c->cv.descs, c->descs.data(), sizeof(TensorDesc) * c->descs.size(), hipMemcpyHostToDevice, c->stream));
+  if (!c->flat.empty()) HIP_TRY(c, hipMemcpyAsync(c->ws + c->cv.flat, c->flat.data(), sizeof(WorkItem) * c->flat.size(), hipMemcpyHostToDevice, c->stream));
+  if (!c->tiles.empty()) HIP_TRY(c, hipMemcpyAsync(c->ws + c->cv.tiles, c->tiles.data(), sizeof(WorkItem) * c->tiles.size(), hipMemcpyHostToDevice, c->stream));
+  // the host vectors must outlive the copies
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->lists_dirty = false;
+  return ZGR_OK;
+}
+
+PerturbArgs perturb_args(zgr_ctx* c, uint64_t step) {
+  PerturbArgs a{};
+  a.descs = reinterpret_cast<const TensorDesc*>(c->ws + c->cv.descs);
+  a.flat = reinterpret_cast<const WorkItem*>(c->ws + c->cv.flat);
+  a.tiles = reinterpret_cast<const WorkItem*>(c->ws + c->cv.tiles);
+  a.n_flat = (int32_t)c->flat.size(); a.n_tiles = (int32_t)c->tiles.size();
+  a.k0 = (uint32_t)c->cfg.seed; a.k1 = (uint32_t)(c->cfg.seed >> 32);
+  a.step = (uint32_t)step; a.bits = c->cfg.gauss_bits; a.dtype = c->dtype; a.max_k = c->max_k;
+  return a;
+}
+
+zgr_status perturb_pass(zgr_ctx* c, uint64_t step, float coef) {
+  if (step >> 32) return fail(c, ZGR_ERR_CONFIG, "step must be < 2^32");
+  zgr_status st = upload_lists(c);
+  if (st != ZGR_OK) return st;
+  const PerturbArgs a = perturb_args(c, step);
+  { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(a, coef, nullptr, c->stream, c->n_cu)); }
+  { ProfScope ps(c, ZGR_K_PERTURB_FLAT); HIP_TRY(c, launch_perturb_flat(a, coef, nullptr, c->stream, c->n_cu)); }
+  return ZGR_OK;
+}
+
+// ---------------------------------------------------------------- forward
+const void* T(zgr_ctx* c, int idx) { return c->t[idx].theta; }
+
+zgr_status forward_loss(zgr_ctx* c, const zgr_batch* b, int slot) {
+  const zgr_model& m = c->model;
+  hipStream_t s = c->stream;
+  unsigned char* ws = c->ws;
+  double* loss_dev = reinterpret_cast<double*>(ws + c->cv.loss) + slot;
+  float* row_loss = reinterpret_cast<float*>(ws + c->cv.row_loss);
+  float* logits = reinterpret_cast<float*>(ws + c->cv.logits);
+  const int dt = c->dtype;
+  if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
+    const zgr_tensor& w = c->t[c->lsq_w];
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(0, b->x, w.theta, nullptr, logits, EPI_F32, b->batch, (int)w.rows, (int)w.cols, s)); }
+    { ProfScope ps(c, ZGR_K_LOSS);
+      HIP_TRY(c, launch_lsq_rows(logits, reinterpret_cast<const float*>(b->y), row_loss, b->batch, (int)w.rows, s));
+      HIP_TRY(c, launch_mean_f64(row_loss, b->batch, 1.0 / b->batch, loss_dev, s)); }
+    c->last_rows = b->batch;
+    return ZGR_OK;
+  }
+  const int M = b->batch * b->seq, d = m.d_model, ff = m.d_ff;
+  float* x = reinterpret_cast<float*>(ws + c->cv.x);
+  void* h = ws + c->cv.h; void* qkv = ws + c->cv.qkv; void* ctx = ws + c->cv.ctx; void* ffb = ws + c->cv.ff;
+  const int32_t* tok = reinterpret_cast<const int32_t*>(b->x);
+  const bool lm = m.arch == ZGR_ARCH_DECODER_LM;
+  { ProfScope ps(c, ZGR_K_EMBED); HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), x, M, b->seq, d, m.vocab, s)); }
+  for (int l = 0; l < m.n_layer; ++l) {
+    const Layer& L = c->layers[l];
+    { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, L.ln1_g), T(c, L.ln1_b), h, M, d, m.ln_eps, s)); }
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, L.wq), T(c, L.bq), qkv, EPI_STORE, M, 3 * d, d, s)); }
+    { ProfScope ps(c, ZGR_K_ATTN); HIP_TRY(c, launch_attention(dt, qkv, ctx, lm ? nullptr : b->lengths, b->batch, b->seq, d, m.n_head, lm ? 1 : 0, s)); }
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, ctx, T(c, L.wo), T(c, L.bo), x, EPI_RESID, M, d, d, s)); }
+    { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, L.ln2_g), T(c, L.ln2_b), h, M, d, m.ln_eps, s)); }
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, L.w1), T(c, L.b1), ffb, EPI_GELU, M, ff, d, s)); }
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, ffb, T(c, L.w2), T(c, L.b2), x, EPI_RESID, M, d, ff, s)); }
+  }
+  { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, c->lnf_g), T(c, c->lnf_b), h, M, d, m.ln_eps, s)); }
+  if (lm) {
+    int32_t* tgt = reinterpret_cast<int32_t*>(ws + c->cv.targets);
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, c->tok_emb), nullptr, logits, EPI_F32, M, m.vocab, d, s)); }
+    { ProfScope ps(c, ZGR_K_LOSS);
+      HIP_TRY(c, launch_lm_targets(tok, tgt, M, b->seq, s));
+      HIP_TRY(c, launch_ce_rows(logits, tgt, row_loss, M, m.vocab, s));
+      HIP_TRY(c, launch_mean_f64(row_loss, M, 1.0 / ((double)b->batch * (b->seq - 1)), loss_dev, s)); }
+    c->last_rows = M;
+  } else {
+    { ProfScope ps(c, ZGR_K_LOSS);
+      HIP_TRY(c, launch_cls_head(dt, h, T(c, c->cls_w), T(c, c->cls_b), logits, b->batch, b->seq, d, m.n_class, s));
+      HIP_TRY(c, launch_ce_rows(logits, reinterpret_cast<const int32_t*>(b->y), row_loss, b->batch, m.n_class, s));
+      HIP_TRY(c, launch_mean_f64(row_loss, b->batch, 1.0 / b->batch, loss_dev, s)); }
+    c->last_rows = b->batch;
+  }
+  return ZGR_OK;
+}
+
+zgr_status check_batch(zgr_ctx* c, const zgr_batch* b) {
+  if (!b || !b->x) return fail(c, ZGR_ERR_NULL, "batch or batch->x is NULL");
+  const zgr_model& m = c->model;
+  if (m.arch == ZGR_ARCH_NONE) return fail(c, ZGR_ERR_STATE, "this context has no model: it can only perturb and update");
+  if (b->batch < 1 || b->batch > c->max_batch) return fail(c, ZGR_ERR_SHAPE, "batch = %d outside [1, %d]", b->batch, c->max_batch);
+  if (m.arch == ZGR_ARCH_LINEAR_LSQ) { if (!b->y) return fail(c, ZGR_ERR_NULL, "batch->y is NULL"); return ZGR_OK; }
+  if (b->seq < 2 || b->seq > c->max_seq || b->seq > m.max_pos) return fail(c, ZGR_ERR_SHAPE, "seq = %d outside [2, min(%d, %d)]", b->seq, c->max_seq, m.max_pos);
+  if (m.arch == ZGR_ARCH_ENCODER_CLS && (!b->y || !b->lengths)) return fail(c, ZGR_ERR_NULL, "the classifier needs labels and lengths");
+  return ZGR_OK;
+}
+
+// Map roles to tensors and check shapes against the model.
+zgr_status bind_model(zgr_ctx* c) {
+  const zgr_model& m = c->model;
+  if (m.arch == ZGR_ARCH_NONE) return ZGR_OK;
+  auto shape_is = [&](int idx, int64_t r, int64_t cl) { return c->t[idx].rows == r && c->t[idx].cols == cl; };
+  if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
+    for (size_t i = 0; i < c->t.size(); ++i) if (c->t[i].role == ZGR_ROLE_LSQ_W) { if (c->lsq_w >= 0) return fail(nullptr, ZGR_ERR_SHAPE, "more than one LSQ_W tensor"); c->lsq_w = (int)i; }
+    if (c->lsq_w < 0) return fail(nullptr, ZGR_ERR_SHAPE, "the least-squares model needs one ZGR_ROLE_LSQ_W tensor");
+    return ZGR_OK;
+  }
+  c->layers.assign(m.n_layer, Layer());
+  const int d = m.d_model, ff = m.d_ff;
+  for (size_t i = 0; i < c->t.size(); ++i) {
+    const zgr_tensor& t = c->t[i];
+    int* slot = nullptr; int64_t r = 1, cl = d;
+    const bool in_layer = t.role >= ZGR_ROLE_LN1_G && t.role <= ZGR_ROLE_B2;
+    if (in_layer && (t.layer < 0 || t.layer >= m.n_layer)) return fail(nullptr, ZGR_ERR_SHAPE, "tensor %zu: layer %d out of range", i, t.layer);
+    Layer* L = in_layer ? &c->layers[t.layer] : nullptr;
+    switch (t.role) {
+      case ZGR_ROLE_TOK_EMB: slot = &c->tok_emb; r = m.vocab; break;
+      case ZGR_ROLE_POS_EMB: slot = &c->pos_emb; r = m.max_pos; break;
+      case ZGR_ROLE_LN1_G: slot = &L->ln1_g; break;  case ZGR_ROLE_LN1_B: slot = &L->ln1_b; break;
+      case ZGR_ROLE_WQ: slot = &L->wq; r = d; break; case ZGR_ROLE_BQ: slot = &L->bq; break;
+      case ZGR_ROLE_WK: slot = &L->wk; r = d; break; case ZGR_ROLE_BK: slot = &L->bk; break;
+      case ZGR_ROLE_WV: slot = &L->wv; r = d; break; case ZGR_ROLE_BV: slot = &L->bv; break;
+      case ZGR_ROLE_WO: slot = &L->wo; r = d; break; case ZGR_ROLE_BO: slot = &L->bo; break;
+      case ZGR_ROLE_LN2_G: slot = &L->ln2_g; break;  case ZGR_ROLE_LN2_B: slot = &L->ln2_b; break;
+      case ZGR_ROLE_W1: slot = &L->w1; r = ff; break; case ZGR_ROLE_B1: slot = &L->b1; cl = ff; break;
+      case ZGR_ROLE_W2: slot = &L->w2; r = d; cl = ff; break; case ZGR_ROLE_B2: slot = &L->b2; break;
+      case ZGR_ROLE_LNF_G: slot = &c->lnf_g; break;  case ZGR_ROLE_LNF_B: slot = &c->lnf_b; break;
+      case ZGR_ROLE_CLS_W: slot = &c->cls_w; r = m.n_class; break;
+      case ZGR_ROLE_CLS_B: slot = &c->cls_b; cl = m.n_class; break;
+      default: return fail(nullptr, ZGR_ERR_SHAPE, "tensor %zu: role %d does not belong to a transformer", i, t.role);
+    }
+    if (*slot >= 0) return fail(nullptr, ZGR_ERR_SHAPE, "tensor %zu: role %d of layer %d given twice", i, t.role, t.layer);
+    if (!shape_is((int)i, r, cl)) return fail(nullptr, ZGR_ERR_SHAPE, "tensor %zu (role %d): shape %lld x %lld, expected %lld x %lld", i, t.role, (long long)t.rows, (long long)t.cols, (long long)r, (long long)cl);
+    *slot = (int)i;
+  }
+  if (c->tok_emb < 0 || c->pos_emb < 0 || c->lnf_g < 0 || c->lnf_b < 0) return fail(nullptr, ZGR_ERR_SHAPE, "embeddings or final LayerNorm missing");
+  if (m.arch == ZGR_ARCH_ENCODER_CLS && (c->cls_w < 0 || c->cls_b < 0)) return fail(nullptr, ZGR_ERR_SHAPE, "classification head missing");
+  const size_t es = elem_size(c->dtype);
+  for (int l = 0; l < m.n_layer; ++l) {
+    const Layer& L = c->layers[l];
+    const int all[] = {L.ln1_g, L.ln1_b, L.wq, L.bq, L.wk, L.bk, L.wv, L.bv, L.wo, L.bo, L.ln2_g, L.ln2_b, L.w1, L.b1, L.w2, L.b2};
+    for (int v : all) if (v < 0) return fail(nullptr, ZGR_ERR_SHAPE, "layer %d: a tensor is missing", l);
+    const char* q = (const char*)c->t[L.wq].theta; const char* k = (const char*)c->t[L.wk].theta; const char* v = (const char*)c->t[L.wv].theta;
+    if (k != q + (size_t)d * d * es || v != k + (size_t)d * d * es) return fail(nullptr, ZGR_ERR_SHAPE, "layer %d: Wq, Wk, Wv must be adjacent in memory", l);
+    const char* bq = (const char*)c->t[L.bq].theta; const char* bk = (const char*)c->t[L.bk].theta; const char* bv = (const char*)c->t[L.bv].theta;
+    if (bk != bq + (size_t)d * es || bv != bk + (size_t)d * es) return fail(nullptr, ZGR_ERR_SHAPE, "layer %d: bq, bk, bv must be adjacent in memory", l);
+  }
+  return ZGR_OK;
+}
+
+}  // namespace
+
+// =============================================================================== C ABI
+extern "C" {
+
+size_t zgr_workspace_bytes(const zgr_model* model, const zgr_tensor* tensors, int32_t n_t, int32_t max_batch, int32_t max_seq) {
+  if (!model || (n_t > 0 && !tensors) || n_t < 0 || max_batch < 0 || max_seq < 0) return 0;
+  for (int i = 0; i < n_t; ++i) if (tensors[i].rows < 1 || tensors[i].cols < 1) return 0;
+  // sized for the finer of the two Philox groupings so that either gauss_bits fits
+  const size_t a = carve(*model, tensors, n_t, max_batch, max_seq, 32).total;
+  const size_t b = carve(*model, tensors, n_t, max_batch, max_seq, 16).total;
+  return std::max(a, b);
+}
+
+zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* tensors, int32_t n_t, const zgr_config* config,
+                    void* workspace, size_t workspace_bytes, int32_t max_batch, int32_t max_seq, void* hip_stream) {
+  if (!out) return fail(nullptr, ZGR_ERR_NULL, "out is NULL");
+  *out = nullptr;
+  if (!model || !tensors || !config) return fail(nullptr, ZGR_ERR_NULL, "model, tensors or config is NULL");
+  if (n_t < 1) return fail(nullptr, ZGR_ERR_SHAPE, "n_t must be >= 1");
+  zgr_status st = check_config(nullptr, *config);
+  if (st != ZGR_OK) return st;
+  for (int i = 0; i < n_t; ++i) {
+    st = check_tensor(nullptr, tensors[i], i, config->gauss_bits, true);
+    if (st != ZGR_OK) return st;
+    if (tensors[i].dtype != tensors[0].dtype) return fail(nullptr, ZGR_ERR_DTYPE, "tensor %d: all tensors must share one dtype", i);
+    for (int j = 0; j < i; ++j) if (tensors[j].tensor_id == tensors[i].tensor_id) return fail(nullptr, ZGR_ERR_CONFIG, "tensors %d and %d share tensor_id %u", j, i, tensors[i].tensor_id);
+  }
+  st = check_model(nullptr, *model, tensors[0].dtype);
+  if (st != ZGR_OK) return st;
+  if (model->arch != ZGR_ARCH_NONE && (max_batch < 1 || (is_transformer(model->arch) && max_seq < 2))) return fail(nullptr, ZGR_ERR_SHAPE, "max_batch / max_seq too small");
+  if (!workspace) return fail(nullptr, ZGR_ERR_NULL, "workspace is NULL");
+  if ((uintptr_t)workspace & 255) return fail(nullptr, ZGR_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  zgr_ctx* c = new (std::nothrow) zgr_ctx();
+  if (!c) return fail(nullptr, ZGR_ERR_DEVICE, "out of host memory");
+  c->model = *model; c->cfg = *config; c->t.assign(tensors, tensors + n_t); c->dtype = tensors[0].dtype;
+  c->max_batch = max_batch; c->max_seq = max_seq; c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->cv = carve(*model, tensors, n_t, max_batch, max_seq, config->gauss_bits);
+  if (workspace_bytes < c->cv.total) {
+    st = fail(nullptr, ZGR_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, c->cv.total);
+    delete c; return st;
+  }
+  c->ws = reinterpret_cast<unsigned char*>(workspace); c->ws_bytes = workspace_bytes;
+  st = bind_model(c);
+  if (st != ZGR_OK) { delete c; return st; }
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) {
+    delete c; return fail(nullptr, ZGR_ERR_DEVICE, "no usable HIP device");
+  }
+  c->n_cu = n_cu;
+  const RadiusEntry* tab = nullptr;
+  if (ensure_radius_table(&tab) != hipSuccess) { delete c; return fail(nullptr, ZGR_ERR_DEVICE, "could not set up the device tables"); }
+  build_lists(c);
+  *out = c;
+  return ZGR_OK;
+}
+
+zgr_status zgr_set_basis(zgr_ctx* c, int32_t idx, const float* U, int32_t k, int32_t ldu) {
+  if (!c) return ZGR_ERR_NULL;
+  if (idx < 0 || idx >= (int)c->t.size()) return fail(c, ZGR_ERR_SHAPE, "tensor_index %d out of range", idx);
+  zgr_tensor t = c->t[idx];
+  t.U = (U && k > 0) ? U : nullptr; t.k = (U && k > 0) ? k : 0; t.ldu = ldu;
+  zgr_status st = check_tensor(c, t, idx, c->cfg.gauss_bits, true);
+  if (st != ZGR_OK) return st;
+  c->t[idx] = t;
+  build_lists(c);
+  if (c->flat.size() > c->cv.cap_flat || c->tiles.size() > c->cv.cap_tiles) return fail(c, ZGR_ERR_WORKSPACE, "work lists outgrew the workspace");
+  return ZGR_OK;
+}
+
+zgr_status zgr_perturb(zgr_ctx* c, uint64_t step, float coef) {
+  if (!c) return ZGR_ERR_NULL;
+  return perturb_pass(c, step, coef);
+}
+
+zgr_status zgr_loss(zgr_ctx* c, const zgr_batch* b, double* loss_out) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!loss_out) return fail(c, ZGR_ERR_NULL, "loss_out is NULL");
+  zgr_status st = check_batch(c, b);
+  if (st != ZGR_OK) return st;
+  st = forward_loss(c, b, 0);
+  if (st != ZGR_OK) return st;
+  HIP_TRY(c, hipMemcpyAsync(c->host_loss, c->ws + c->cv.loss, sizeof(double), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (c->prof.on) prof_harvest(c);
+  *loss_out = c->host_loss[0];
+  return std::isfinite(*loss_out) ? ZGR_OK : fail(c, ZGR_ERR_NONFINITE, "loss is not finite");
+}
+
+zgr_status zgr_step(zgr_ctx* c, uint64_t step, const zgr_batch* b, zgr_result* out) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!out) return fail(c, ZGR_ERR_NULL, "out is NULL");
+  zgr_status st = check_batch(c, b);
+  if (st != ZGR_OK) return st;
+  const float eps = c->cfg.eps;
+  if ((st = perturb_pass(c, step, eps)) != ZGR_OK) return st;                 // W + eps Z
+  st = forward_loss(c, b, 0);
+  zgr_status st2 = perturb_pass(c, step, -2.0f * eps);                        // W - eps Z
+  if (st == ZGR_OK && st2 == ZGR_OK) st = forward_loss(c, b, 1);
+  zgr_status st3 = perturb_pass(c, step, eps);                                // restore
+  if (st == ZGR_OK) st = st2 != ZGR_OK ? st2 : st3;
+  if (st != ZGR_OK) return st;
+  HIP_TRY(c, hipMemcpyAsync(c->host_loss, c->ws + c->cv.loss, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (c->prof.on) prof_harvest(c);
+  out->loss_plus = c->host_loss[0];
+  out->loss_minus = c->host_loss[1];
+  out->g = (float)((out->loss_plus - out->loss_minus) / (2.0 * (double)eps));
+  if (!std::isfinite(out->loss_plus) || !std::isfinite(out->loss_minus)) return fail(c, ZGR_ERR_NONFINITE, "a loss is not finite (L+ = %g, L- = %g)", out->loss_plus, out->loss_minus);
+  return ZGR_OK;
+}
+
+zgr_status zgr_apply_update(zgr_ctx* c, uint64_t step, float g, float lr) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!std::isfinite(g) || !std::isfinite(lr)) return fail(c, ZGR_ERR_NONFINITE, "g or lr is not finite");
+  const float coef = -(lr * g);
+  return perturb_pass(c, step, coef);
+}
+
+void zgr_destroy(zgr_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+const char* zgr_last_error(const zgr_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+zgr_status zgr_profile_enable(zgr_ctx* c, int32_t on) {
+  if (!c) return ZGR_ERR_NULL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->prof.used = 0;
+  for (int i = 0; i < ZGR_K_COUNT; ++i) { c->prof.ms[i] = 0; c->prof.n[i] = 0; }
+  c->prof.on = on != 0;
+  return ZGR_OK;
+}
+
+zgr_status zgr_profile_read(zgr_ctx* c, double* ms, int64_t* launches) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!ms || !launches) return fail(c, ZGR_ERR_NULL, "ms or launches is NULL");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  prof_harvest(c);
+  for (int i = 0; i < ZGR_K_COUNT; ++i) { ms[i] = c->prof.ms[i]; launches[i] = c->prof.n[i]; }
+  return ZGR_OK;
+}
+
+// ---------------------------------------------------------------- test-only exports
+zgr_status zgr_debug_philox(const uint32_t* ctr, const uint32_t* key, uint32_t* out, int64_t n, void* hip_stream) {
+  if (n < 0) return fail(nullptr, ZGR_ERR_SHAPE, "n < 0");
+  if (n == 0) return ZGR_OK;
+  if (!ctr || !key || !out) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  HIP_TRY(nullptr, launch_debug_philox(ctr, key[0], key[1], out, n, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_gauss(uint64_t seed, uint64_t step, uint32_t tensor_id, int32_t stream, int32_t gauss_bits, int64_t first, int64_t n,
+                           float* out, void* hip_stream) {
+  if (!out) return fail(nullptr, ZGR_ERR_NULL, "out is NULL");
+  if ((gauss_bits != 32 && gauss_bits != 16) || first < 0 || n < 0 || tensor_id >= 0x80000000u || (stream != 0 && stream != 1) || (step >> 32))
+    return fail(nullptr, ZGR_ERR_CONFIG, "bad argument");
+  HIP_TRY(nullptr, launch_debug_gauss((uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, tensor_id | ((uint32_t)stream << 31), gauss_bits, first, n, out,
+                                      reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_fill_z(zgr_ctx* c, int32_t idx, uint64_t step, float* Z) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!Z) return fail(c, ZGR_ERR_NULL, "Z is NULL");
+  if (idx < 0 || idx >= (int)c->t.size()) return fail(c, ZGR_ERR_SHAPE, "tensor_index %d out of range", idx);
+  if (step >> 32) return fail(c, ZGR_ERR_CONFIG, "step must be < 2^32");
+  zgr_status st = upload_lists(c);
+  if (st != ZGR_OK) return st;
+  std::vector<WorkItem> fl, tl;
+  append_items(c->t[idx], idx, is_guided(c->t[idx]), group_size(c->cfg.gauss_bits), fl, tl);
+  std::vector<WorkItem>& items = fl.empty() ? tl : fl;
+  if (items.size() > c->cv.cap_dbg) return fail(c, ZGR_ERR_WORKSPACE, "debug list outgrew the workspace");
+  HIP_TRY(c, hipMemcpyAsync(c->ws + c->cv.dbg, items.data(), sizeof(WorkItem) * items.size(), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  PerturbArgs a = perturb_args(c, step);
+  const WorkItem* dbg = reinterpret_cast<const WorkItem*>(c->ws + c->cv.dbg);
+  if (!fl.empty()) { a.flat = dbg; a.n_flat = (int32_t)fl.size(); a.n_tiles = 0; HIP_TRY(c, launch_perturb_flat(a, 0.f, Z, c->stream, c->n_cu)); }
+  else { a.tiles = dbg; a.n_tiles = (int32_t)tl.size(); a.n_flat = 0; a.max_k = c->t[idx].k; HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu)); }
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_last_row_losses(zgr_ctx* c, float* out, int64_t n) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!out) return fail(c, ZGR_ERR_NULL, "out is NULL");
+  if (c->model.arch == ZGR_ARCH_NONE || n != c->last_rows) return fail(c, ZGR_ERR_SHAPE, "n = %lld, the last forward produced %lld rows", (long long)n, (long long)c->last_rows);
+  HIP_TRY(c, hipMemcpyAsync(out, c->ws + c->cv.row_loss, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_radius_table(int32_t gauss_bits, float* out, void* hip_stream) {
+  if (!out) return fail(nullptr, ZGR_ERR_NULL, "out is NULL");
+  if (gauss_bits != 32 && gauss_bits != 16) return fail(nullptr, ZGR_ERR_CONFIG, "gauss_bits must be 32 or 16");
+  HIP_TRY(nullptr, launch_debug_radius_table(gauss_bits, out, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_cossin_table(int32_t gauss_bits, float* cos_out, float* sin_out, void* hip_stream) {
+  if (!cos_out || !sin_out) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  if (gauss_bits != 32 && gauss_bits != 16) return fail(nullptr, ZGR_ERR_CONFIG, "gauss_bits must be 32 or 16");
+  HIP_TRY(nullptr, launch_debug_cossin_table(gauss_bits, cos_out, sin_out, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+}  // extern "C"

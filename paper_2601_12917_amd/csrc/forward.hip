@@ -1,0 +1,402 @@
+// Forward pass L(W; x) for the two loss evaluations of the ZGR step (Sec. 4.2,
+// Eq. (11); Sec. 4.1 workflow step 6): pre-LayerNorm transformer blocks with
+// softmax attention and erf-GELU feed-forward, next-token cross-entropy through
+// the tied embedding (decoder) or a classification head on the first token
+// (encoder), and the least-squares loss of a single linear layer.
+//
+// Storage type T of weights and GEMM inputs is fp32 or bf16; accumulation, the
+// residual stream, LayerNorm, softmax and the loss are fp32, the final mean fp64.
+#include "forward.h"
+
+namespace zgr {
+
+namespace {
+
+struct bf16_t { uint16_t bits; };
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
+__device__ __forceinline__ void from_f32(float x, float& o) { o = x; }
+__device__ __forceinline__ void from_f32(float x, bf16_t& o) {
+  const uint32_t b = __float_as_uint(x);
+  o.bits = (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// block of 256 threads: reduce across the 4 waves through LDS
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+// ------------------------------------------------------------------ embedding
+template <typename T>
+__global__ void __launch_bounds__(256) embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, const T* __restrict__ Pe,
+                                                    float* __restrict__ x, int M, int seq, int d, int vocab) {
+  const int m = blockIdx.x;
+  int t = tok[m];
+  t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+  const T* e = E + (size_t)t * d;
+  const T* p = Pe + (size_t)(m % seq) * d;
+  for (int i = threadIdx.x; i < d; i += 256) x[(size_t)m * d + i] = to_f32(e[i]) + to_f32(p[i]);
+}
+
+// ------------------------------------------------------------------ LayerNorm (one block per row)
+template <typename T>
+__global__ void __launch_bounds__(256) layernorm_kernel(const float* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
+                                                        T* __restrict__ out, int d, float eps) {
+  __shared__ float red[4];
+  const float* row = x + (size_t)blockIdx.x * d;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) s += row[i];
+  const float mu = block_sum(s, red) / d;
+  float v = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) { const float t = row[i] - mu; v += t * t; }
+  const float rstd = 1.0f / sqrtf(block_sum(v, red) / d + eps);
+  T* o = out + (size_t)blockIdx.x * d;
+  for (int i = threadIdx.x; i < d; i += 256) from_f32((row[i] - mu) * rstd * to_f32(g[i]) + to_f32(b[i]), o[i]);
+}
+
+// ------------------------------------------------------------------ GEMM  C = A W^T (+bias) with epilogues
+// A [M,K] and W [N,K] are K-contiguous.
+//   EPI_STORE: out T [M,N] = acc + bias
+//   EPI_GELU : out T [M,N] = gelu(acc + bias)
+//   EPI_RESID: xres fp32 [M,N] += acc + bias
+//   EPI_F32  : outf fp32 [M,N] = acc + bias (bias may be null)
+struct GemmEpi { int mode; void* out; const void* bias; };
+
+template <typename T>
+__device__ __forceinline__ void epilogue_store(const GemmEpi& ep, int m, int n, int N, float v) {
+  if (ep.bias) v += to_f32(reinterpret_cast<const T*>(ep.bias)[n]);
+  const size_t o = (size_t)m * N + n;
+  switch (ep.mode) {
+    case EPI_STORE: from_f32(v, reinterpret_cast<T*>(ep.out)[o]); break;
+    case EPI_GELU:  from_f32(gelu_erf(v), reinterpret_cast<T*>(ep.out)[o]); break;
+    case EPI_RESID: reinterpret_cast<float*>(ep.out)[o] += v; break;
+    default:        reinterpret_cast<float*>(ep.out)[o] = v; break;
+  }
+}
+
+// fp32 path: 64x64 tile, BK = 16, each thread 4x4 outputs; any M, N, K.
+__global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ W, int M, int N, int K, GemmEpi ep) {
+  __shared__ float As[16][64 + 4], Ws[16][64 + 4];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      const int r = i >> 4, kk = i & 15;
+      As[kk][r] = (m0 + r < M && k0 + kk < K) ? A[(size_t)(m0 + r) * K + k0 + kk] : 0.f;
+      Ws[kk][r] = (n0 + r < N && k0 + kk < K) ? W[(size_t)(n0 + r) * K + k0 + kk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; w[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], w[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) epilogue_store<float>(ep, m, n, N, acc[i][j]);
+    }
+}
+
+// bf16 path: MFMA 32x32x16, 128x128 block tile, BK = 64, 4 waves of 64x64, LDS double buffer.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int GB_M = 128, GB_N = 128, GB_K = 64, GB_LD = GB_K + 8;   // row stride 144 B breaks bank conflicts
+
+__global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K, GemmEpi ep) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(gsm);                       // [2][128][GB_LD]
+  bf16_t* Ws = As + 2 * GB_M * GB_LD;                                // [2][128][GB_LD]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * GB_M, n0 = blockIdx.x * GB_N;
+  // global -> register staging: each thread moves 4 chunks of 16 B per operand per k-tile
+  const int lr = tid >> 3, lc = (tid & 7) * 8;                       // row (0..31) + 32*i, column chunk
+  uint4 ra[4], rw[4];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int r = m0 + lr + 32 * i; r = r < M ? r : M - 1;
+      ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)r * K + k0 + lc);
+      int c = n0 + lr + 32 * i; c = c < N ? c : N - 1;
+      rw[i] = *reinterpret_cast<const uint4*>(W + (size_t)c * K + k0 + lc);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<uint4*>(As + (buf * GB_M + lr + 32 * i) * GB_LD + lc) = ra[i];
+      *reinterpret_cast<uint4*>(Ws + (buf * GB_N + lr + 32 * i) * GB_LD + lc) = rw[i];
+    }
+  };
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int nk = K / GB_K;
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  const int l32 = lane & 31, kg = (lane >> 5) * 8;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) gload((kt + 1) * GB_K);
+#pragma unroll
+    for (int ks = 0; ks < GB_K; ks += 16) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = *reinterpret_cast<const bf16x8*>(As + (buf * GB_M + wm * 64 + i * 32 + l32) * GB_LD + ks + kg);
+        b[i] = *reinterpret_cast<const bf16x8*>(Ws + (buf * GB_N + wn * 64 + i * 32 + l32) * GB_LD + ks + kg);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) sstore(buf ^ 1);
+    __syncthreads();
+  }
+  // epilogue: lane holds column l32, rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 tile
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn * 64 + j * 32 + l32;
+      if (n >= N) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (m < M) epilogue_store<bf16_t>(ep, m, n, N, acc[i][j][v]);
+      }
+    }
+}
+
+// ------------------------------------------------------------------ attention
+// One thread per query row, one block per (batch, head, 256-query chunk); keys/values
+// stream through LDS in chunks of 32; online softmax in fp32.
+template <typename T, int DH>
+__global__ void __launch_bounds__(256) attention_kernel(const T* __restrict__ qkv, T* __restrict__ ctx, const int32_t* __restrict__ lengths,
+                                                        int seq, int d, int n_head, int causal) {
+  constexpr int KC = 32;
+  __shared__ float Ks[KC][DH], Vs[KC][DH];
+  const int chunks = (seq + 255) / 256;
+  const int qc = blockIdx.x % chunks, h = (blockIdx.x / chunks) % n_head, b = blockIdx.x / (chunks * n_head);
+  const int qi = qc * 256 + threadIdx.x;
+  const bool active = qi < seq;
+  const int len = lengths ? lengths[b] : seq;
+  const size_t ld = (size_t)3 * d;
+  const T* base = qkv + (size_t)b * seq * ld + (size_t)h * DH;
+  float q[DH], acc[DH];
+  const float scale = 1.0f / sqrtf((float)DH);
+#pragma unroll
+  for (int i = 0; i < DH; ++i) { q[i] = active ? to_f32(base[(size_t)qi * ld + i]) * scale : 0.f; acc[i] = 0.f; }
+  float mx = -INFINITY, den = 0.f;
+  int kend = len < seq ? len : seq;
+  if (causal) { const int last = qc * 256 + 255; kend = kend < last + 1 ? kend : last + 1; }
+  for (int k0 = 0; k0 < kend; k0 += KC) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < KC * DH; i += 256) {
+      const int r = i / DH, c = i - r * DH;
+      const int kj = k0 + r;
+      Ks[r][c] = kj < seq ? to_f32(base[(size_t)kj * ld + d + c]) : 0.f;
+      Vs[r][c] = kj < seq ? to_f32(base[(size_t)kj * ld + 2 * d + c]) : 0.f;
+    }
+    __syncthreads();
+    if (!active) continue;
+    for (int r = 0; r < KC; ++r) {
+      const int kj = k0 + r;
+      if (kj >= kend || (causal && kj > qi)) break;
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < DH; ++i) s = __builtin_fmaf(q[i], Ks[r][i], s);
+      const float nm = fmaxf(mx, s);
+      const float corr = __expf(mx - nm), p = __expf(s - nm);
+      den = den * corr + p;
+#pragma unroll
+      for (int i = 0; i < DH; ++i) acc[i] = __builtin_fmaf(p, Vs[r][i], acc[i] * corr);
+      mx = nm;
+    }
+  }
+  if (active) {
+    T* o = ctx + ((size_t)b * seq + qi) * d + (size_t)h * DH;
+    const float inv = den > 0.f ? 1.0f / den : 0.f;
+#pragma unroll
+    for (int i = 0; i < DH; ++i) from_f32(acc[i] * inv, o[i]);
+  }
+}
+
+// ------------------------------------------------------------------ losses
+// Cross-entropy of one row of fp32 logits [n]: loss = logsumexp - logit[target]; target < 0: row skipped (loss 0).
+__global__ void __launch_bounds__(256) ce_rows_kernel(const float* __restrict__ logits, const int32_t* __restrict__ targets, float* __restrict__ row_loss,
+                                                      int n, int vocab_clamp) {
+  __shared__ float red[4];
+  const int m = blockIdx.x;
+  int tgt = targets[m];
+  if (tgt < 0) { if (threadIdx.x == 0) row_loss[m] = 0.f; return; }
+  tgt = tgt >= vocab_clamp ? vocab_clamp - 1 : tgt;
+  const float* row = logits + (size_t)m * n;
+  float mx = -INFINITY;
+  for (int i = threadIdx.x; i < n; i += 256) mx = fmaxf(mx, row[i]);
+  mx = block_max(mx, red);
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += expf(row[i] - mx);
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) row_loss[m] = logf(s) + mx - row[tgt];
+}
+
+// next-token targets: row m = b*seq + t predicts tok[m+1] for t < seq-1, else -1
+__global__ void lm_targets_kernel(const int32_t* __restrict__ tok, int32_t* __restrict__ tgt, int M, int seq) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m < M) tgt[m] = (m % seq) < seq - 1 ? tok[m + 1] : -1;
+}
+
+// mean of n_rows losses (ignoring the skipped ones by dividing by `count`), accumulated in fp64
+__global__ void __launch_bounds__(256) mean_f64_kernel(const float* __restrict__ v, int n, double inv_count, double* __restrict__ out) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) s += (double)v[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) { if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o]; __syncthreads(); }
+  if (threadIdx.x == 0) *out = red[0] * inv_count;
+}
+
+// classification head on token 0 of every sequence: logits[b][c] = h[b*seq] . Wc[c] + bc[c]
+template <typename T>
+__global__ void __launch_bounds__(64) cls_head_kernel(const T* __restrict__ h, const T* __restrict__ Wc, const T* __restrict__ bc, float* __restrict__ logits,
+                                                      int seq, int d, int n_class) {
+  const int b = blockIdx.x / n_class, c = blockIdx.x % n_class;
+  const T* x = h + (size_t)b * seq * d;
+  const T* w = Wc + (size_t)c * d;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 64) s = __builtin_fmaf(to_f32(x[i]), to_f32(w[i]), s);
+  s = wave_sum(s);
+  if (threadIdx.x == 0) logits[b * n_class + c] = s + to_f32(bc[c]);
+}
+
+// least squares: row_loss[b] = sum_o (pred[b][o] - Y[b][o])^2 / 2
+__global__ void __launch_bounds__(256) lsq_rows_kernel(const float* __restrict__ pred, const float* __restrict__ Y, float* __restrict__ row_loss, int n_out) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n_out; i += 256) { const float r = pred[(size_t)b * n_out + i] - Y[(size_t)b * n_out + i]; s = __builtin_fmaf(r, r, s); }
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) row_loss[b] = 0.5f * s;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ host launchers
+hipError_t launch_embed(int dtype, const int32_t* tok, const void* E, const void* Pe, float* x, int M, int seq, int d, int vocab, hipStream_t s) {
+  if (dtype == 0) hipLaunchKernelGGL(embed_kernel<float>, dim3(M), dim3(256), 0, s, tok, (const float*)E, (const float*)Pe, x, M, seq, d, vocab);
+  else            hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(M), dim3(256), 0, s, tok, (const bf16_t*)E, (const bf16_t*)Pe, x, M, seq, d, vocab);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s) {
+  if (dtype == 0) hipLaunchKernelGGL(layernorm_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps);
+  else            hipLaunchKernelGGL(layernorm_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias, void* out, int epi, int M, int N, int K, hipStream_t s) {
+  GemmEpi ep{epi, out, bias};
+  if (dtype == 0) {
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, s, (const float*)A, (const float*)W, M, N, K, ep);
+  } else {
+    if (K % GB_K != 0) return hipErrorInvalidValue;
+    const size_t lds = (size_t)2 * (GB_M + GB_N) * GB_LD * sizeof(bf16_t);
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_bf16_kernel, dim3((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M), dim3(256), lds, s, (const bf16_t*)A, (const bf16_t*)W, M, N, K, ep);
+  }
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_attention_t(const T* qkv, T* ctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal, hipStream_t s) {
+  const int dh = d / n_head;
+  const int grid = batch * n_head * ((seq + 255) / 256);
+  switch (dh) {
+    case 8:   hipLaunchKernelGGL((attention_kernel<T, 8>), dim3(grid), dim3(256), 0, s, qkv, ctx, lengths, seq, d, n_head, causal); break;
+    case 16:  hipLaunchKernelGGL((attention_kernel<T, 16>), dim3(grid), dim3(256), 0, s, qkv, ctx, lengths, seq, d, n_head, causal); break;
+    case 32:  hipLaunchKernelGGL((attention_kernel<T, 32>), dim3(grid), dim3(256), 0, s, qkv, ctx, lengths, seq, d, n_head, causal); break;
+    case 64:  hipLaunchKernelGGL((attention_kernel<T, 64>), dim3(grid), dim3(256), 0, s, qkv, ctx, lengths, seq, d, n_head, causal); break;
+    default:  return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(int dtype, const void* qkv, void* ctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal, hipStream_t s) {
+  if (dtype == 0) return launch_attention_t<float>((const float*)qkv, (float*)ctx, lengths, batch, seq, d, n_head, causal, s);
+  return launch_attention_t<bf16_t>((const bf16_t*)qkv, (bf16_t*)ctx, lengths, batch, seq, d, n_head, causal, s);
+}
+
+bool attention_head_dim_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh == 64; }
+
+hipError_t launch_lm_targets(const int32_t* tok, int32_t* tgt, int M, int seq, hipStream_t s) {
+  hipLaunchKernelGGL(lm_targets_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tok, tgt, M, seq);
+  return hipGetLastError();
+}
+
+hipError_t launch_ce_rows(const float* logits, const int32_t* targets, float* row_loss, int M, int n, hipStream_t s) {
+  hipLaunchKernelGGL(ce_rows_kernel, dim3(M), dim3(256), 0, s, logits, targets, row_loss, n, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_mean_f64(const float* v, int n, double inv_count, double* out, hipStream_t s) {
+  hipLaunchKernelGGL(mean_f64_kernel, dim3(1), dim3(256), 0, s, v, n, inv_count, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_cls_head(int dtype, const void* h, const void* Wc, const void* bc, float* logits, int batch, int seq, int d, int n_class, hipStream_t s) {
+  if (dtype == 0) hipLaunchKernelGGL(cls_head_kernel<float>, dim3(batch * n_class), dim3(64), 0, s, (const float*)h, (const float*)Wc, (const float*)bc, logits, seq, d, n_class);
+  else            hipLaunchKernelGGL(cls_head_kernel<bf16_t>, dim3(batch * n_class), dim3(64), 0, s, (const bf16_t*)h, (const bf16_t*)Wc, (const bf16_t*)bc, logits, seq, d, n_class);
+  return hipGetLastError();
+}
+
+hipError_t launch_lsq_rows(const float* pred, const float* Y, float* row_loss, int batch, int n_out, hipStream_t s) {
+  hipLaunchKernelGGL(lsq_rows_kernel, dim3(batch), dim3(256), 0, s, pred, Y, row_loss, n_out);
+  return hipGetLastError();
+}
+
+}  // namespace zgr

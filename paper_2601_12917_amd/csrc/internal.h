@@ -1,0 +1,60 @@
+// Internal interfaces between the host runtime (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "rng.h"
+
+namespace zgr {
+
+// Device-visible description of one parameter tensor for the perturbation pass.
+struct TensorDesc {
+  void*        theta;
+  const float* U;        // nullptr or k == 0: isotropic, Z = G
+  int64_t      rows, cols;
+  uint32_t     id;       // < 2^31
+  int32_t      k, ldu;
+  float        a, b;     // Z = a G + b U R   (a = 1, b = 0 when isotropic)
+  int32_t      dtype;    // 0 fp32, 1 bf16
+};
+
+// One unit of work of the perturbation kernels.
+//  flat kernel: `first` = first Philox group of the chunk, `count` = groups in the chunk
+//  tile kernel: `first` = row0 << 32 | col0, `count` = rows in the tile
+struct WorkItem {
+  int32_t tensor;
+  int32_t count;
+  int64_t first;
+};
+
+constexpr int kFlatGroupsPerItem = 2048;   // Philox calls per flat work item (8 per thread)
+constexpr int kTileRowsPerIter   = 128;    // rows one block covers per iteration (4 waves x 32)
+constexpr int kMaxK              = 64;
+
+struct PerturbArgs {
+  const TensorDesc* descs;     // device
+  const WorkItem*   flat;      // device
+  const WorkItem*   tiles;     // device
+  int32_t           n_flat, n_tiles;
+  uint32_t          k0, k1;    // Philox key = seed
+  uint32_t          step;
+  int32_t           bits;      // 32 | 16
+  int32_t           dtype;
+  int32_t           max_k;     // largest k among tiled tensors
+};
+
+// theta += c * Z for everything in the flat / tile work list.  zout != nullptr:
+// instead write Z of the single tensor in the list as fp32 [rows, cols].
+hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu);
+hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu);
+
+// radius table upload (once per process and device) and access
+hipError_t ensure_radius_table(const RadiusEntry** dev_ptr);
+
+hipError_t launch_debug_philox(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out, int64_t n, hipStream_t s);
+hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t id_stream, int bits, int64_t first, int64_t n,
+                              float* out, hipStream_t s);
+hipError_t launch_debug_radius_table(int bits, float* out, hipStream_t s);
+hipError_t launch_debug_cossin_table(int bits, float* c, float* sn, hipStream_t s);
+
+}  // namespace zgr

@@ -1,0 +1,332 @@
+// In-place perturbation pass theta <- rnd(theta + c Z), Z = a G + b U R (Eq. (10)),
+// with G and R regenerated from the shared seed in registers / LDS and never
+// stored (Sec. 4.1 step 5; Algorithm 1, client and edge-server blocks).  One
+// pass reads and writes every parameter exactly once.
+//
+// Two persistent kernels per pass, each looping over a work list:
+//   flat: tensors without a basis (embeddings, biases, LayerNorm, non-guided
+//         rounds): one thread per Philox call, fully coalesced vector RMW;
+//   tile: guided matrices: a block owns a [rows x 32P] column strip piece,
+//         generates its slice of R once into LDS, stages U row blocks in LDS,
+//         contracts U R in registers and fuses G, the mix and the axpy.
+#include "internal.h"
+
+namespace zgr {
+
+namespace {
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
+__device__ __forceinline__ void from_f32(float x, float& o) { o = x; }
+__device__ __forceinline__ void from_f32(float x, bf16_t& o) {     // round to nearest, ties to even
+  const uint32_t b = __float_as_uint(x);
+  o.bits = (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+
+template <typename T, int P> struct alignas(sizeof(T) * P <= 16 ? sizeof(T) * P : 16) Vec { T v[P]; };
+
+template <int P> __device__ __forceinline__ void gaussP(const u32x4 w, const RadiusEntry* tab, float* g);
+template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss4(w, tab, g); }
+template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
+
+// ------------------------------------------------------------------ flat
+template <typename T, int P, bool WRITE_Z>
+__global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
+                                                           float* __restrict__ zout) {
+  __shared__ RadiusEntry tab[kRadiusTabEntries];
+  load_radius_table(tab, gtab);
+  __syncthreads();
+  for (int w = blockIdx.x; w < a.n_flat; w += gridDim.x) {
+    const WorkItem it = a.flat[w];
+    const TensorDesc d = a.descs[it.tensor];
+    const int64_t n = d.rows * d.cols;
+    T* __restrict__ th = reinterpret_cast<T*>(d.theta);
+    for (int g = threadIdx.x; g < it.count; g += 256) {
+      const int64_t q = it.first + g;
+      const int64_t e0 = q * P;
+      float G[P];
+      gaussP<P>(philox_call((uint64_t)q, d.id, a.step, a.k0, a.k1), tab, G);
+      if (WRITE_Z) {
+        for (int j = 0; j < P; ++j) if (e0 + j < n) zout[e0 + j] = G[j];
+      } else if (e0 + P <= n) {
+        Vec<T, P>* p = reinterpret_cast<Vec<T, P>*>(th + e0);
+        Vec<T, P> x = *p;
+#pragma unroll
+        for (int j = 0; j < P; ++j) from_f32(__builtin_fmaf(c, G[j], to_f32(x.v[j])), x.v[j]);
+        *p = x;
+      } else {
+        for (int j = 0; j < P; ++j)
+          if (e0 + j < n) { T x = th[e0 + j]; from_f32(__builtin_fmaf(c, G[j], to_f32(x)), x); th[e0 + j] = x; }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ tile
+// Lane layout inside a wave's 32-row slab: column group cg = lane % 32 owns P
+// consecutive columns; register v of the lane is row 8*(v/4) + 4*(lane/32) + v%4.
+template <typename T, int P, bool WRITE_Z>
+__global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
+                                                           float* __restrict__ zout, int kp) {
+  extern __shared__ float smem[];
+  RadiusEntry* tab = reinterpret_cast<RadiusEntry*>(smem);
+  float* Us = smem + kRadiusTabEntries * 3;          // [128][kp]
+  float* Rs = Us + kTileRowsPerIter * kp;            // [kp][TC]
+  constexpr int TC = 32 * P;
+  constexpr int RB = (P == 4) ? 16 : 8;              // rows a lane holds at once
+  load_radius_table(tab, gtab);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cg = lane & 31, rh = lane >> 5;
+
+  for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
+    const WorkItem it = a.tiles[w];
+    const TensorDesc d = a.descs[it.tensor];
+    const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
+    const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7;
+    T* __restrict__ th = reinterpret_cast<T*>(d.theta);
+    __syncthreads();                                 // table loaded / previous tile's readers done
+    // this tile's slice of b*R: rows l < k, columns col0 .. col0+TC
+    for (int idx = tid; idx < kpt * 32; idx += 256) {
+      const int l = idx >> 5, g = idx & 31;
+      const int64_t col = col0 + (int64_t)g * P;
+      float r[P];
+#pragma unroll
+      for (int j = 0; j < P; ++j) r[j] = 0.f;
+      if (l < k && col < d.cols) {
+        const uint64_t q = (uint64_t)((int64_t)l * d.cols + col) / P;
+        gaussP<P>(philox_call(q, d.id | 0x80000000u, a.step, a.k0, a.k1), tab, r);
+#pragma unroll
+        for (int j = 0; j < P; ++j) r[j] *= d.b;
+      }
+#pragma unroll
+      for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
+    }
+    for (int r0 = 0; r0 < nrows; r0 += kTileRowsPerIter) {
+      if (r0 > 0) __syncthreads();                   // previous row block's readers of Us done
+      for (int idx = tid; idx < kTileRowsPerIter * kpt; idx += 256) {
+        const int r = idx / kpt, l = idx - r * kpt;
+        const int64_t row = row0 + r0 + r;
+        Us[r * kp + l] = (l < k && r0 + r < nrows && row < d.rows) ? d.U[row * d.ldu + l] : 0.f;
+      }
+      __syncthreads();
+      const int64_t col = col0 + (int64_t)cg * P;
+#pragma unroll 1
+      for (int vb = 0; vb < 16; vb += RB) {
+        float acc[RB][P];
+#pragma unroll
+        for (int v = 0; v < RB; ++v)
+#pragma unroll
+          for (int j = 0; j < P; ++j) acc[v][j] = 0.f;
+        for (int l0 = 0; l0 < kpt; l0 += 8) {
+          float Rreg[8][P];
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < P; ++j) Rreg[i][j] = Rs[(l0 + i) * TC + cg * P + j];
+#pragma unroll
+          for (int v = 0; v < RB; ++v) {
+            const int vv = vb + v;
+            const int rloc = 32 * wave + 8 * (vv >> 2) + 4 * rh + (vv & 3);
+            const float* u = Us + rloc * kp + l0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const float ui = u[i];
+#pragma unroll
+              for (int j = 0; j < P; ++j) acc[v][j] = __builtin_fmaf(ui, Rreg[i][j], acc[v][j]);
+            }
+          }
+        }
+        if (col < d.cols) {
+#pragma unroll
+          for (int v = 0; v < RB; ++v) {
+            const int vv = vb + v;
+            const int rloc = 32 * wave + 8 * (vv >> 2) + 4 * rh + (vv & 3);
+            const int64_t row = row0 + r0 + rloc;
+            if (r0 + rloc < nrows && row < d.rows) {
+              const int64_t e0 = row * d.cols + col;
+              float G[P];
+              gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
+              if (WRITE_Z) {
+#pragma unroll
+                for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[v][j]);
+              } else {
+                Vec<T, P>* p = reinterpret_cast<Vec<T, P>*>(th + e0);
+                Vec<T, P> x = *p;
+#pragma unroll
+                for (int j = 0; j < P; ++j) {
+                  const float z = __builtin_fmaf(d.a, G[j], acc[v][j]);
+                  from_f32(__builtin_fmaf(c, z, to_f32(x.v[j])), x.v[j]);
+                }
+                *p = x;
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ debug kernels
+__global__ void debug_philox_kernel(const uint32_t* __restrict__ ctr, uint32_t k0, uint32_t k1, uint32_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const u32x4 r = philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], k0, k1);
+  out[4 * i] = r.x; out[4 * i + 1] = r.y; out[4 * i + 2] = r.z; out[4 * i + 3] = r.w;
+}
+
+template <int P>
+__global__ void __launch_bounds__(256) debug_gauss_kernel(uint32_t k0, uint32_t k1, uint32_t step, uint32_t id_stream, int64_t first,
+                                                          int64_t n, const RadiusEntry* __restrict__ gtab, float* __restrict__ out) {
+  __shared__ RadiusEntry tab[kRadiusTabEntries];
+  load_radius_table(tab, gtab);
+  __syncthreads();
+  const int64_t q0 = first / P, q1 = (first + n + P - 1) / P;
+  for (int64_t q = q0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < q1; q += (int64_t)gridDim.x * blockDim.x) {
+    float G[P];
+    gaussP<P>(philox_call((uint64_t)q, id_stream, step, k0, k1), tab, G);
+    for (int j = 0; j < P; ++j) {
+      const int64_t e = q * P + j;
+      if (e >= first && e < first + n) out[e - first] = G[j];
+    }
+  }
+}
+
+// all radius uniforms: bits=32: N = 2n+1, n < 2^23; bits=16: N = (2h+1) << 7, h < 2^16
+__global__ void __launch_bounds__(256) debug_radius_kernel(int bits, const RadiusEntry* __restrict__ gtab, float* __restrict__ out) {
+  __shared__ RadiusEntry tab[kRadiusTabEntries];
+  load_radius_table(tab, gtab);
+  __syncthreads();
+  const uint32_t total = bits == 32 ? (1u << 23) : (1u << 16);
+  for (uint32_t n = blockIdx.x * blockDim.x + threadIdx.x; n < total; n += gridDim.x * blockDim.x) {
+    const uint32_t N = bits == 32 ? ((n << 1) | 1u) : (((n << 1) | 1u) << 7);
+    out[n] = radius_from_odd24(N, tab);
+  }
+}
+
+__global__ void __launch_bounds__(256) debug_cossin_kernel(int bits, float* __restrict__ co, float* __restrict__ so) {
+#pragma clang fp contract(off)
+  const uint32_t total = bits == 32 ? (1u << 24) : (1u << 16);
+  for (uint32_t n = blockIdx.x * blockDim.x + threadIdx.x; n < total; n += gridDim.x * blockDim.x) {
+    const uint32_t m = bits == 32 ? n : (n << 8);
+    const TrigHL t = trig_from_u24(m);
+    // the fused kernel multiplies (hi, lo) by the radius; with radius 1 the product is the rounded sum
+    const float one_c = __uint_as_float(0x3F800000u ^ t.csign), one_s = __uint_as_float(0x3F800000u ^ t.ssign);
+    co[n] = __builtin_fmaf(one_c, t.ch, one_c * t.cl);
+    so[n] = __builtin_fmaf(one_s, t.sh, one_s * t.sl);
+  }
+}
+
+// The table lives in static device memory: the library allocates nothing.
+__device__ RadiusEntry g_radius_table[kRadiusTabEntries];
+
+}  // namespace
+
+hipError_t ensure_radius_table(const RadiusEntry** dev_ptr) {
+  static const RadiusEntry* cached[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!cached[dev]) {
+    static RadiusEntry host[kRadiusTabEntries];
+    for (int E = 0; E < 24; ++E)
+      for (int j = 0; j < 64; ++j) {
+        const double cj = __builtin_rint(128.0 / (1.0 + (j + 0.5) / 64.0)) / 128.0;
+        double hl = 2.0 * __builtin_log(cj) + 2.0 * (24.0 - E) * 0.69314718055994530942;
+        if (E == 23 && j == 63) hl = 0.0;        // c = 1/2, N c 2^-23 -> exactly -2 log1p(z)
+        RadiusEntry& r = host[E * 64 + j];
+        r.H = (float)hl;
+        r.L = (float)(hl - (double)r.H);
+        r.C = (float)__builtin_ldexp(cj, -E);
+      }
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_radius_table));
+    if (e != hipSuccess) return e;
+    e = hipMemcpy(p, host, sizeof(host), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return e;
+    cached[dev] = reinterpret_cast<const RadiusEntry*>(p);
+  }
+  *dev_ptr = cached[dev];
+  return hipSuccess;
+}
+
+namespace {
+template <typename T, int P>
+hipError_t launch_flat_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
+  const int grid = a.n_flat < n_cu * 8 ? a.n_flat : n_cu * 8;
+  if (zout) hipLaunchKernelGGL((perturb_flat_kernel<T, P, true>), dim3(grid), dim3(256), 0, s, a, c, tab, zout);
+  else      hipLaunchKernelGGL((perturb_flat_kernel<T, P, false>), dim3(grid), dim3(256), 0, s, a, c, tab, zout);
+  return hipGetLastError();
+}
+template <typename T, int P>
+hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
+  const int kp = (a.max_k + 7) & ~7;
+  const size_t lds = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kTileRowsPerIter * kp + (size_t)kp * 32 * P);
+  int per_cu = (int)((160 * 1024) / lds);
+  if (per_cu > 4) per_cu = 4;
+  if (per_cu < 1) per_cu = 1;
+  const int grid = a.n_tiles < n_cu * per_cu ? a.n_tiles : n_cu * per_cu;
+  auto kern = zout ? perturb_tile_kernel<T, P, true> : perturb_tile_kernel<T, P, false>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, c, tab, zout, kp);
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu) {
+  if (a.n_flat <= 0) return hipSuccess;
+  const RadiusEntry* tab = nullptr;
+  hipError_t e = ensure_radius_table(&tab);
+  if (e != hipSuccess) return e;
+  if (a.dtype == 0) return a.bits == 32 ? launch_flat_t<float, 4>(a, c, zout, s, n_cu, tab) : launch_flat_t<float, 8>(a, c, zout, s, n_cu, tab);
+  return a.bits == 32 ? launch_flat_t<bf16_t, 4>(a, c, zout, s, n_cu, tab) : launch_flat_t<bf16_t, 8>(a, c, zout, s, n_cu, tab);
+}
+
+hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu) {
+  if (a.n_tiles <= 0) return hipSuccess;
+  if (a.max_k < 1 || a.max_k > kMaxK) return hipErrorInvalidValue;
+  const RadiusEntry* tab = nullptr;
+  hipError_t e = ensure_radius_table(&tab);
+  if (e != hipSuccess) return e;
+  if (a.dtype == 0) return a.bits == 32 ? launch_tile_t<float, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<float, 8>(a, c, zout, s, n_cu, tab);
+  return a.bits == 32 ? launch_tile_t<bf16_t, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<bf16_t, 8>(a, c, zout, s, n_cu, tab);
+}
+
+hipError_t launch_debug_philox(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(debug_philox_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ctr, k0, k1, out, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t id_stream, int bits, int64_t first, int64_t n,
+                              float* out, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const RadiusEntry* tab = nullptr;
+  hipError_t e = ensure_radius_table(&tab);
+  if (e != hipSuccess) return e;
+  const int P = bits == 32 ? 4 : 8;
+  int64_t blocks = (n / P + 256) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (bits == 32) hipLaunchKernelGGL(debug_gauss_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1, step, id_stream, first, n, tab, out);
+  else            hipLaunchKernelGGL(debug_gauss_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1, step, id_stream, first, n, tab, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_radius_table(int bits, float* out, hipStream_t s) {
+  const RadiusEntry* tab = nullptr;
+  hipError_t e = ensure_radius_table(&tab);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(debug_radius_kernel, dim3(bits == 32 ? 2048 : 64), dim3(256), 0, s, bits, tab, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_cossin_table(int bits, float* c, float* sn, hipStream_t s) {
+  hipLaunchKernelGGL(debug_cossin_kernel, dim3(bits == 32 ? 4096 : 64), dim3(256), 0, s, bits, c, sn);
+  return hipGetLastError();
+}
+
+}  // namespace zgr

@@ -1,0 +1,192 @@
+"""Device-memory plumbing around the C ABI: allocates parameters, bases, batch
+and workspace with torch, builds the tensor table and forwards every call to
+libzgr.so.  No arithmetic of the method happens here."""
+import ctypes as C
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class ParamSpec:
+    """One tensor handed to the session: host values fp32 [rows, cols]
+    (bf16-representable when dtype is 'bf16'), optional basis fp32 [rows, ldu]."""
+
+    def __init__(self, name, role, layer, tensor_id, values, U=None, k=0):
+        self.name, self.role, self.layer, self.tensor_id = name, int(role), int(layer), int(tensor_id)
+        self.values = np.ascontiguousarray(values, dtype=np.float32)
+        self.U = None if U is None else np.ascontiguousarray(U, dtype=np.float32)
+        self.k = int(k) if U is not None else 0
+
+
+def _align(x, a=256):
+    return (x + a - 1) // a * a
+
+
+class Session:
+    def __init__(self, arch, dtype, params: Sequence[ParamSpec], seed, eps, alpha, scale_mode=B.ZGR_SCALE_UNIT,
+                 gauss_bits=32, n_layer=0, d_model=0, n_head=0, d_ff=0, vocab=0, max_pos=0, n_class=0, ln_eps=1e-5,
+                 max_batch=1, max_seq=2, device="cuda:0", pack_after=()):
+        """pack_after: names of tensors that must start right where the previous one ends
+        (Wk, Wv after Wq; bk, bv after bq)."""
+        self.lib = B.lib()
+        self.dev = torch.device(device)
+        torch.cuda.set_device(self.dev)
+        self.dtype = dtype
+        self.tdtype = torch.float32 if dtype == "f32" else torch.bfloat16
+        es = 4 if dtype == "f32" else 2
+        self.params = list(params)
+        # one slab for all parameters
+        offs, off = [], 0
+        for p in self.params:
+            if p.name not in pack_after:
+                off = _align(off)
+            offs.append(off)
+            off += p.values.size * es
+        self.slab = torch.zeros(_align(off) // es, dtype=self.tdtype, device=self.dev)
+        self.theta: List[torch.Tensor] = []
+        for p, o in zip(self.params, offs):
+            t = self.slab[o // es: o // es + p.values.size].view(p.values.shape)
+            t.copy_(torch.from_numpy(p.values).to(self.tdtype))
+            self.theta.append(t)
+        self.U = [None if p.U is None else torch.from_numpy(p.U).to(self.dev) for p in self.params]
+        self.table = (B.zgr_tensor * len(self.params))()
+        for i, p in enumerate(self.params):
+            e = self.table[i]
+            e.theta = self.theta[i].data_ptr()
+            e.rows, e.cols = p.values.shape
+            e.dtype = B.ZGR_F32 if dtype == "f32" else B.ZGR_BF16
+            e.tensor_id = p.tensor_id
+            e.U = self.U[i].data_ptr() if self.U[i] is not None else None
+            e.k = p.k
+            e.ldu = p.U.shape[1] if p.U is not None else 0
+            e.role, e.layer = p.role, p.layer
+        self.model = B.zgr_model(arch, n_layer, d_model, n_head, d_ff, vocab, max_pos, n_class, ln_eps)
+        self.config = B.zgr_config(seed, eps, alpha, scale_mode, gauss_bits)
+        nbytes = self.lib.zgr_workspace_bytes(C.byref(self.model), self.table, len(self.params), max_batch, max_seq)
+        if nbytes == 0:
+            raise B.ZgrError(B.ZGR_ERR_SHAPE, "zgr_workspace_bytes rejected the arguments")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+        self.stream = torch.cuda.current_stream(self.dev)
+        self.ctx = C.c_void_p()
+        st = self.lib.zgr_init(C.byref(self.ctx), C.byref(self.model), self.table, len(self.params), C.byref(self.config),
+                               self.workspace.data_ptr(), nbytes, max_batch, max_seq, self.stream.cuda_stream)
+        B.check(st, None)
+        self._batch_keep = None
+
+    # ---- batches --------------------------------------------------------------
+    def make_batch(self, x, y=None, lengths=None, seq=0):
+        keep = []
+
+        def up(a):
+            if a is None:
+                return None
+            t = torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+            keep.append(t)
+            return t.data_ptr()
+        b = B.zgr_batch(up(x), up(y), up(lengths), int(np.asarray(x).shape[0]), int(seq))
+        self._batch_keep = keep
+        return b
+
+    # ---- calls of the C ABI ---------------------------------------------------
+    def step(self, step, batch):
+        r = B.zgr_result()
+        B.check(self.lib.zgr_step(self.ctx, step, C.byref(batch), C.byref(r)), self.ctx)
+        return r.loss_plus, r.loss_minus, r.g
+
+    def apply_update(self, step, g, lr):
+        B.check(self.lib.zgr_apply_update(self.ctx, step, g, lr), self.ctx)
+
+    def perturb(self, step, c):
+        B.check(self.lib.zgr_perturb(self.ctx, step, c), self.ctx)
+
+    def loss(self, batch):
+        v = C.c_double()
+        B.check(self.lib.zgr_loss(self.ctx, C.byref(batch), C.byref(v)), self.ctx)
+        return v.value
+
+    def set_basis(self, index, U: Optional[np.ndarray], k):
+        if U is None:
+            B.check(self.lib.zgr_set_basis(self.ctx, index, None, 0, 0), self.ctx)
+            return
+        t = torch.from_numpy(np.ascontiguousarray(U, dtype=np.float32)).to(self.dev)
+        self.U[index] = t
+        B.check(self.lib.zgr_set_basis(self.ctx, index, t.data_ptr(), k, U.shape[1]), self.ctx)
+
+    def fill_z(self, index, step):
+        rows, cols = self.params[index].values.shape
+        z = torch.empty(rows, cols, dtype=torch.float32, device=self.dev)
+        B.check(self.lib.zgr_debug_fill_z(self.ctx, index, step, z.data_ptr()), self.ctx)
+        torch.cuda.synchronize(self.dev)
+        return z.cpu().numpy()
+
+    def last_row_losses(self, n):
+        out = np.empty(n, dtype=np.float32)
+        B.check(self.lib.zgr_debug_last_row_losses(self.ctx, out.ctypes.data, n), self.ctx)
+        return out
+
+    def profile_enable(self, on=True):
+        B.check(self.lib.zgr_profile_enable(self.ctx, 1 if on else 0), self.ctx)
+
+    def profile_read(self):
+        ms = (C.c_double * B.ZGR_K_COUNT)()
+        n = (C.c_int64 * B.ZGR_K_COUNT)()
+        B.check(self.lib.zgr_profile_read(self.ctx, ms, n), self.ctx)
+        return {name: (ms[i], n[i]) for i, name in enumerate(B.KERNEL_CLASS_NAMES)}
+
+    def get_theta(self, index):
+        torch.cuda.synchronize(self.dev)
+        return self.theta[index].float().cpu().numpy()
+
+    def set_theta(self, index, values):
+        self.theta[index].copy_(torch.from_numpy(np.ascontiguousarray(values, dtype=np.float32)).to(self.tdtype))
+
+    def close(self):
+        if self.ctx:
+            self.lib.zgr_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- context-free debug exports ------------------------------------------------
+def debug_philox(ctr: np.ndarray, key, device="cuda:0"):
+    lib = B.lib()
+    c = torch.from_numpy(np.ascontiguousarray(ctr, dtype=np.uint32).view(np.int32)).to(device)
+    out = torch.empty_like(c)
+    k = (C.c_uint32 * 2)(int(key[0]), int(key[1]))
+    B.check(lib.zgr_debug_philox(c.data_ptr(), k, out.data_ptr(), c.shape[0], torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    return out.cpu().numpy().view(np.uint32)
+
+
+def debug_gauss(seed, step, tensor_id, stream, bits, first, n, device="cuda:0"):
+    lib = B.lib()
+    out = torch.empty(n, dtype=torch.float32, device=device)
+    B.check(lib.zgr_debug_gauss(seed, step, tensor_id, stream, bits, first, n, out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def debug_radius_table(bits, device="cuda:0"):
+    lib = B.lib()
+    out = torch.empty(1 << (23 if bits == 32 else 16), dtype=torch.float32, device=device)
+    B.check(lib.zgr_debug_radius_table(bits, out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def debug_cossin_table(bits, device="cuda:0"):
+    lib = B.lib()
+    n = 1 << (24 if bits == 32 else 16)
+    c = torch.empty(n, dtype=torch.float32, device=device)
+    s = torch.empty(n, dtype=torch.float32, device=device)
+    B.check(lib.zgr_debug_cossin_table(bits, c.data_ptr(), s.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    return c.cpu().numpy(), s.cpu().numpy()

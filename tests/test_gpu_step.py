@@ -1,0 +1,155 @@
+"""HIP path vs CPU oracle for the losses and the whole ZGR step (Algorithm 1):
+per-pass losses within 1e-4 (fp32) / 2e-2 (bf16) relative, updated parameters
+within 1e-5 (fp32) / 1e-2 (bf16) relative when fed the oracle's g."""
+import numpy as np
+import pytest
+
+import zgr_inputs as I
+from oracle import forward as F
+from oracle import perturbation as P
+from tests.util import inputs_of, make_batch_arrays, make_oracle, make_session, oracle_loss_fn, session_batch
+
+pytestmark = pytest.mark.gpu
+
+LOSS_RTOL = {"f32": 1e-4, "bf16": 2e-2}
+PARAM_RTOL = {"f32": 1e-5, "bf16": 1e-2}
+PARAM_SCALE = 0.02
+
+TINY_LM = I.shrink(I.CONFIGS["cfg2"], name="tiny_lm", n_layer=2, d_model=32, n_head=4, d_ff=64, vocab=97,
+                   max_pos=16, batch=3, seq=12, k=4, k_full=4)
+TINY_CLS = I.shrink(I.CONFIGS["cfg4"], name="tiny_cls", dtype="f32", n_layer=2, d_model=32, n_head=2, d_ff=48,
+                    vocab=89, max_pos=16, batch=4, seq=14, tokens="uniform", k=4, k_full=4)
+SMALL_BF16_LM = I.shrink(I.CONFIGS["cfg3"], name="small_bf16_lm", n_layer=2, d_model=128, n_head=2, d_ff=256, vocab=1000,
+                         max_pos=64, batch=3, seq=40, k=16, k_full=16)
+SMALL_BF16_CLS = I.shrink(I.CONFIGS["cfg4"], name="small_bf16_cls", n_layer=2, d_model=128, n_head=2, d_ff=192, vocab=777,
+                          max_pos=64, batch=5, seq=33, k=32, k_full=32)
+
+
+def _params_dict(specs, values):
+    return {s.name: v.astype(np.float64) for s, v in zip(specs, values)}
+
+
+def _close_params(got, want, dtype, eps_z=None):
+    """fp32: 1e-5 relative to the parameter scale.  bf16: 1e-2 relative to the magnitude the value was
+    rounded at, |theta| + eps |Z| (a one-ulp flip of theta + eps Z survives the restore pass), and all
+    but a few elements identical."""
+    if dtype == "f32":
+        return np.all(np.abs(got - want) <= PARAM_RTOL["f32"] * (np.abs(want) + PARAM_SCALE))
+    mag = np.abs(want) + (0.0 if eps_z is None else eps_z)
+    return np.all(np.abs(got - want) <= PARAM_RTOL["bf16"] * mag + 1e-30) and np.mean(got == want) > 0.995
+
+
+@pytest.mark.parametrize("cfg", [TINY_LM, TINY_CLS, I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS], ids=lambda c: c.name)
+def test_loss_and_row_losses_match_oracle(cfg):
+    specs, values, bases = inputs_of(cfg)
+    # a 10x larger init than N(0, 0.02) so that attention and the MLP are far from trivial
+    values = [v if s.role in (I.ROLE_LN1_G, I.ROLE_LN2_G, I.ROLE_LNF_G) else (P.bf16_round(v * np.float32(8)) if cfg.dtype == "bf16" else v * np.float32(8))
+              for s, v in zip(specs, values)]
+    arrays = make_batch_arrays(cfg)
+    sess = make_session(cfg, specs, values, bases)
+    got = sess.loss(session_batch(sess, cfg, arrays))
+    Pd = _params_dict(specs, values)
+    if cfg.arch == I.ARCH_DECODER_LM:
+        rows = F.lm_token_losses(Pd, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        got_rows = sess.last_row_losses(cfg.batch * cfg.seq).reshape(cfg.batch, cfg.seq)[:, :-1]
+    else:
+        rows = F.cls_row_losses(Pd, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        got_rows = sess.last_row_losses(cfg.batch)
+    want = rows.mean()
+    assert abs(got - want) <= LOSS_RTOL[cfg.dtype] * abs(want), (got, want)
+    tol = 1e-4 if cfg.dtype == "f32" else 6e-2
+    assert np.all(np.abs(got_rows - rows) <= tol * np.maximum(np.abs(rows), 1.0)), np.abs(got_rows - rows).max()
+    assert rows.std() > 0.05
+    sess.close()
+
+
+def test_cfg1_trajectory_matches_oracle():
+    cfg = I.CONFIGS["cfg1"]
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays))
+    sess = make_session(cfg, specs, values, bases)
+    batch = session_batch(sess, cfg, arrays)
+    worst_own = 0.0
+    for step in range(cfg.steps):
+        lp, lm, g = sess.step(step, batch)
+        olp, olm, og = o.step(step)
+        assert abs(lp - olp) <= LOSS_RTOL["f32"] * abs(olp) and abs(lm - olm) <= LOSS_RTOL["f32"] * abs(olm)
+        # restore: parameters are back (to rounding) on both sides
+        assert _close_params(sess.get_theta(0), o.tensors[0].theta, "f32")
+        # g amplifies loss error by 1/(2 eps): the bound is |dL| / (2 eps) with fp32 losses ~1e-6 relative
+        assert abs(g - og) <= 2e-6 * abs(olp) / (2 * cfg.eps) + 1e-4 * abs(og)
+        worst_own = max(worst_own, abs(g - og))
+        # decoupled update: both sides apply the oracle's g
+        sess.apply_update(step, float(og), cfg.lr)
+        o.apply_update(step, og, cfg.lr)
+        assert _close_params(sess.get_theta(0), o.tensors[0].theta, "f32")
+    final = sess.loss(batch)
+    assert abs(final - o.loss()) <= 1e-6 * abs(final)
+    sess.close()
+
+
+@pytest.mark.parametrize("cfg", [I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS, TINY_CLS], ids=lambda c: c.name)
+@pytest.mark.parametrize("bits", [32, 16])
+def test_step_and_update_match_oracle(cfg, bits):
+    steps = 3 if cfg.name == "cfg2" else 2
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays), bits=bits)
+    sess = make_session(cfg, specs, values, bases, bits=bits)
+    batch = session_batch(sess, cfg, arrays)
+    for step in range(steps):
+        lp, lm, g = sess.step(step, batch)
+        olp, olm, og = o.step(step)
+        assert abs(lp - olp) <= LOSS_RTOL[cfg.dtype] * abs(olp), (lp, olp)
+        assert abs(lm - olm) <= LOSS_RTOL[cfg.dtype] * abs(olm), (lm, olm)
+        eps_z = [np.float32(cfg.eps) * np.abs(o.z_of(t, step)) for t in o.tensors]
+        for i, t in enumerate(o.tensors):
+            assert _close_params(sess.get_theta(i), t.theta, cfg.dtype, eps_z[i]), t.name
+        sess.apply_update(step, float(og), cfg.lr)
+        o.apply_update(step, og, cfg.lr)
+        for i, t in enumerate(o.tensors):
+            got = sess.get_theta(i)
+            assert _close_params(got, t.theta, cfg.dtype, eps_z[i]), t.name
+            # keep the two sides on the same trajectory: bf16 roundings may legitimately differ by one ulp
+            t.theta = got.copy()
+    sess.close()
+
+
+def test_cfg2_full_trajectory_with_own_g():
+    """20 steps of cfg2 driven by the device's own g; the deviation from the oracle's trajectory is
+    bounded by lr |Z| |dL_err| / (2 eps) per step and reported."""
+    cfg = I.CONFIGS["cfg2"]
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays))
+    sess = make_session(cfg, specs, values, bases)
+    batch = session_batch(sess, cfg, arrays)
+    for step in range(cfg.steps):
+        lp, lm, g = sess.step(step, batch)
+        olp, olm, og = o.step(step)
+        assert abs(lp - olp) <= 1e-4 * abs(olp) and abs(lm - olm) <= 1e-4 * abs(olm)
+        sess.apply_update(step, g, cfg.lr)
+        o.apply_update(step, og, cfg.lr)
+    dev = max(np.abs(sess.get_theta(i) - t.theta).max() for i, t in enumerate(o.tensors))
+    # fp32 loss error ~1e-6 * 7 -> g error ~4e-3 -> lr * 6 sigma * that per step, 20 steps
+    assert dev <= 20 * cfg.lr * 6.0 * 5e-3 + 1e-7, dev
+    sess.close()
+
+
+def test_seed_replay_by_a_context_without_model():
+    """The edge server regenerates the update from (step, g) alone."""
+    cfg = I.CONFIGS["cfg1"]
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    client = make_session(cfg, specs, values, bases)
+    server = make_session(cfg, specs, values, bases, arch=-1)
+    batch = session_batch(client, cfg, arrays)
+    for step in range(4):
+        _, _, g = client.step(step, batch)
+        client.apply_update(step, g, cfg.lr)
+        server.apply_update(step, g, cfg.lr)
+    assert np.allclose(client.get_theta(0), server.get_theta(0), rtol=0, atol=1e-7)
+    with pytest.raises(Exception):
+        server.loss(batch)
+    client.close(); server.close()
