@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the client-side ZGR step on one MI355X.
+
+One step = the whole hot path on one synthetic batch already resident in HBM:
+perturb +eps Z, forward, perturb -2 eps Z, forward, restore +eps Z, form g,
+update theta <- theta - lr g Z (four streaming passes over all parameters and
+two forward passes).  Prints one JSON line with the throughput, the roofline
+of the dominant kernel (HIP-event timed inside the timed region) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def forward_gemm_flops(cfg):
+    """Algorithmic FLOPs of the GEMM launches of one forward pass (linear layers + vocabulary projection)."""
+    M, d, ff = cfg.batch * cfg.seq, cfg.d_model, cfg.d_ff
+    per_layer = 2.0 * M * (4 * d * d + 2 * d * ff)
+    return cfg.n_layer * per_layer + 2.0 * M * d * cfg.vocab
+
+
+def cpu_baseline(cfg, specs, budget_note=True):
+    """Times the oracle (as it stands) on a bounded sample of the workload and scales to steps/s."""
+    import zgr_inputs as I
+    from oracle import forward as F
+    from oracle import perturbation as P
+    threads = os.cpu_count() or 1
+    try:
+        import threadpoolctl
+        infos = threadpoolctl.threadpool_info()
+        if infos:
+            threads = max(i.get("num_threads", 1) for i in infos)
+    except Exception:
+        pass
+    d, ff, V, T = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.seq
+    rng = np.random.default_rng(0)
+    # (i) one perturbation pass over one guided d x d matrix
+    q, _ = np.linalg.qr(rng.standard_normal((d, cfg.k)))
+    U = q.astype(np.float32)
+    W = (rng.standard_normal((d, d)) * 0.02).astype(np.float32)
+    t0 = time.perf_counter()
+    Z = P.hybrid_z(cfg.seed, 0, 7, d, d, U, cfg.k, cfg.alpha)
+    P.axpy_inplace_value(W, np.float32(cfg.eps), Z, cfg.dtype)
+    t_pass = time.perf_counter() - t0
+    total_params = sum(s.numel for s in specs)
+    # (ii) one transformer block + the vocabulary projection and loss on one sequence
+    one = I.shrink(cfg, name="cpu_sample", n_layer=1, batch=1)
+    sspecs = I.tensor_specs(one)
+    Pd = {s.name: (rng.standard_normal((s.rows, s.cols)) * 0.02) for s in sspecs}
+    for n in ("l0.ln1_g", "l0.ln2_g", "lnf_g"):
+        Pd[n] = Pd[n] + 1.0
+    tok = rng.integers(0, V, size=(1, T))
+    t0 = time.perf_counter()
+    x = Pd["tok_emb"][tok] + Pd["pos_emb"][:T][None]
+    x = F.block(x, Pd, 0, cfg.n_head, True, None, cfg.ln_eps)
+    t_layer = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    h = F.layer_norm(x, Pd["lnf_g"], Pd["lnf_b"], cfg.ln_eps)
+    logp = F.log_softmax(h[:, :-1] @ Pd["tok_emb"].T)
+    float(-np.take_along_axis(logp, tok[:, 1:, None], axis=-1).mean())
+    t_head = time.perf_counter() - t0
+    fwd = cfg.batch * (cfg.n_layer * t_layer + t_head)
+    step_s = 4.0 * t_pass * total_params / (d * d) + 2.0 * fwd
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": (f"one perturbation pass over one {d}x{d} guided matrix ({t_pass:.2f} s) scaled to {total_params} parameters x 4 passes; "
+                       f"one block ({t_layer:.2f} s) and the vocabulary projection + loss ({t_head:.2f} s) on one {T}-token sequence, "
+                       f"scaled to {cfg.n_layer} blocks x {cfg.batch} sequences x 2 forwards")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg5")
+    ap.add_argument("--gauss-bits", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import zgr_inputs as I
+    from paper_2601_12917_amd import binding as B
+    from tests.util import inputs_of, make_batch_arrays, make_session, session_batch
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2601_12917_amd.build import build
+        build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = I.CONFIGS[args.config]
+    t0 = time.perf_counter()
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    sess = make_session(cfg, specs, values, bases, bits=args.gauss_bits)
+    del values
+    batch = session_batch(sess, cfg, arrays)
+    setup_s = time.perf_counter() - t0
+
+    def one_step(i):
+        lp, lm, g = sess.step(i, batch)
+        sess.apply_update(i, g, cfg.lr)
+        return lp, lm, g
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        sess.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    last = None
+    for i in range(args.steps):
+        last = one_step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = sess.profile_read() if not args.no_profile else {}
+    ms_per_step = 1e3 * elapsed / args.steps
+    steps_per_s = args.steps / elapsed
+
+    es = 4 if cfg.dtype == "f32" else 2
+    guided_elems = sum(s.numel for s in specs if s.guided)
+    flat_elems = sum(s.numel for s in specs if not s.guided)
+    u_bytes = sum(s.rows * cfg.k * 4 for s in specs if s.guided)
+    out = {
+        "metric": "ZGR steps/sec", "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {I.CONFIGS[args.config].n_layer}-layer d={cfg.d_model} decoder, batch {cfg.batch} x seq {cfg.seq}, "
+                               f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns), gauss_bits={args.gauss_bits}"
+                   if cfg.arch != I.ARCH_LINEAR_LSQ else f"{cfg.name}: linear least squares {cfg.lsq_out}x{cfg.lsq_in}",
+                   "params": int(guided_elems + flat_elems), "tokens_per_step": int(cfg.batch * max(cfg.seq, 1))},
+        "tokens_per_s": steps_per_s * cfg.batch * max(cfg.seq, 1),
+        "last_losses": None if last is None else [last[0], last[1], last[2]],
+        "setup_s": setup_s,
+    }
+    if prof:
+        kern = {}
+        for name, (ms, n) in prof.items():
+            if n:
+                kern[name] = {"ms_total": ms, "launches": int(n), "ms_avg": ms / n}
+        out["kernel_ms"] = kern
+        passes = 4 * args.steps
+        # perturbation pass over the guided matrices: read + write every element once, plus one read of U
+        if "perturb_tile" in kern:
+            k1 = kern["perturb_tile"]
+            bytes_per_launch = 2.0 * guided_elems * es + u_bytes
+            gbs = bytes_per_launch / (k1["ms_avg"] * 1e-3) / 1e9
+            out["roofline_perturb"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                       "traffic": None, "kernel": "perturb_tile_kernel", "bytes_per_launch": bytes_per_launch}
+        if "perturb_flat" in kern:
+            k1 = kern["perturb_flat"]
+            gbs = 2.0 * flat_elems * es / (k1["ms_avg"] * 1e-3) / 1e9
+            out["roofline_perturb_flat"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                            "traffic": None, "kernel": "perturb_flat_kernel"}
+        if "gemm" in kern and cfg.arch != I.ARCH_LINEAR_LSQ:
+            gm = kern["gemm"]
+            flops_per_launch = 2.0 * args.steps * forward_gemm_flops(cfg) / gm["launches"]
+            tf = flops_per_launch / (gm["ms_avg"] * 1e-3) / 1e12
+            peak = MFMA_PEAK_TFLOPS[cfg.dtype]
+            gemm_roof = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": None,
+                         "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel", "flops_per_launch": flops_per_launch}
+            out["roofline_gemm"] = gemm_roof
+        # the dominant kernel of the step carries the headline roofline
+        dom = max(kern, key=lambda n: kern[n]["ms_total"])
+        out["roofline"] = {"gemm": out.get("roofline_gemm"), "perturb_tile": out.get("roofline_perturb"),
+                           "perturb_flat": out.get("roofline_perturb_flat")}.get(dom) or out.get("roofline_gemm") or out.get("roofline_perturb")
+        out["dominant_kernel_class"] = dom
+    sess.close()
+    if not args.no_cpu_baseline and cfg.arch == I.ARCH_DECODER_LM:
+        out["cpu_baseline"] = cpu_baseline(cfg, specs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
