@@ -129,81 +129,134 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
     }
 }
 
-// bf16 path: MFMA 32x32x16, 128x128 block tile, BK = 64, 4 waves of 64x64, LDS double buffer.
+// bf16 path: MFMA 32x32x16.  Block tile BM x BN (128 or 256 each), BK = 64, four waves in a 2 x 2 grid,
+// each owning (BM/2) x (BN/2) of the output as FM x FN accumulator fragments of 32 x 32.  Global
+// loads for k-tile t+1 are issued before the MFMAs of tile t and land in the other LDS buffer
+// after them (register-staged double buffering, one barrier per k-tile).
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-constexpr int GB_M = 128, GB_N = 128, GB_K = 64, GB_LD = GB_K + 8;   // row stride 144 B breaks bank conflicts
+constexpr int GB_K = 64, GB_LD = GB_K + 8;   // row stride 144 B: conflict-free 16-byte reads
 
-__global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K, GemmEpi ep) {
+template <int MODE>
+__device__ __forceinline__ void epilogue_bf16(void* out, const bf16_t* bias, int m, int n, int N, float v) {
+  if (bias) v += to_f32(bias[n]);
+  const size_t o = (size_t)m * N + n;
+  if (MODE == EPI_STORE) from_f32(v, reinterpret_cast<bf16_t*>(out)[o]);
+  else if (MODE == EPI_GELU) from_f32(gelu_erf(v), reinterpret_cast<bf16_t*>(out)[o]);
+  else if (MODE == EPI_RESID) reinterpret_cast<float*>(out)[o] += v;
+  else reinterpret_cast<float*>(out)[o] = v;
+}
+
+template <int BM, int BN, int WM, int WN, int MODE>
+__global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K,
+                                                                 void* __restrict__ out, const bf16_t* __restrict__ bias) {
+  constexpr int NT = 64 * WM * WN;
+  constexpr int FM = BM / (32 * WM), FN = BN / (32 * WN);      // 32x32 fragments per wave
+  constexpr int RPP = NT / 8;                                  // rows covered by one pass of 16-byte chunks
+  constexpr int LA = BM / RPP, LW = BN / RPP;                  // chunks per thread per k-tile
   extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(gsm);                       // [2][128][GB_LD]
-  bf16_t* Ws = As + 2 * GB_M * GB_LD;                                // [2][128][GB_LD]
+  bf16_t* As = reinterpret_cast<bf16_t*>(gsm);                 // [2][BM][GB_LD]
+  bf16_t* Ws = As + 2 * BM * GB_LD;                            // [2][BN][GB_LD]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * GB_M, n0 = blockIdx.x * GB_N;
-  // global -> register staging: each thread moves 4 chunks of 16 B per operand per k-tile
-  const int lr = tid >> 3, lc = (tid & 7) * 8;                       // row (0..31) + 32*i, column chunk
-  uint4 ra[4], rw[4];
-  auto gload = [&](int k0) {
+  const int wm = wave / WN, wn = wave % WN;
+  // XCD-aware tile order: consecutive block ids go to different XCDs, so give each XCD a contiguous
+  // band of tiles, which share rows of A and columns of W in that XCD's L2
+  const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM, n_tiles = tiles_m * tiles_n;
+  int bid = blockIdx.x;
+  if (n_tiles % 8 == 0) bid = (bid & 7) * (n_tiles / 8) + (bid >> 3);
+  const int m0 = (bid / tiles_n) * BM, n0 = (bid % tiles_n) * BN;
+  const int lr = tid >> 3, lc = (tid & 7) * 8;
+  uint32_t ao[LA], wo[LW];                                     // element offsets of this thread's chunks
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int r = m0 + lr + 32 * i; r = r < M ? r : M - 1;
-      ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)r * K + k0 + lc);
-      int c = n0 + lr + 32 * i; c = c < N ? c : N - 1;
-      rw[i] = *reinterpret_cast<const uint4*>(W + (size_t)c * K + k0 + lc);
-    }
-  };
-  auto sstore = [&](int buf) {
+  for (int i = 0; i < LA; ++i) { int r = m0 + lr + RPP * i; r = r < M ? r : M - 1; ao[i] = (uint32_t)r * (uint32_t)K + lc; }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<uint4*>(As + (buf * GB_M + lr + 32 * i) * GB_LD + lc) = ra[i];
-      *reinterpret_cast<uint4*>(Ws + (buf * GB_N + lr + 32 * i) * GB_LD + lc) = rw[i];
-    }
-  };
-  f32x16 acc[2][2];
+  for (int i = 0; i < LW; ++i) { int c = n0 + lr + RPP * i; c = c < N ? c : N - 1; wo[i] = (uint32_t)c * (uint32_t)K + lc; }
+  uint4 ra[LA], rw[LW];
+  f32x16 acc[FM][FN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   const int nk = K / GB_K;
-  gload(0);
-  sstore(0);
+#pragma unroll
+  for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4*>(A + ao[i]);
+#pragma unroll
+  for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const uint4*>(W + wo[i]);
+#pragma unroll
+  for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4*>(As + (lr + RPP * i) * GB_LD + lc) = ra[i];
+#pragma unroll
+  for (int i = 0; i < LW; ++i) *reinterpret_cast<uint4*>(Ws + (lr + RPP * i) * GB_LD + lc) = rw[i];
   __syncthreads();
   const int l32 = lane & 31, kg = (lane >> 5) * 8;
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) gload((kt + 1) * GB_K);
+    const int knext = (kt + 1 < nk ? kt + 1 : kt) * GB_K;      // the last iteration reloads its own tile (unused)
+#pragma unroll
+    for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4*>(A + ao[i] + knext);
+#pragma unroll
+    for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const uint4*>(W + wo[i] + knext);
+    const bf16_t* as = As + (buf * BM + wm * (BM / WM) + l32) * GB_LD + kg;
+    const bf16_t* ws = Ws + (buf * BN + wn * (BN / WN) + l32) * GB_LD + kg;
 #pragma unroll
     for (int ks = 0; ks < GB_K; ks += 16) {
-      bf16x8 a[2], b[2];
+      bf16x8 a[FM], b[FN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i] = *reinterpret_cast<const bf16x8*>(As + (buf * GB_M + wm * 64 + i * 32 + l32) * GB_LD + ks + kg);
-        b[i] = *reinterpret_cast<const bf16x8*>(Ws + (buf * GB_N + wn * 64 + i * 32 + l32) * GB_LD + ks + kg);
-      }
+      for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * GB_LD + ks);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < FN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(ws + j * 32 * GB_LD + ks);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) sstore(buf ^ 1);
+    bf16_t* ad = As + ((buf ^ 1) * BM + lr) * GB_LD + lc;
+    bf16_t* wd = Ws + ((buf ^ 1) * BN + lr) * GB_LD + lc;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4*>(ad + RPP * i * GB_LD) = ra[i];
+#pragma unroll
+    for (int i = 0; i < LW; ++i) *reinterpret_cast<uint4*>(wd + RPP * i * GB_LD) = rw[i];
     __syncthreads();
   }
-  // epilogue: lane holds column l32, rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 tile
+  // epilogue: lane holds column l32, rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 fragment
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + l32;
+    for (int j = 0; j < FN; ++j) {
+      const int n = n0 + wn * (BN / WN) + j * 32 + l32;
       if (n >= N) continue;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (m < M) epilogue_store<bf16_t>(ep, m, n, N, acc[i][j][v]);
+        const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (m < M) epilogue_bf16<MODE>(out, bias, m, n, N, acc[i][j][v]);
       }
     }
+}
+
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bias, void* out, int epi, int M, int N, int K, hipStream_t s) {
+  const size_t lds = (size_t)2 * (BM + BN) * GB_LD * sizeof(bf16_t);
+  const int grid = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+#define ZGR_GEMM_LAUNCH(MODE)                                                                                           \
+  {                                                                                                                     \
+    static bool attr_set = false;                                                                                       \
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, MODE>;                                                                 \
+    if (!attr_set) {                                                                                                    \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                                    \
+      attr_set = true;                                                                                                  \
+    }                                                                                                                   \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, s, A, W, M, N, K, out, bias);                         \
+  }
+  switch (epi) {
+    case EPI_STORE: ZGR_GEMM_LAUNCH(EPI_STORE) break;
+    case EPI_GELU:  ZGR_GEMM_LAUNCH(EPI_GELU) break;
+    case EPI_RESID: ZGR_GEMM_LAUNCH(EPI_RESID) break;
+    default:        ZGR_GEMM_LAUNCH(EPI_F32) break;
+  }
+#undef ZGR_GEMM_LAUNCH
+  return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ attention
@@ -340,14 +393,13 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
     hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, s, (const float*)A, (const float*)W, M, N, K, ep);
   } else {
     if (K % GB_K != 0) return hipErrorInvalidValue;
-    const size_t lds = (size_t)2 * (GB_M + GB_N) * GB_LD * sizeof(bf16_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(gemm_bf16_kernel, dim3((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M), dim3(256), lds, s, (const bf16_t*)A, (const bf16_t*)W, M, N, K, ep);
+    const bf16_t* a = (const bf16_t*)A; const bf16_t* w = (const bf16_t*)W; const bf16_t* b = (const bf16_t*)bias;
+    // largest tile that still gives every CU a block
+    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256), t128x256 = (long)((M + 127) / 128) * ((N + 255) / 256);
+    if ((size_t)M * K >= ((size_t)1 << 32) || (size_t)N * K >= ((size_t)1 << 32)) return hipErrorInvalidValue;   // 32-bit element offsets
+    if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4>(a, w, b, out, epi, M, N, K, s);
+    if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4>(a, w, b, out, epi, M, N, K, s);
+    return launch_gemm_bf16_t<128, 128, 2, 2>(a, w, b, out, epi, M, N, K, s);
   }
   return hipGetLastError();
 }
