@@ -51,7 +51,7 @@ struct zgr_ctx {
   std::vector<TensorDesc> descs;
   std::vector<WorkItem> flat, tiles;
   bool lists_dirty = true;
-  int max_k = 0;
+  int max_k = 0, min_k = 0;
   int dtype = 0;
   std::vector<Layer> layers;
   int tok_emb = -1, pos_emb = -1, lnf_g = -1, lnf_b = -1, cls_w = -1, cls_b = -1, lsq_w = -1;
@@ -126,7 +126,7 @@ bool is_guided(const zgr_tensor& t) { return t.U != nullptr && t.k > 0; }
 void build_lists(zgr_ctx* c) {
   const int P = group_size(c->cfg.gauss_bits);
   c->flat.clear(); c->tiles.clear(); c->descs.resize(c->t.size());
-  c->max_k = 0;
+  c->max_k = 0; c->min_k = kMaxK + 1;
   for (size_t i = 0; i < c->t.size(); ++i) {
     const zgr_tensor& t = c->t[i];
     TensorDesc& d = c->descs[i];
@@ -135,6 +135,7 @@ void build_lists(zgr_ctx* c) {
     mix_coefficients(c->cfg, t, &d.a, &d.b);
     append_items(t, (int)i, is_guided(t), P, c->flat, c->tiles);
     if (is_guided(t) && t.k > c->max_k) c->max_k = t.k;
+    if (is_guided(t) && t.k < c->min_k) c->min_k = t.k;
   }
   c->lists_dirty = true;
 }
@@ -265,7 +266,7 @@ PerturbArgs perturb_args(zgr_ctx* c, uint64_t step) {
   a.tiles = reinterpret_cast<const WorkItem*>(c->ws + c->cv.tiles);
   a.n_flat = (int32_t)c->flat.size(); a.n_tiles = (int32_t)c->tiles.size();
   a.k0 = (uint32_t)c->cfg.seed; a.k1 = (uint32_t)(c->cfg.seed >> 32);
-  a.step = (uint32_t)step; a.bits = c->cfg.gauss_bits; a.dtype = c->dtype; a.max_k = c->max_k;
+  a.step = (uint32_t)step; a.bits = c->cfg.gauss_bits; a.dtype = c->dtype; a.max_k = c->max_k; a.min_k = c->min_k;
   return a;
 }
 
@@ -579,7 +580,7 @@ zgr_status zgr_debug_fill_z(zgr_ctx* c, int32_t idx, uint64_t step, float* Z) {
   PerturbArgs a = perturb_args(c, step);
   const WorkItem* dbg = reinterpret_cast<const WorkItem*>(c->ws + c->cv.dbg);
   if (!fl.empty()) { a.flat = dbg; a.n_flat = (int32_t)fl.size(); a.n_tiles = 0; HIP_TRY(c, launch_perturb_flat(a, 0.f, Z, c->stream, c->n_cu)); }
-  else { a.tiles = dbg; a.n_tiles = (int32_t)tl.size(); a.n_flat = 0; a.max_k = c->t[idx].k; HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu)); }
+  else { a.tiles = dbg; a.n_tiles = (int32_t)tl.size(); a.n_flat = 0; a.max_k = a.min_k = c->t[idx].k; HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu)); }
   return ZGR_OK;
 }
 

@@ -41,6 +41,7 @@ struct PerturbArgs {
   int32_t           bits;      // 32 | 16
   int32_t           dtype;
   int32_t           max_k;     // largest k among tiled tensors
+  int32_t           min_k;     // smallest k among tiled tensors
 };
 
 // theta += c * Z for everything in the flat / tile work list.  zout != nullptr:

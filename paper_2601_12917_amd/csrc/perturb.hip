@@ -65,6 +65,30 @@ __global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, float 
 }
 
 // ------------------------------------------------------------------ tile
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kMfmaMinK = 16;      // from this rank on the U R contraction runs on the matrix cores
+
+// One lane's P consecutive elements starting at flat index e0: G from the seed, Z = a G + (b U R), axpy.
+template <typename T, int P, bool WRITE_Z>
+__device__ __forceinline__ void finish_row(const TensorDesc& d, T* __restrict__ th, float* __restrict__ zout, int64_t e0, const float* ur,
+                                           float c, const PerturbArgs& a, const RadiusEntry* tab) {
+  float G[P];
+  gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
+  if (WRITE_Z) {
+#pragma unroll
+    for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], ur[j]);
+  } else {
+    Vec<T, P>* p = reinterpret_cast<Vec<T, P>*>(th + e0);
+    Vec<T, P> x = *p;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      const float z = __builtin_fmaf(d.a, G[j], ur[j]);
+      from_f32(__builtin_fmaf(c, z, to_f32(x.v[j])), x.v[j]);
+    }
+    *p = x;
+  }
+}
+
 // Lane layout inside a wave's 32-row slab: column group cg = lane % 32 owns P
 // consecutive columns; register v of the lane is row 8*(v/4) + 4*(lane/32) + v%4.
 template <typename T, int P, bool WRITE_Z>
@@ -144,27 +168,116 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, float 
             const int vv = vb + v;
             const int rloc = 32 * wave + 8 * (vv >> 2) + 4 * rh + (vv & 3);
             const int64_t row = row0 + r0 + rloc;
-            if (r0 + rloc < nrows && row < d.rows) {
-              const int64_t e0 = row * d.cols + col;
-              float G[P];
-              gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
-              if (WRITE_Z) {
-#pragma unroll
-                for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[v][j]);
-              } else {
-                Vec<T, P>* p = reinterpret_cast<Vec<T, P>*>(th + e0);
-                Vec<T, P> x = *p;
-#pragma unroll
-                for (int j = 0; j < P; ++j) {
-                  const float z = __builtin_fmaf(d.a, G[j], acc[v][j]);
-                  from_f32(__builtin_fmaf(c, z, to_f32(x.v[j])), x.v[j]);
-                }
-                *p = x;
-              }
-            }
+            if (r0 + rloc < nrows && row < d.rows) finish_row<T, P, WRITE_Z>(d, th, zout, row * d.cols + col, acc[v], c, a, tab);
           }
         }
       }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ tile, U R on the matrix cores (k >= 16)
+// fp32 MFMA 32x32x2 with contraction index l = (lane/32)*(kpt/2) + s: a lane reads kpt/2 consecutive
+// floats of its row of U from global memory and one row of the R slice from LDS per step.  The MFMA
+// result layout (lane = column group, register v = row 8*(v/4) + 4*(lane/32) + v%4) is the layout the
+// epilogue works in, so Z never leaves registers.
+template <typename T, int P, bool WRITE_Z, bool FULL>
+__device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const PerturbArgs& a, float c, const RadiusEntry* tab, const float* Rs,
+                                               T* __restrict__ th, float* __restrict__ zout, int64_t row0, int64_t col0, int r0, int nrows,
+                                               int k, int kh, int wave, int cg, int rh) {
+  constexpr int TC = 32 * P;
+  const int mrow = r0 + 32 * wave + cg;
+  const int64_t urow = row0 + mrow;
+  const bool uvalid = FULL || (mrow < nrows && urow < d.rows);
+  const float* up = d.U + urow * d.ldu + rh * kh;
+  const int64_t col = col0 + (int64_t)cg * P;
+  const bool cvalid = FULL || col < d.cols;
+  // this lane's 16 rows of theta: issue the loads first, they fly while the matrix cores work
+  Vec<T, P> x[16];
+  const int64_t ebase = (row0 + r0 + 32 * wave + 4 * rh) * d.cols + col;
+  if (!WRITE_Z) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rl = 8 * (v >> 2) + (v & 3);
+      const bool ok = FULL || (cvalid && r0 + 32 * wave + 4 * rh + rl < nrows && row0 + r0 + 32 * wave + 4 * rh + rl < d.rows);
+      if (ok) x[v] = *reinterpret_cast<const Vec<T, P>*>(th + ebase + (int64_t)rl * d.cols);
+    }
+  }
+  f32x16 acc[P];
+#pragma unroll
+  for (int j = 0; j < P; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+  for (int s0 = 0; s0 < kh; s0 += 4) {
+    float ua[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ua[i] = (uvalid && rh * kh + s0 + i < k) ? up[s0 + i] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float* rrow = Rs + (rh * kh + s0 + i) * TC + cg * P;
+#pragma unroll
+      for (int j = 0; j < P; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(ua[i], rrow[j], acc[j], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int rl = 8 * (v >> 2) + (v & 3);
+    const bool ok = FULL || (cvalid && r0 + 32 * wave + 4 * rh + rl < nrows && row0 + r0 + 32 * wave + 4 * rh + rl < d.rows);
+    if (ok) {
+      const int64_t e0 = ebase + (int64_t)rl * d.cols;
+      float G[P];
+      gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
+      if (WRITE_Z) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[j][v]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+          const float z = __builtin_fmaf(d.a, G[j], acc[j][v]);
+          from_f32(__builtin_fmaf(c, z, to_f32(x[v].v[j])), x[v].v[j]);
+        }
+        *reinterpret_cast<Vec<T, P>*>(th + e0) = x[v];
+      }
+    }
+  }
+}
+
+template <typename T, int P, bool WRITE_Z>
+__global__ void __launch_bounds__(256) perturb_tile_mfma_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
+                                                                float* __restrict__ zout, int kp) {
+  extern __shared__ float smem[];
+  RadiusEntry* tab = reinterpret_cast<RadiusEntry*>(smem);
+  float* Rs = smem + kRadiusTabEntries * 3;          // [kp][TC]
+  constexpr int TC = 32 * P;
+  load_radius_table(tab, gtab);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cg = lane & 31, rh = lane >> 5;
+  for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
+    const WorkItem it = a.tiles[w];
+    const TensorDesc d = a.descs[it.tensor];
+    const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
+    const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kh = kpt >> 1;
+    T* __restrict__ th = reinterpret_cast<T*>(d.theta);
+    __syncthreads();                                 // table loaded / previous tile's readers of Rs done
+    for (int idx = tid; idx < kpt * 32; idx += 256) {
+      const int l = idx >> 5, g = idx & 31;
+      const int64_t col = col0 + (int64_t)g * P;
+      float r[P];
+#pragma unroll
+      for (int j = 0; j < P; ++j) r[j] = 0.f;
+      if (l < k && col < d.cols) {
+        gaussP<P>(philox_call((uint64_t)((int64_t)l * d.cols + col) / P, d.id | 0x80000000u, a.step, a.k0, a.k1), tab, r);
+#pragma unroll
+        for (int j = 0; j < P; ++j) r[j] *= d.b;
+      }
+#pragma unroll
+      for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
+    }
+    __syncthreads();
+    const bool full = (nrows % kTileRowsPerIter == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
+    for (int r0 = 0; r0 < nrows; r0 += kTileRowsPerIter) {
+      if (full) mfma_row_block<T, P, WRITE_Z, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kh, wave, cg, rh);
+      else      mfma_row_block<T, P, WRITE_Z, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kh, wave, cg, rh);
     }
   }
 }
@@ -269,6 +382,17 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
   if (per_cu > 4) per_cu = 4;
   if (per_cu < 1) per_cu = 1;
   const int grid = a.n_tiles < n_cu * per_cu ? a.n_tiles : n_cu * per_cu;
+  if (a.min_k >= kMfmaMinK) {
+    const size_t lds_m = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kp * 32 * P);
+    int per = (int)((160 * 1024) / lds_m);
+    per = per > 3 ? 3 : (per < 1 ? 1 : per);
+    const int grid_m = a.n_tiles < n_cu * per ? a.n_tiles : n_cu * per;
+    auto km = zout ? perturb_tile_mfma_kernel<T, P, true> : perturb_tile_mfma_kernel<T, P, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, c, tab, zout, kp);
+    return hipGetLastError();
+  }
   auto kern = zout ? perturb_tile_kernel<T, P, true> : perturb_tile_kernel<T, P, false>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
