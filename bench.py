@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="cfg5")
     ap.add_argument("--gauss-bits", type=int, default=32)
+    ap.add_argument("--non-guided", action="store_true", help="non-guided round of Algorithm 1: no bases, Z = G for every tensor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
     args = ap.parse_args()
@@ -105,6 +106,10 @@ def main():
     cfg = I.CONFIGS[args.config]
     t0 = time.perf_counter()
     specs, values, bases = inputs_of(cfg)
+    if args.non_guided:
+        bases = [None] * len(bases)
+        for sp in specs:
+            sp.guided = False
     arrays = make_batch_arrays(cfg)
     sess = make_session(cfg, specs, values, bases, bits=args.gauss_bits)
     del values
