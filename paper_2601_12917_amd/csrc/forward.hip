@@ -313,6 +313,131 @@ __global__ void __launch_bounds__(256) attention_kernel(const T* __restrict__ qk
   }
 }
 
+// MFMA attention for bf16 storage and head size 64.  One block = 128 queries of one (batch, head):
+// K [keys][64] and V^T [64][keys] are staged in LDS once; each wave owns 32 queries and walks the keys in
+// blocks of 32, computing S^T = K Q^T and O^T += V^T P^T with v_mfma_f32_32x32x16_bf16.  In the S^T
+// result a lane holds one query column and 16 keys in registers, so the softmax reductions run over
+// registers plus one exchange with the partner lane (lane ^ 32); P goes straight from the accumulator
+// registers into the B operand of the second product (the contraction order of that product is the
+// accumulator's key order, which the V^T operand is read in as well).
+constexpr int AT_LDK = 64 + 8;          // K row stride (bf16): 144 B
+template <int DH>
+__global__ void __launch_bounds__(256) attention_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, const int32_t* __restrict__ lengths,
+                                                             int seq, int d, int n_head, int causal, int kpad) {
+  static_assert(DH == 64, "head size 64");
+  extern __shared__ __attribute__((aligned(16))) unsigned char asm_[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(asm_);                 // [kpad][AT_LDK]
+  bf16_t* Vt = Ks + (size_t)kpad * AT_LDK;                      // [DH][kpad + 8]
+  const int ldv = kpad + 8;
+  const int qblocks = (seq + 127) / 128;
+  const int qb = blockIdx.x % qblocks, h = (blockIdx.x / qblocks) % n_head, b = blockIdx.x / (qblocks * n_head);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int len = lengths ? min(lengths[b], seq) : seq;
+  const size_t ld = (size_t)3 * d;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)h * DH;
+  // keys this block can need, rounded up to 32
+  int kend = len;
+  if (causal) kend = min(kend, qb * 128 + 128);
+  const int kblocks = (kend + 31) / 32;
+  // stage K and V^T (zero beyond seq so masked products stay finite)
+  for (int i = tid; i < kblocks * 32 * 8; i += 256) {
+    const int r = i >> 3, c = (i & 7) * 8;
+    uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+    if (r < seq) {
+      kv = *reinterpret_cast<const uint4*>(base + (size_t)r * ld + d + c);
+      vv = *reinterpret_cast<const uint4*>(base + (size_t)r * ld + 2 * d + c);
+    }
+    *reinterpret_cast<uint4*>(Ks + r * AT_LDK + c) = kv;
+    const uint16_t* ve = reinterpret_cast<const uint16_t*>(&vv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) Vt[(c + j) * ldv + r].bits = ve[j];
+  }
+  // this wave's queries: B operand of S^T = K Q^T, lane (query l32, k-group half) holds Q[q][16 s + 8 half .. +8]
+  const int q0 = qb * 128 + wave * 32;
+  const int qi = q0 + l32;
+  bf16x8 qf[DH / 16];
+#pragma unroll
+  for (int s4 = 0; s4 < DH / 16; ++s4) {
+    uint4 t = make_uint4(0, 0, 0, 0);
+    if (qi < seq) t = *reinterpret_cast<const uint4*>(base + (size_t)qi * ld + s4 * 16 + half * 8);
+    qf[s4] = *reinterpret_cast<bf16x8*>(&t);
+  }
+  __syncthreads();
+  f32x16 o[DH / 32];
+#pragma unroll
+  for (int f = 0; f < DH / 32; ++f)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[f][v] = 0.f;
+  float mx = -INFINITY, lsum = 0.f;
+  const float scale_log2 = 1.44269504088896341f / sqrtf((float)DH);
+  int wave_kblocks = kblocks;
+  if (causal) wave_kblocks = min(kblocks, (q0 + 31) / 32 + 1);
+  if (q0 >= seq) wave_kblocks = 0;
+  for (int kb = 0; kb < wave_kblocks; ++kb) {
+    f32x16 sacc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+    for (int s4 = 0; s4 < DH / 16; ++s4) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + l32) * AT_LDK + s4 * 16 + half * 8);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s4], sacc, 0, 0, 0);
+    }
+    // lane: query qi, keys kb*32 + 8*(v/4) + 4*half + v%4; scores in log2 units
+    float sv[16], mloc = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+      const bool ok = key < len && (!causal || key <= qi);
+      sv[v] = ok ? sacc[v] * scale_log2 : -INFINITY;
+      mloc = fmaxf(mloc, sv[v]);
+    }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float mnew = fmaxf(mx, mloc);
+    const float msafe = mnew == -INFINITY ? 0.f : mnew;
+    const float corr = exp2f(mx - msafe);            // mx = -inf -> 0
+    float psum = 0.f;
+    bf16x8 pf[2];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float pv = exp2f(sv[v] - msafe);
+      psum += pv;
+      bf16_t t; from_f32(pv, t);
+      reinterpret_cast<uint16_t*>(&pf[v >> 3])[v & 7] = t.bits;
+    }
+    lsum = lsum * corr + psum;
+    mx = mnew;
+#pragma unroll
+    for (int f = 0; f < DH / 32; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[f][v] *= corr;
+    // O^T += V^T P^T: A operand lane (dh row 32 f + l32, half) reads the keys in the accumulator's order
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int f = 0; f < DH / 32; ++f) {
+        const bf16_t* vr = Vt + (f * 32 + l32) * ldv + kb * 32 + st * 16 + 4 * half;
+        const uint2 lo = *reinterpret_cast<const uint2*>(vr), hi = *reinterpret_cast<const uint2*>(vr + 8);
+        uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&t), pf[st], o[f], 0, 0, 0);
+      }
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (qi < seq) {
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    bf16_t* orow = ctx + ((size_t)b * seq + qi) * d + (size_t)h * DH;
+#pragma unroll
+    for (int f = 0; f < DH / 32; ++f)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        uint16_t pk[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { bf16_t t; from_f32(o[f][v4 * 4 + i] * inv, t); pk[i] = t.bits; }
+        *reinterpret_cast<uint2*>(orow + f * 32 + 8 * v4 + 4 * half) = *reinterpret_cast<uint2*>(pk);
+      }
+  }
+}
+
 // ------------------------------------------------------------------ losses
 // Cross-entropy of one row of fp32 logits [n]: loss = logsumexp - logit[target]; target < 0: row skipped (loss 0).
 __global__ void __launch_bounds__(256) ce_rows_kernel(const float* __restrict__ logits, const int32_t* __restrict__ targets, float* __restrict__ row_loss,
@@ -419,6 +544,19 @@ static hipError_t launch_attention_t(const T* qkv, T* ctx, const int32_t* length
 }
 
 hipError_t launch_attention(int dtype, const void* qkv, void* ctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal, hipStream_t s) {
+  if (dtype == 1 && d / n_head == 64 && seq <= 512 && d % 8 == 0) {
+    const int kpad = (seq + 31) / 32 * 32;
+    const size_t lds = sizeof(bf16_t) * ((size_t)kpad * AT_LDK + (size_t)64 * (kpad + 8));
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    const int grid = batch * n_head * ((seq + 127) / 128);
+    hipLaunchKernelGGL(attention_mfma_kernel<64>, dim3(grid), dim3(256), lds, s, (const bf16_t*)qkv, (bf16_t*)ctx, lengths, seq, d, n_head, causal, kpad);
+    return hipGetLastError();
+  }
   if (dtype == 0) return launch_attention_t<float>((const float*)qkv, (float*)ctx, lengths, batch, seq, d, n_head, causal, s);
   return launch_attention_t<bf16_t>((const bf16_t*)qkv, (bf16_t*)ctx, lengths, batch, seq, d, n_head, causal, s);
 }
