@@ -195,6 +195,12 @@ zgr_status zgr_debug_last_row_losses(zgr_ctx* ctx, float* out /* HOST */, int64_
 zgr_status zgr_debug_radius_table(int32_t gauss_bits, float* out /* DEVICE */, void* hip_stream);
 zgr_status zgr_debug_cossin_table(int32_t gauss_bits, float* cos_out, float* sin_out /* DEVICE */, void* hip_stream);
 
+/* One linear layer of the forward pass as the library runs it: out = epilogue(A[M,K] W[N,K]^T + bias),
+ * all DEVICE.  dtype: storage type of A, W, bias (bf16 needs K % 64 == 0).  epilogue: 0 store (storage
+ * type), 1 GELU then store, 2 add into fp32 out, 3 store fp32.  bias may be NULL.                       */
+zgr_status zgr_debug_gemm(int32_t dtype, const void* A, const void* W, const void* bias, void* out, int32_t epilogue,
+                          int32_t M, int32_t N, int32_t K, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

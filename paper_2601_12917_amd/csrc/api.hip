@@ -607,4 +607,13 @@ zgr_status zgr_debug_cossin_table(int32_t gauss_bits, float* cos_out, float* sin
   return ZGR_OK;
 }
 
+zgr_status zgr_debug_gemm(int32_t dtype, const void* A, const void* W, const void* bias, void* out, int32_t epilogue,
+                          int32_t M, int32_t N, int32_t K, void* hip_stream) {
+  if (!A || !W || !out) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  if ((dtype != ZGR_F32 && dtype != ZGR_BF16) || epilogue < 0 || epilogue > 3) return fail(nullptr, ZGR_ERR_CONFIG, "bad dtype or epilogue");
+  if (M < 1 || N < 1 || K < 1 || (dtype == ZGR_BF16 && K % 64)) return fail(nullptr, ZGR_ERR_SHAPE, "bad GEMM shape");
+  HIP_TRY(nullptr, launch_gemm(dtype, A, W, bias, out, epilogue, M, N, K, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
 }  // extern "C"

@@ -138,9 +138,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int GB_K = 64, GB_LD = GB_K + 8;   // row stride 144 B: conflict-free 16-byte reads
 
 template <int MODE>
-__device__ __forceinline__ void epilogue_bf16(void* out, const bf16_t* bias, int m, int n, int N, float v) {
-  if (bias) v += to_f32(bias[n]);
-  const size_t o = (size_t)m * N + n;
+__device__ __forceinline__ void epilogue_bf16(void* out, size_t o, float v) {
   if (MODE == EPI_STORE) from_f32(v, reinterpret_cast<bf16_t*>(out)[o]);
   else if (MODE == EPI_GELU) from_f32(gelu_erf(v), reinterpret_cast<bf16_t*>(out)[o]);
   else if (MODE == EPI_RESID) reinterpret_cast<float*>(out)[o] += v;
@@ -159,12 +157,16 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   bf16_t* Ws = As + 2 * BM * GB_LD;                            // [2][BN][GB_LD]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  // XCD-aware tile order: consecutive block ids go to different XCDs, so give each XCD a contiguous
-  // band of tiles, which share rows of A and columns of W in that XCD's L2
-  const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM, n_tiles = tiles_m * tiles_n;
-  int bid = blockIdx.x;
-  if (n_tiles % 8 == 0) bid = (bid & 7) * (n_tiles / 8) + (bid >> 3);
-  const int m0 = (bid / tiles_n) * BM, n0 = (bid % tiles_n) * BN;
+  // XCD-aware tile order.  Consecutive block ids go round-robin to the 8 XCDs, each with its own L2 and
+  // about 32 blocks in flight.  Give XCD x the super-tiles x, x+8, ... of GM x GN = 4 x 8 tiles, walked in
+  // order inside the XCD, so that the blocks resident in one L2 share 4 row panels of A and 8 of W.
+  constexpr int GM = 4, GN = 8;
+  const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
+  const int stn = (tiles_n + GN - 1) / GN;
+  const int local = blockIdx.x >> 3, st = (local / (GM * GN)) * 8 + (blockIdx.x & 7), w = local % (GM * GN);
+  const int tm = (st / stn) * GM + w / GN, tn = (st % stn) * GN + w % GN;
+  if (tm >= tiles_m || tn >= tiles_n) return;
+  const int m0 = tm * BM, n0 = tn * BN;
   const int lr = tid >> 3, lc = (tid & 7) * 8;
   uint32_t ao[LA], wo[LW];                                     // element offsets of this thread's chunks
 #pragma unroll
@@ -197,6 +199,7 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
     for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4*>(A + ao[i] + knext);
 #pragma unroll
     for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const uint4*>(W + wo[i] + knext);
+    __builtin_amdgcn_sched_barrier(0);     // keep the loads of the next k-tile ahead of this tile's matrix work
     const bf16_t* as = As + (buf * BM + wm * (BM / WM) + l32) * GB_LD + kg;
     const bf16_t* ws = Ws + (buf * BN + wn * (BN / WN) + l32) * GB_LD + kg;
 #pragma unroll
@@ -211,6 +214,7 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
     bf16_t* ad = As + ((buf ^ 1) * BM + lr) * GB_LD + lc;
     bf16_t* wd = Ws + ((buf ^ 1) * BN + lr) * GB_LD + lc;
 #pragma unroll
@@ -220,24 +224,42 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
     __syncthreads();
   }
   // epilogue: lane holds column l32, rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 fragment
+  float bv[FN];
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+  for (int j = 0; j < FN; ++j) {
+    const int n = n0 + wn * (BN / WN) + j * 32 + l32;
+    bv[j] = (bias && n < N) ? to_f32(bias[n]) : 0.f;
+  }
+  const int mbase = m0 + wm * (BM / WM) + 4 * (lane >> 5), nbase = n0 + wn * (BN / WN) + l32;
+  if (m0 + BM <= M && n0 + BN <= N) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int n = n0 + wn * (BN / WN) + j * 32 + l32;
-      if (n >= N) continue;
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (m < M) epilogue_bf16<MODE>(out, bias, m, n, N, acc[i][j][v]);
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          epilogue_bf16<MODE>(out, (size_t)(mbase + i * 32 + 8 * (v >> 2) + (v & 3)) * N + nbase + j * 32, acc[i][j][v] + bv[j]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int n = nbase + j * 32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = mbase + i * 32 + 8 * (v >> 2) + (v & 3);
+          if (m < M && n < N) epilogue_bf16<MODE>(out, (size_t)m * N + n, acc[i][j][v] + bv[j]);
+        }
       }
-    }
+  }
 }
 
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bias, void* out, int epi, int M, int N, int K, hipStream_t s) {
   const size_t lds = (size_t)2 * (BM + BN) * GB_LD * sizeof(bf16_t);
-  const int grid = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  // super-tiles of 4 x 8 tiles, rounded up to a multiple of 8 super-tiles (one per XCD)
+  const int stm = ((M + BM - 1) / BM + 3) / 4, stn = ((N + BN - 1) / BN + 7) / 8;
+  const int grid = ((stm * stn + 7) / 8 * 8) * 32;
 #define ZGR_GEMM_LAUNCH(MODE)                                                                                           \
   {                                                                                                                     \
     static bool attr_set = false;                                                                                       \
