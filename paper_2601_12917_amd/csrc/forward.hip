@@ -135,26 +135,59 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 // after them (register-staged double buffering, one barrier per k-tile).
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-constexpr int GB_K = 64, GB_LD = GB_K + 8;   // row stride 144 B: conflict-free 16-byte reads
+constexpr int GB_K = 64;
+
+__device__ __forceinline__ void wait_vmem() {   // all outstanding global -> LDS transfers of this wave have landed
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+}
+
+// erf-GELU with erf from the rational/exponential approximation of Abramowitz & Stegun 7.1.26
+// (|error| <= 1.5e-7 absolute on erf): far below the bf16 rounding of the result.
+__device__ __forceinline__ float gelu_fast(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+  float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+  p = __builtin_fmaf(p, t, 1.421413741f);
+  p = __builtin_fmaf(p, t, -0.284496736f);
+  p = __builtin_fmaf(p, t, 0.254829592f);
+  const float e = p * t * __builtin_amdgcn_exp2f(z * z * -1.44269504088896341f);   // 1 - erf(|x|/sqrt 2)
+  const float half_x = 0.5f * x;
+  return x >= 0.f ? __builtin_fmaf(-half_x, e, x) : half_x * e;     // 0.5 x (1 + erf): x >= 0: x - 0.5 x e; x < 0: 0.5 x e
+}
 
 template <int MODE>
 __device__ __forceinline__ void epilogue_bf16(void* out, size_t o, float v) {
   if (MODE == EPI_STORE) from_f32(v, reinterpret_cast<bf16_t*>(out)[o]);
-  else if (MODE == EPI_GELU) from_f32(gelu_erf(v), reinterpret_cast<bf16_t*>(out)[o]);
+  else if (MODE == EPI_GELU) from_f32(gelu_fast(v), reinterpret_cast<bf16_t*>(out)[o]);
   else if (MODE == EPI_RESID) reinterpret_cast<float*>(out)[o] += v;
   else reinterpret_cast<float*>(out)[o] = v;
 }
 
-template <int BM, int BN, int WM, int WN, int MODE>
+template <int N> __device__ __forceinline__ void wait_vmem_upto() {   // at most N global -> LDS transfers of this wave still in flight
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#endif
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int MODE>
 __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K,
                                                                  void* __restrict__ out, const bf16_t* __restrict__ bias) {
-  constexpr int NT = 64 * WM * WN;
+  constexpr int NW = WM * WN;
   constexpr int FM = BM / (32 * WM), FN = BN / (32 * WN);      // 32x32 fragments per wave
-  constexpr int RPP = NT / 8;                                  // rows covered by one pass of 16-byte chunks
-  constexpr int LA = BM / RPP, LW = BN / RPP;                  // chunks per thread per k-tile
-  extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(gsm);                 // [2][BM][GB_LD]
-  bf16_t* Ws = As + 2 * BM * GB_LD;                            // [2][BN][GB_LD]
+  constexpr int CPR = BK / 8;                                  // 16-byte chunks per LDS row
+  constexpr int RPI = 64 / CPR;                                // rows one global_load_lds instruction fills (1 KiB)
+  constexpr int RPB = 256 / (BK * 2);                          // rows per 256 B of LDS (one sweep over all banks)
+  constexpr int GA = BM / RPI / NW, GW = BN / RPI / NW;        // instructions per wave per k-tile
+  static_assert(GA >= 1 && GW >= 1 && (STAGES - 2) * (GA + GW) < 64, "tile / stage configuration");
+  // LDS: STAGES slabs of [BM + BN][BK] bf16, rows unpadded; the 16-byte chunk c of row r sits in slot
+  // c ^ ((r / RPB) % CPR), which makes the MFMA operand reads conflict-free.  The slabs are written by
+  // global_load_lds (global memory -> LDS without passing registers): one instruction fills RPI rows, lane L
+  // supplying row L / CPR, slot L % CPR, i.e. it fetches the global chunk (L % CPR) ^ swizzle(row).
+  extern __shared__ __attribute__((aligned(1024))) unsigned char gsm[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(gsm);                 // [STAGES][BM][BK]
+  bf16_t* Ws = As + STAGES * BM * BK;                          // [STAGES][BN][BK]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   // XCD-aware tile order.  Consecutive block ids go round-robin to the 8 XCDs, each with its own L2 and
@@ -167,13 +200,21 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   const int tm = (st / stn) * GM + w / GN, tn = (st % stn) * GN + w % GN;
   if (tm >= tiles_m || tn >= tiles_n) return;
   const int m0 = tm * BM, n0 = tn * BN;
-  const int lr = tid >> 3, lc = (tid & 7) * 8;
-  uint32_t ao[LA], wo[LW];                                     // element offsets of this thread's chunks
+  // loader: this lane's source offsets (elements) for the row groups its wave owns
+  const int lrow = lane / CPR, lslot = lane % CPR;
+  uint32_t ao[GA], wo[GW];
 #pragma unroll
-  for (int i = 0; i < LA; ++i) { int r = m0 + lr + RPP * i; r = r < M ? r : M - 1; ao[i] = (uint32_t)r * (uint32_t)K + lc; }
+  for (int g = 0; g < GA; ++g) {
+    const int rl = (wave * GA + g) * RPI + lrow;               // row within the tile
+    int r = m0 + rl; r = r < M ? r : M - 1;
+    ao[g] = (uint32_t)r * (uint32_t)K + ((lslot ^ ((rl / RPB) % CPR)) << 3);
+  }
 #pragma unroll
-  for (int i = 0; i < LW; ++i) { int c = n0 + lr + RPP * i; c = c < N ? c : N - 1; wo[i] = (uint32_t)c * (uint32_t)K + lc; }
-  uint4 ra[LA], rw[LW];
+  for (int g = 0; g < GW; ++g) {
+    const int rl = (wave * GW + g) * RPI + lrow;
+    int c = n0 + rl; c = c < N ? c : N - 1;
+    wo[g] = (uint32_t)c * (uint32_t)K + ((lslot ^ ((rl / RPB) % CPR)) << 3);
+  }
   f32x16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -181,47 +222,47 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  const int nk = K / GB_K;
+  const int nk = K / BK;
+  auto issue = [&](int kt, int buf) {
+#if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll
-  for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4*>(A + ao[i]);
+    for (int g = 0; g < GA; ++g)
+      __builtin_amdgcn_global_load_lds(A + ao[g] + kt * BK, As + (buf * BM + (wave * GA + g) * RPI) * BK, 16, 0, 0);
 #pragma unroll
-  for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const uint4*>(W + wo[i]);
+    for (int g = 0; g < GW; ++g)
+      __builtin_amdgcn_global_load_lds(W + wo[g] + kt * BK, Ws + (buf * BN + (wave * GW + g) * RPI) * BK, 16, 0, 0);
+#endif
+  };
+  // prologue: STAGES - 1 k-tiles in flight
 #pragma unroll
-  for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4*>(As + (lr + RPP * i) * GB_LD + lc) = ra[i];
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < nk) issue(p, p);
+  // reader: lane (l32, half) reads row l32 of each fragment, logical chunk 2*ks + half
+  const int l32 = lane & 31, half = lane >> 5, swz = (l32 / RPB) % CPR;
+  int koff[BK / 16];
 #pragma unroll
-  for (int i = 0; i < LW; ++i) *reinterpret_cast<uint4*>(Ws + (lr + RPP * i) * GB_LD + lc) = rw[i];
-  __syncthreads();
-  const int l32 = lane & 31, kg = (lane >> 5) * 8;
+  for (int ks = 0; ks < BK / 16; ++ks) koff[ks] = ((2 * ks + half) ^ swz) << 3;
+  int buf = 0;
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    const int knext = (kt + 1 < nk ? kt + 1 : kt) * GB_K;      // the last iteration reloads its own tile (unused)
+    // k-tile kt has landed once at most the STAGES - 2 younger tiles are still in flight
+    if (kt + STAGES - 2 < nk) wait_vmem_upto<(STAGES - 2) * (GA + GW)>(); else wait_vmem_upto<0>();
+    __syncthreads();                                           // ... for every wave; and slab (kt - 1) % STAGES is free
+    if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1, buf == 0 ? STAGES - 1 : buf - 1);
+    const bf16_t* as = As + (buf * BM + wm * (BM / WM) + l32) * BK;
+    const bf16_t* ws = Ws + (buf * BN + wn * (BN / WN) + l32) * BK;
 #pragma unroll
-    for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4*>(A + ao[i] + knext);
-#pragma unroll
-    for (int i = 0; i < LW; ++i) rw[i] = *reinterpret_cast<const uint4*>(W + wo[i] + knext);
-    __builtin_amdgcn_sched_barrier(0);     // keep the loads of the next k-tile ahead of this tile's matrix work
-    const bf16_t* as = As + (buf * BM + wm * (BM / WM) + l32) * GB_LD + kg;
-    const bf16_t* ws = Ws + (buf * BN + wn * (BN / WN) + l32) * GB_LD + kg;
-#pragma unroll
-    for (int ks = 0; ks < GB_K; ks += 16) {
+    for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 a[FM], b[FN];
 #pragma unroll
-      for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * GB_LD + ks);
+      for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * BK + koff[ks]);
 #pragma unroll
-      for (int j = 0; j < FN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(ws + j * 32 * GB_LD + ks);
+      for (int j = 0; j < FN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(ws + j * 32 * BK + koff[ks]);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    bf16_t* ad = As + ((buf ^ 1) * BM + lr) * GB_LD + lc;
-    bf16_t* wd = Ws + ((buf ^ 1) * BN + lr) * GB_LD + lc;
-#pragma unroll
-    for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4*>(ad + RPP * i * GB_LD) = ra[i];
-#pragma unroll
-    for (int i = 0; i < LW; ++i) *reinterpret_cast<uint4*>(wd + RPP * i * GB_LD) = rw[i];
-    __syncthreads();
+    buf = buf + 1 == STAGES ? 0 : buf + 1;
   }
   // epilogue: lane holds column l32, rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 fragment
   float bv[FN];
@@ -254,16 +295,16 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK, int STAGES>
 hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bias, void* out, int epi, int M, int N, int K, hipStream_t s) {
-  const size_t lds = (size_t)2 * (BM + BN) * GB_LD * sizeof(bf16_t);
+  const size_t lds = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
   // super-tiles of 4 x 8 tiles, rounded up to a multiple of 8 super-tiles (one per XCD)
   const int stm = ((M + BM - 1) / BM + 3) / 4, stn = ((N + BN - 1) / BN + 7) / 8;
   const int grid = ((stm * stn + 7) / 8 * 8) * 32;
 #define ZGR_GEMM_LAUNCH(MODE)                                                                                           \
   {                                                                                                                     \
     static bool attr_set = false;                                                                                       \
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, MODE>;                                                                 \
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, STAGES, MODE>;                                                                 \
     if (!attr_set) {                                                                                                    \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
       if (e != hipSuccess) return e;                                                                                    \
@@ -544,9 +585,14 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
     // largest tile that still gives every CU a block
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256), t128x256 = (long)((M + 127) / 128) * ((N + 255) / 256);
     if ((size_t)M * K >= ((size_t)1 << 32) || (size_t)N * K >= ((size_t)1 << 32)) return hipErrorInvalidValue;   // 32-bit element offsets
-    if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4>(a, w, b, out, epi, M, N, K, s);
-    if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4>(a, w, b, out, epi, M, N, K, s);
-    return launch_gemm_bf16_t<128, 128, 2, 2>(a, w, b, out, epi, M, N, K, s);
+    // 256 x 256 tiles unless their count leaves the last round of 256 CUs less than ~85 % full and 256 x 192 tiles fill it better
+    const long t192 = (long)((M + 255) / 256) * ((N + 191) / 192);
+    auto fill = [](long t) { const long rounds = (t + 255) / 256; return (double)t / (double)(rounds * 256); };
+    if (t256 >= 256 && (fill(t256) >= 0.85 || fill(t192) <= fill(t256))) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 2>(a, w, b, out, epi, M, N, K, s);
+    if (t192 >= 256 && N % 192 == 0) return launch_gemm_bf16_t<256, 192, 4, 2, 64, 2>(a, w, b, out, epi, M, N, K, s);
+    if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 2>(a, w, b, out, epi, M, N, K, s);
+    if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4, 64, 2>(a, w, b, out, epi, M, N, K, s);
+    return launch_gemm_bf16_t<128, 128, 2, 2, 64, 4>(a, w, b, out, epi, M, N, K, s);
   }
   return hipGetLastError();
 }
