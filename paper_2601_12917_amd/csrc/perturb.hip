@@ -20,9 +20,9 @@ struct bf16_t { uint16_t bits; };
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
 __device__ __forceinline__ void from_f32(float x, float& o) { o = x; }
-__device__ __forceinline__ void from_f32(float x, bf16_t& o) {     // round to nearest, ties to even
-  const uint32_t b = __float_as_uint(x);
-  o.bits = (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+__device__ __forceinline__ void from_f32(float x, bf16_t& o) {     // round to nearest, ties to even (v_cvt_pk_bf16_f32)
+  const __bf16 h = static_cast<__bf16>(x);
+  o.bits = __builtin_bit_cast(uint16_t, h);
 }
 
 template <typename T, int P> struct alignas(sizeof(T) * P <= 16 ? sizeof(T) * P : 16) Vec { T v[P]; };
@@ -177,69 +177,75 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, float 
 }
 
 // ------------------------------------------------------------------ tile, U R on the matrix cores (k >= 16)
-// fp32 MFMA 32x32x2 with contraction index l = (lane/32)*(kpt/2) + s: a lane reads kpt/2 consecutive
-// floats of its row of U from global memory and one row of the R slice from LDS per step.  The MFMA
-// result layout (lane = column group, register v = row 8*(v/4) + 4*(lane/32) + v%4) is the layout the
-// epilogue works in, so Z never leaves registers.
+// fp32 MFMA 16x16x4.  A wave covers 16 rows x 32P columns per step: lane (n = lane % 16, rg = lane / 16)
+// ends up with rows 4 rg + v (v = 0..3) and, in each of the two column groups g, the P consecutive columns
+// g*16P + P n + j -- one Philox call per (row, group) -- so Z never leaves registers and a lane needs only
+// 2P x 4 accumulators.  The contraction index is l = rg * (kpt/4) + s: a lane reads kpt/4 consecutive floats
+// of its row of U from global memory and one row of the R slice from LDS per step.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <typename T, int P, bool WRITE_Z, bool FULL>
 __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const PerturbArgs& a, float c, const RadiusEntry* tab, const float* Rs,
                                                T* __restrict__ th, float* __restrict__ zout, int64_t row0, int64_t col0, int r0, int nrows,
-                                               int k, int kh, int wave, int cg, int rh) {
-  constexpr int TC = 32 * P;
-  const int mrow = r0 + 32 * wave + cg;
-  const int64_t urow = row0 + mrow;
-  const bool uvalid = FULL || (mrow < nrows && urow < d.rows);
-  const float* up = d.U + urow * d.ldu + rh * kh;
-  const int64_t col = col0 + (int64_t)cg * P;
-  const bool cvalid = FULL || col < d.cols;
-  // this lane's 16 rows of theta: issue the loads first, they fly while the matrix cores work
-  Vec<T, P> x[16];
-  const int64_t ebase = (row0 + r0 + 32 * wave + 4 * rh) * d.cols + col;
+                                               int k, int kq4, int wave, int n16, int rg) {
+  constexpr int TC = 32 * P, GC = 16 * P;                     // tile columns, columns per group
+  const int mrow = r0 + 16 * wave + n16;                      // A operand: this lane feeds row (lane % 16) of the slab
+  const bool uvalid = FULL || (mrow < nrows && row0 + mrow < d.rows);
+  const float* up = d.U + (row0 + mrow) * d.ldu + rg * kq4;
+  const int rbase = r0 + 16 * wave + 4 * rg;                  // first of this lane's 4 rows (tile-relative)
+  const int64_t ebase = (row0 + rbase) * d.cols + col0 + (int64_t)P * n16;
+  bool ok[4][2];
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+      ok[v][g] = FULL || (rbase + v < nrows && row0 + rbase + v < d.rows && col0 + g * GC + P * n16 < d.cols);
+  // this lane's 8 vectors of theta: the loads fly while the matrix cores work
+  Vec<T, P> x[4][2];
   if (!WRITE_Z) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int rl = 8 * (v >> 2) + (v & 3);
-      const bool ok = FULL || (cvalid && r0 + 32 * wave + 4 * rh + rl < nrows && row0 + r0 + 32 * wave + 4 * rh + rl < d.rows);
-      if (ok) x[v] = *reinterpret_cast<const Vec<T, P>*>(th + ebase + (int64_t)rl * d.cols);
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int g = 0; g < 2; ++g)
+        if (ok[v][g]) x[v][g] = *reinterpret_cast<const Vec<T, P>*>(th + ebase + (int64_t)v * d.cols + g * GC);
+  }
+  f32x4 acc[2 * P];
+#pragma unroll
+  for (int j = 0; j < 2 * P; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < kq4; s0 += 2) {
+    float ua[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) ua[i] = (uvalid && rg * kq4 + s0 + i < k) ? up[s0 + i] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const float* rrow = Rs + (rg * kq4 + s0 + i) * TC + P * n16;
+#pragma unroll
+      for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+          acc[g * P + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[i], rrow[g * GC + j], acc[g * P + j], 0, 0, 0);
     }
   }
-  f32x16 acc[P];
 #pragma unroll
-  for (int j = 0; j < P; ++j)
+  for (int v = 0; v < 4; ++v)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-  for (int s0 = 0; s0 < kh; s0 += 4) {
-    float ua[4];
+    for (int g = 0; g < 2; ++g)
+      if (ok[v][g]) {
+        const int64_t e0 = ebase + (int64_t)v * d.cols + g * GC;
+        float G[P];
+        gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
+        if (WRITE_Z) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ua[i] = (uvalid && rh * kh + s0 + i < k) ? up[s0 + i] : 0.f;
+          for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
+        } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float* rrow = Rs + (rh * kh + s0 + i) * TC + cg * P;
-#pragma unroll
-      for (int j = 0; j < P; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(ua[i], rrow[j], acc[j], 0, 0, 0);
-    }
-  }
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int rl = 8 * (v >> 2) + (v & 3);
-    const bool ok = FULL || (cvalid && r0 + 32 * wave + 4 * rh + rl < nrows && row0 + r0 + 32 * wave + 4 * rh + rl < d.rows);
-    if (ok) {
-      const int64_t e0 = ebase + (int64_t)rl * d.cols;
-      float G[P];
-      gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
-      if (WRITE_Z) {
-#pragma unroll
-        for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[j][v]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < P; ++j) {
-          const float z = __builtin_fmaf(d.a, G[j], acc[j][v]);
-          from_f32(__builtin_fmaf(c, z, to_f32(x[v].v[j])), x[v].v[j]);
+          for (int j = 0; j < P; ++j) {
+            const float z = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
+            from_f32(__builtin_fmaf(c, z, to_f32(x[v][g].v[j])), x[v][g].v[j]);
+          }
+          *reinterpret_cast<Vec<T, P>*>(th + e0) = x[v][g];
         }
-        *reinterpret_cast<Vec<T, P>*>(th + e0) = x[v];
       }
-    }
-  }
 }
 
 template <typename T, int P, bool WRITE_Z>
@@ -251,12 +257,12 @@ __global__ void __launch_bounds__(256) perturb_tile_mfma_kernel(PerturbArgs a, f
   constexpr int TC = 32 * P;
   load_radius_table(tab, gtab);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int cg = lane & 31, rh = lane >> 5;
+  const int n16 = lane & 15, rg = lane >> 4;
   for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
     const WorkItem it = a.tiles[w];
     const TensorDesc d = a.descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
-    const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kh = kpt >> 1;
+    const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kq4 = kpt >> 2;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
     __syncthreads();                                 // table loaded / previous tile's readers of Rs done
     for (int idx = tid; idx < kpt * 32; idx += 256) {
@@ -274,10 +280,10 @@ __global__ void __launch_bounds__(256) perturb_tile_mfma_kernel(PerturbArgs a, f
       for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
     }
     __syncthreads();
-    const bool full = (nrows % kTileRowsPerIter == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
-    for (int r0 = 0; r0 < nrows; r0 += kTileRowsPerIter) {
-      if (full) mfma_row_block<T, P, WRITE_Z, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kh, wave, cg, rh);
-      else      mfma_row_block<T, P, WRITE_Z, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kh, wave, cg, rh);
+    const bool full = (nrows % 64 == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
+    for (int r0 = 0; r0 < nrows; r0 += 64) {
+      if (full) mfma_row_block<T, P, WRITE_Z, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
+      else      mfma_row_block<T, P, WRITE_Z, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
     }
   }
 }
@@ -326,9 +332,9 @@ __global__ void __launch_bounds__(256) debug_cossin_kernel(int bits, float* __re
     const uint32_t m = bits == 32 ? n : (n << 8);
     const TrigHL t = trig_from_u24(m);
     // the fused kernel multiplies (hi, lo) by the radius; with radius 1 the product is the rounded sum
-    const float one_c = __uint_as_float(0x3F800000u ^ t.csign), one_s = __uint_as_float(0x3F800000u ^ t.ssign);
-    co[n] = __builtin_fmaf(one_c, t.ch, one_c * t.cl);
-    so[n] = __builtin_fmaf(one_s, t.sh, one_s * t.sl);
+    const float one = __uint_as_float(0x3F800000u ^ t.sign);
+    co[n] = __builtin_fmaf(one, t.ch, one * t.cl);
+    so[n] = __builtin_fmaf(one, t.sh, one * t.sl);
   }
 }
 
@@ -385,7 +391,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
   if (a.min_k >= kMfmaMinK) {
     const size_t lds_m = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kp * 32 * P);
     int per = (int)((160 * 1024) / lds_m);
-    per = per > 3 ? 3 : (per < 1 ? 1 : per);
+    per = per > 8 ? 8 : (per < 1 ? 1 : per);
     const int grid_m = a.n_tiles < n_cu * per ? a.n_tiles : n_cu * per;
     auto km = zout ? perturb_tile_mfma_kernel<T, P, true> : perturb_tile_mfma_kernel<T, P, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);

@@ -80,8 +80,9 @@ __device__ __forceinline__ float radius_from_odd24(uint32_t N, const RadiusEntry
   return __builtin_fmaf(d, 0.5f * r, rho0);
 }
 
-// cos(2 pi v), sin(2 pi v) for v = m * 2^-24, as (hi, lo) pairs and sign masks.
-struct TrigHL { float ch, cl, sh, sl; uint32_t csign, ssign; };
+// cos(2 pi v), sin(2 pi v) for v = m * 2^-24 as (hi, lo) pairs, up to the common sign `sign`
+// (0 or 0x80000000) that the caller folds into the radius.
+struct TrigHL { float ch, cl, sh, sl; uint32_t sign; };
 
 __device__ __forceinline__ TrigHL trig_from_u24(uint32_t m) {
 #pragma clang fp contract(off)
@@ -107,14 +108,13 @@ __device__ __forceinline__ TrigHL trig_from_u24(uint32_t m) {
   g = __builtin_fmaf(y2, g, y2l * C1h);
   const float ch = __builtin_fmaf(y2, C1h, 1.0f);
   const float cl = __builtin_fmaf(y2, C1h, 1.0f - ch) + g;
-  // quadrant q = bits 22..23 of mp: odd -> swap; cos negative for q in {1,2}, sin negative for q in {2,3}
+  // quadrant q = bits 22..23 of mp: (cos, sin) = R(q * 90 deg) (c, s).  Odd q rotates by a quarter turn,
+  // (c, s) -> (-s, c); q >= 2 negates both, which is left to the caller as one sign on the radius.
   const bool odd = (mp >> 22) & 1u;
   TrigHL o;
-  o.ch = odd ? sh : ch;  o.cl = odd ? sl : cl;
-  o.sh = odd ? ch : sh;  o.sl = odd ? cl : sl;
-  const uint32_t t = mp << 8;                    // bit 23 -> bit 31
-  o.ssign = t & 0x80000000u;
-  o.csign = (t ^ (t << 1)) & 0x80000000u;
+  o.ch = odd ? -sh : ch;  o.cl = odd ? -sl : cl;
+  o.sh = odd ? ch : sh;   o.sl = odd ? cl : sl;
+  o.sign = (mp << 8) & 0x80000000u;                // bit 23 -> bit 31
   return o;
 }
 
@@ -123,10 +123,9 @@ __device__ __forceinline__ void box_muller(uint32_t N, uint32_t m, const RadiusE
 #pragma clang fp contract(off)
   const float rho = radius_from_odd24(N, tab);
   const TrigHL t = trig_from_u24(m);
-  const float rc = __uint_as_float(__float_as_uint(rho) ^ t.csign);
-  const float rs = __uint_as_float(__float_as_uint(rho) ^ t.ssign);
-  g_cos = __builtin_fmaf(rc, t.ch, rc * t.cl);
-  g_sin = __builtin_fmaf(rs, t.sh, rs * t.sl);
+  const float r = __uint_as_float(__float_as_uint(rho) ^ t.sign);
+  g_cos = __builtin_fmaf(r, t.ch, r * t.cl);
+  g_sin = __builtin_fmaf(r, t.sh, r * t.sl);
 }
 
 // Four Gaussians of one Philox call (32-bit mode): pairs from words (0,1) and (2,3).
