@@ -194,21 +194,6 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
   const float* up = d.U + (row0 + mrow) * d.ldu + rg * kq4;
   const int rbase = r0 + 16 * wave + 4 * rg;                  // first of this lane's 4 rows (tile-relative)
   const int64_t ebase = (row0 + rbase) * d.cols + col0 + (int64_t)P * n16;
-  bool ok[4][2];
-#pragma unroll
-  for (int v = 0; v < 4; ++v)
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-      ok[v][g] = FULL || (rbase + v < nrows && row0 + rbase + v < d.rows && col0 + g * GC + P * n16 < d.cols);
-  // this lane's 8 vectors of theta: the loads fly while the matrix cores work
-  Vec<T, P> x[4][2];
-  if (!WRITE_Z) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v)
-#pragma unroll
-      for (int g = 0; g < 2; ++g)
-        if (ok[v][g]) x[v][g] = *reinterpret_cast<const Vec<T, P>*>(th + ebase + (int64_t)v * d.cols + g * GC);
-  }
   f32x4 acc[2 * P];
 #pragma unroll
   for (int j = 0; j < 2 * P; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -230,8 +215,10 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
   for (int v = 0; v < 4; ++v)
 #pragma unroll
     for (int g = 0; g < 2; ++g)
-      if (ok[v][g]) {
+      if (FULL || (rbase + v < nrows && row0 + rbase + v < d.rows && col0 + g * GC + P * n16 < d.cols)) {
         const int64_t e0 = ebase + (int64_t)v * d.cols + g * GC;
+        Vec<T, P> xv;
+        if (!WRITE_Z) xv = *reinterpret_cast<const Vec<T, P>*>(th + e0);
         float G[P];
         gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
         if (WRITE_Z) {
@@ -241,15 +228,15 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
 #pragma unroll
           for (int j = 0; j < P; ++j) {
             const float z = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
-            from_f32(__builtin_fmaf(c, z, to_f32(x[v][g].v[j])), x[v][g].v[j]);
+            from_f32(__builtin_fmaf(c, z, to_f32(xv.v[j])), xv.v[j]);
           }
-          *reinterpret_cast<Vec<T, P>*>(th + e0) = x[v][g];
+          *reinterpret_cast<Vec<T, P>*>(th + e0) = xv;
         }
       }
 }
 
 template <typename T, int P, bool WRITE_Z>
-__global__ void __launch_bounds__(256) perturb_tile_mfma_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) perturb_tile_mfma_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
                                                                 float* __restrict__ zout, int kp) {
   extern __shared__ float smem[];
   RadiusEntry* tab = reinterpret_cast<RadiusEntry*>(smem);
@@ -391,7 +378,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
   if (a.min_k >= kMfmaMinK) {
     const size_t lds_m = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kp * 32 * P);
     int per = (int)((160 * 1024) / lds_m);
-    per = per > 8 ? 8 : (per < 1 ? 1 : per);
+    per = per > 5 ? 5 : (per < 1 ? 1 : per);
     const int grid_m = a.n_tiles < n_cu * per ? a.n_tiles : n_cu * per;
     auto km = zout ? perturb_tile_mfma_kernel<T, P, true> : perturb_tile_mfma_kernel<T, P, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);
