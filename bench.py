@@ -19,8 +19,20 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+COPY_BYTES = 1 << 30
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_hbm_traffic.json")
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def load_traffic():
+    """HBM bytes per launch from the committed counter runs, or {} when the kernels changed since."""
+    try:
+        from paper_2601_12917_amd.build import source_digest
+        rec = json.load(open(TRAFFIC_FILE))
+        return rec["kernels"] if rec.get("source_digest") == source_digest() else {}
+    except Exception:
+        return {}
 
 
 def forward_gemm_flops(cfg):
@@ -28,6 +40,15 @@ def forward_gemm_flops(cfg):
     M, d, ff = cfg.batch * cfg.seq, cfg.d_model, cfg.d_ff
     per_layer = 2.0 * M * (4 * d * d + 2 * d * ff)
     return cfg.n_layer * per_layer + 2.0 * M * d * cfg.vocab
+
+
+def kernel_traffic(traffic, prefix):
+    """Measured HBM bytes (fetch + write) per launch, averaged over the kernels whose name starts with prefix."""
+    sel = [v for k, v in traffic.items() if k.startswith(prefix)]
+    n = sum(v["launches"] for v in sel)
+    if not n:
+        return None
+    return sum((v["fetch_bytes"] + v["write_bytes"]) * v["launches"] for v in sel) / n
 
 
 def cpu_baseline(cfg, specs, budget_note=True):
@@ -87,6 +108,7 @@ def main():
     ap.add_argument("--gauss-bits", type=int, default=32)
     ap.add_argument("--non-guided", action="store_true", help="non-guided round of Algorithm 1: no bases, Z = G for every tensor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run the plain 1 GiB copy kernel that HBM traffic counters are scaled by")
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -134,6 +156,14 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = sess.profile_read() if not args.no_profile else {}
+    if args.calibrate_copy:
+        src = torch.zeros(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            B.check(B.lib().zgr_debug_copy(dst.data_ptr(), src.data_ptr(), COPY_BYTES, torch.cuda.current_stream().cuda_stream))
+        torch.cuda.synchronize()
+        del src, dst
+    traffic = load_traffic()
     ms_per_step = 1e3 * elapsed / args.steps
     steps_per_s = args.steps / elapsed
 
@@ -166,18 +196,19 @@ def main():
             bytes_per_launch = 2.0 * guided_elems * es + u_bytes
             gbs = bytes_per_launch / (k1["ms_avg"] * 1e-3) / 1e9
             out["roofline_perturb"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                                       "traffic": None, "kernel": "perturb_tile_kernel", "bytes_per_launch": bytes_per_launch}
+                                       "traffic": kernel_traffic(traffic, "perturb_tile"), "kernel": "perturb_tile_mfma_kernel" if cfg.k >= 16 else "perturb_tile_kernel",
+                                       "bytes_per_launch": bytes_per_launch}
         if "perturb_flat" in kern:
             k1 = kern["perturb_flat"]
             gbs = 2.0 * flat_elems * es / (k1["ms_avg"] * 1e-3) / 1e9
             out["roofline_perturb_flat"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                                            "traffic": None, "kernel": "perturb_flat_kernel"}
+                                            "traffic": kernel_traffic(traffic, "perturb_flat"), "kernel": "perturb_flat_kernel"}
         if "gemm" in kern and cfg.arch != I.ARCH_LINEAR_LSQ:
             gm = kern["gemm"]
             flops_per_launch = 2.0 * args.steps * forward_gemm_flops(cfg) / gm["launches"]
             tf = flops_per_launch / (gm["ms_avg"] * 1e-3) / 1e12
             peak = MFMA_PEAK_TFLOPS[cfg.dtype]
-            gemm_roof = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": None,
+            gemm_roof = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": kernel_traffic(traffic, "gemm_"),
                          "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel", "flops_per_launch": flops_per_launch}
             out["roofline_gemm"] = gemm_roof
         # the dominant kernel of the step carries the headline roofline

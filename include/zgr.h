@@ -201,6 +201,10 @@ zgr_status zgr_debug_cossin_table(int32_t gauss_bits, float* cos_out, float* sin
 zgr_status zgr_debug_gemm(int32_t dtype, const void* A, const void* W, const void* bias, void* out, int32_t epilogue,
                           int32_t M, int32_t N, int32_t K, void* hip_stream);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16) by a simple kernel: the known-size
+ * reference that hardware traffic counters are calibrated against.                                      */
+zgr_status zgr_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

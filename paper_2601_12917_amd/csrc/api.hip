@@ -616,4 +616,11 @@ zgr_status zgr_debug_gemm(int32_t dtype, const void* A, const void* W, const voi
   return ZGR_OK;
 }
 
+zgr_status zgr_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  if (bytes % 16 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return fail(nullptr, ZGR_ERR_SHAPE, "size and pointers must be multiples of 16 bytes");
+  HIP_TRY(nullptr, launch_debug_copy(dst, src, bytes, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
 }  // extern "C"

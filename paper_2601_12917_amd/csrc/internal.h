@@ -56,6 +56,7 @@ hipError_t launch_debug_philox(const uint32_t* ctr, uint32_t k0, uint32_t k1, ui
 hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t id_stream, int bits, int64_t first, int64_t n,
                               float* out, hipStream_t s);
 hipError_t launch_debug_radius_table(int bits, float* out, hipStream_t s);
+hipError_t launch_debug_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_debug_cossin_table(int bits, float* c, float* sn, hipStream_t s);
 
 }  // namespace zgr

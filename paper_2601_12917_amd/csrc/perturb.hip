@@ -325,6 +325,10 @@ __global__ void __launch_bounds__(256) debug_cossin_kernel(int bits, float* __re
   }
 }
 
+__global__ void __launch_bounds__(256) copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 // The table lives in static device memory: the library allocates nothing.
 __device__ RadiusEntry g_radius_table[kRadiusTabEntries];
 
@@ -411,6 +415,12 @@ hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipSt
   if (e != hipSuccess) return e;
   if (a.dtype == 0) return a.bits == 32 ? launch_tile_t<float, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<float, 8>(a, c, zout, s, n_cu, tab);
   return a.bits == 32 ? launch_tile_t<bf16_t, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<bf16_t, 8>(a, c, zout, s, n_cu, tab);
+}
+
+hipError_t launch_debug_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_kernel, dim3(256 * 8), dim3(256), 0, s, reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), bytes / 16);
+  return hipGetLastError();
 }
 
 hipError_t launch_debug_philox(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out, int64_t n, hipStream_t s) {
