@@ -319,10 +319,18 @@ zgr_status forward_loss(zgr_ctx* c, const zgr_batch* b, int slot) {
   { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, c->lnf_g), T(c, c->lnf_b), h, M, d, m.ln_eps, s)); }
   if (lm) {
     int32_t* tgt = reinterpret_cast<int32_t*>(ws + c->cv.targets);
-    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, c->tok_emb), nullptr, logits, EPI_F32, M, m.vocab, d, s)); }
-    { ProfScope ps(c, ZGR_K_LOSS);
-      HIP_TRY(c, launch_lm_targets(tok, tgt, M, b->seq, s));
+    { ProfScope ps(c, ZGR_K_LOSS); HIP_TRY(c, launch_lm_targets(tok, tgt, M, b->seq, m.vocab, s)); }
+    if (dt == ZGR_BF16) {
+      // the logits region holds the cross-entropy partials and, behind them, the target logits
+      float* tlogit = logits + (size_t)2 * ce_partials_per_row(m.vocab) * M;
+      ProfScope ps(c, ZGR_K_GEMM);
+      HIP_TRY(c, launch_gemm_ce_bf16(h, T(c, c->tok_emb), tgt, logits, tlogit, row_loss, M, m.vocab, d, s));
+    } else {
+      { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, c->tok_emb), nullptr, logits, EPI_F32, M, m.vocab, d, s)); }
+      ProfScope ps(c, ZGR_K_LOSS);
       HIP_TRY(c, launch_ce_rows(logits, tgt, row_loss, M, m.vocab, s));
+    }
+    { ProfScope ps(c, ZGR_K_LOSS);
       HIP_TRY(c, launch_mean_f64(row_loss, M, 1.0 / ((double)b->batch * (b->seq - 1)), loss_dev, s)); }
     c->last_rows = M;
   } else {

@@ -165,6 +165,15 @@ __device__ __forceinline__ void epilogue_bf16(void* out, size_t o, float v) {
   else reinterpret_cast<float*>(out)[o] = v;
 }
 
+// Bare workgroup barrier.  __syncthreads() also fences memory, which makes the compiler drain every
+// outstanding global -> LDS transfer (vmcnt(0)) and so serialises a multi-stage pipeline; the main loop
+// orders its LDS traffic itself (wait_vmem_upto before the barrier, data-dependent waits on its own reads).
+__device__ __forceinline__ void block_barrier() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_s_barrier();
+#endif
+}
+
 template <int N> __device__ __forceinline__ void wait_vmem_upto() {   // at most N global -> LDS transfers of this wave still in flight
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -173,7 +182,8 @@ template <int N> __device__ __forceinline__ void wait_vmem_upto() {   // at most
 
 template <int BM, int BN, int WM, int WN, int BK, int STAGES, int MODE>
 __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K,
-                                                                 void* __restrict__ out, const bf16_t* __restrict__ bias) {
+                                                                 void* __restrict__ out, const bf16_t* __restrict__ bias,
+                                                                 const int32_t* __restrict__ targets, float* __restrict__ tlogit) {
   constexpr int NW = WM * WN;
   constexpr int FM = BM / (32 * WM), FN = BN / (32 * WN);      // 32x32 fragments per wave
   constexpr int CPR = BK / 8;                                  // 16-byte chunks per LDS row
@@ -246,7 +256,7 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   for (int kt = 0; kt < nk; ++kt) {
     // k-tile kt has landed once at most the STAGES - 2 younger tiles are still in flight
     if (kt + STAGES - 2 < nk) wait_vmem_upto<(STAGES - 2) * (GA + GW)>(); else wait_vmem_upto<0>();
-    __syncthreads();                                           // ... for every wave; and slab (kt - 1) % STAGES is free
+    block_barrier();                                           // ... for every wave; and slab (kt - 1) % STAGES is free
     if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1, buf == 0 ? STAGES - 1 : buf - 1);
     const bf16_t* as = As + (buf * BM + wm * (BM / WM) + l32) * BK;
     const bf16_t* ws = Ws + (buf * BN + wn * (BN / WN) + l32) * BK;
@@ -263,6 +273,42 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
         for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     buf = buf + 1 == STAGES ? 0 : buf + 1;
+  }
+  if (MODE == EPI_CE) {
+    // Cross-entropy partials instead of logits.  The product is taken transposed (rows = vocabulary entries,
+    // columns = tokens), so a lane holds one token per fragment column and FM x 16 vocabulary rows of it in
+    // registers: the maximum and the sum of exp(logit - max) over the wave's BM / WM vocabulary rows reduce
+    // over registers plus one exchange with the partner lane (lane ^ 32).  Written to out as
+    // float2 [tokens][tiles_m * WM]; the lane that meets the target row stores its logit.
+    float2* part = reinterpret_cast<float2*>(out);
+    const int pstride = tiles_m * WM, pcol = tm * WM + wm;
+    const int rbase = m0 + wm * (BM / WM) + 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int token = n0 + wn * (BN / WN) + j * 32 + l32;
+      const int tgt = token < N ? targets[token] : -1;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
+          if (r < M) { mx = fmaxf(mx, acc[i][j][v]); if (r == tgt) tlogit[token] = acc[i][j][v]; }
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float msafe = mx == -INFINITY ? 0.f : mx;            // a strip entirely beyond the vocabulary contributes (-inf, 0)
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = rbase + i * 32 + 8 * (v >> 2) + (v & 3);
+          if (r < M) sum += __builtin_amdgcn_exp2f((acc[i][j][v] - msafe) * 1.44269504088896341f);
+        }
+      sum += __shfl_xor(sum, 32, 64);
+      if (lane < 32 && token < N) part[(size_t)token * pstride + pcol] = make_float2(mx, sum);
+    }
+    return;
   }
   // epilogue: lane holds column l32, rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 fragment
   float bv[FN];
@@ -296,7 +342,8 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int STAGES>
-hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bias, void* out, int epi, int M, int N, int K, hipStream_t s) {
+hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bias, void* out, int epi, int M, int N, int K, hipStream_t s,
+                              const int32_t* targets = nullptr, float* tlogit = nullptr) {
   const size_t lds = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
   // super-tiles of 4 x 8 tiles, rounded up to a multiple of 8 super-tiles (one per XCD)
   const int stm = ((M + BM - 1) / BM + 3) / 4, stn = ((N + BN - 1) / BN + 7) / 8;
@@ -310,12 +357,13 @@ hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bi
       if (e != hipSuccess) return e;                                                                                    \
       attr_set = true;                                                                                                  \
     }                                                                                                                   \
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, s, A, W, M, N, K, out, bias);                         \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, s, A, W, M, N, K, out, bias, targets, tlogit);        \
   }
   switch (epi) {
     case EPI_STORE: ZGR_GEMM_LAUNCH(EPI_STORE) break;
     case EPI_GELU:  ZGR_GEMM_LAUNCH(EPI_GELU) break;
     case EPI_RESID: ZGR_GEMM_LAUNCH(EPI_RESID) break;
+    case EPI_CE:    ZGR_GEMM_LAUNCH(EPI_CE) break;
     default:        ZGR_GEMM_LAUNCH(EPI_F32) break;
   }
 #undef ZGR_GEMM_LAUNCH
@@ -520,10 +568,29 @@ __global__ void __launch_bounds__(256) ce_rows_kernel(const float* __restrict__ 
   if (threadIdx.x == 0) row_loss[m] = logf(s) + mx - row[tgt];
 }
 
+// Combines the cross-entropy partials of one row: loss = log(sum_i s_i exp(m_i - M)) + M - logit[target].
+__global__ void __launch_bounds__(256) ce_combine_kernel(const float2* __restrict__ part, int n_part, const int32_t* __restrict__ targets,
+                                                         const float* __restrict__ tlogit, float* __restrict__ row_loss) {
+  __shared__ float red[4];
+  const int m = blockIdx.x;
+  if (targets[m] < 0) { if (threadIdx.x == 0) row_loss[m] = 0.f; return; }
+  const float2* row = part + (size_t)m * n_part;
+  float mx = -INFINITY;
+  for (int i = threadIdx.x; i < n_part; i += 256) mx = fmaxf(mx, row[i].x);
+  mx = block_max(mx, red);
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n_part; i += 256) s += row[i].y * expf(row[i].x - mx);
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) row_loss[m] = logf(s) + mx - tlogit[m];
+}
+
 // next-token targets: row m = b*seq + t predicts tok[m+1] for t < seq-1, else -1
-__global__ void lm_targets_kernel(const int32_t* __restrict__ tok, int32_t* __restrict__ tgt, int M, int seq) {
+__global__ void lm_targets_kernel(const int32_t* __restrict__ tok, int32_t* __restrict__ tgt, int M, int seq, int vocab) {
   const int m = blockIdx.x * blockDim.x + threadIdx.x;
-  if (m < M) tgt[m] = (m % seq) < seq - 1 ? tok[m + 1] : -1;
+  if (m >= M) return;
+  int t = -1;
+  if ((m % seq) < seq - 1) { t = tok[m + 1]; t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t); }   // same clamp as the embedding
+  tgt[m] = t;
 }
 
 // mean of n_rows losses (ignoring the skipped ones by dividing by `count`), accumulated in fp64
@@ -597,6 +664,19 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
   return hipGetLastError();
 }
 
+// Vocabulary projection fused with the row-wise cross-entropy (bf16 storage): logits are never stored.
+// part: float2 scratch of ce_partials_per_row(N) entries per row; tlogit: float [M].
+int ce_partials_per_row(int N) { return ((N + 255) / 256) * 2; }
+
+hipError_t launch_gemm_ce_bf16(const void* A, const void* W, const int32_t* targets, void* part, float* tlogit, float* row_loss, int M, int N, int K, hipStream_t s) {
+  if (K % GB_K != 0 || (size_t)M * K >= ((size_t)1 << 32) || (size_t)N * K >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  // transposed product: the kernel's rows are the N vocabulary entries, its columns the M tokens
+  hipError_t e = launch_gemm_bf16_t<256, 256, 2, 4, 64, 2>((const bf16_t*)W, (const bf16_t*)A, nullptr, part, EPI_CE, N, M, K, s, targets, tlogit);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(ce_combine_kernel, dim3(M), dim3(256), 0, s, (const float2*)part, ce_partials_per_row(N), targets, tlogit, row_loss);
+  return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t launch_attention_t(const T* qkv, T* ctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal, hipStream_t s) {
   const int dh = d / n_head;
@@ -631,8 +711,8 @@ hipError_t launch_attention(int dtype, const void* qkv, void* ctx, const int32_t
 
 bool attention_head_dim_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh == 64; }
 
-hipError_t launch_lm_targets(const int32_t* tok, int32_t* tgt, int M, int seq, hipStream_t s) {
-  hipLaunchKernelGGL(lm_targets_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tok, tgt, M, seq);
+hipError_t launch_lm_targets(const int32_t* tok, int32_t* tgt, int M, int seq, int vocab, hipStream_t s) {
+  hipLaunchKernelGGL(lm_targets_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tok, tgt, M, seq, vocab);
   return hipGetLastError();
 }
 
