@@ -110,6 +110,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run the plain 1 GiB copy kernel that HBM traffic counters are scaled by")
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
+    ap.add_argument("--profile-every", type=int, default=5,
+                    help="HIP events bracket every kernel launch on one timed step in this many (two event records per "
+                         "launch cost about 8 %% of a step, so they are sampled inside the timed region rather than kept on)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
@@ -146,13 +149,23 @@ def main():
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
+    lib = B.lib()
+    every = max(1, args.profile_every)
+    profiled_steps = 0
     if not args.no_profile:
-        sess.profile_enable(True)
+        sess.profile_enable(True)          # clears the totals
+        lib.zgr_profile_pause(sess.ctx, 1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     last = None
     for i in range(args.steps):
+        sample = (not args.no_profile) and (i % every == every - 1 or args.steps < every and i == args.steps - 1)
+        if sample:
+            lib.zgr_profile_pause(sess.ctx, 0)
+            profiled_steps += 1
         last = one_step(args.warmup + i)
+        if sample:
+            lib.zgr_profile_pause(sess.ctx, 1)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = sess.profile_read() if not args.no_profile else {}
@@ -181,7 +194,7 @@ def main():
                    "params": int(guided_elems + flat_elems), "tokens_per_step": int(cfg.batch * max(cfg.seq, 1))},
         "tokens_per_s": steps_per_s * cfg.batch * max(cfg.seq, 1),
         "last_losses": None if last is None else [last[0], last[1], last[2]],
-        "setup_s": setup_s,
+        "setup_s": setup_s, "profiled_steps": profiled_steps,
     }
     if prof:
         kern = {}
@@ -189,7 +202,6 @@ def main():
             if n:
                 kern[name] = {"ms_total": ms, "launches": int(n), "ms_avg": ms / n}
         out["kernel_ms"] = kern
-        passes = 4 * args.steps
         # perturbation pass over the guided matrices: read + write every element once, plus one read of U
         if "perturb_tile" in kern:
             k1 = kern["perturb_tile"]
@@ -205,7 +217,7 @@ def main():
                                             "traffic": kernel_traffic(traffic, "perturb_flat"), "kernel": "perturb_flat_kernel"}
         if "gemm" in kern and cfg.arch != I.ARCH_LINEAR_LSQ:
             gm = kern["gemm"]
-            flops_per_launch = 2.0 * args.steps * forward_gemm_flops(cfg) / gm["launches"]
+            flops_per_launch = 2.0 * profiled_steps * forward_gemm_flops(cfg) / gm["launches"]
             tf = flops_per_launch / (gm["ms_avg"] * 1e-3) / 1e12
             peak = MFMA_PEAK_TFLOPS[cfg.dtype]
             gemm_roof = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": kernel_traffic(traffic, "gemm_"),

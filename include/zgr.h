@@ -175,6 +175,9 @@ typedef enum { ZGR_K_PERTURB_TILE = 0 /* guided matrices */, ZGR_K_PERTURB_FLAT 
                ZGR_K_COUNT = 7 } zgr_kernel_class;
 /* Enables (1) / disables (0) event recording around every launch and clears the totals. */
 zgr_status zgr_profile_enable(zgr_ctx* ctx, int32_t on);
+/* Suspends (1) / resumes (0) event recording without clearing the totals or synchronising: lets a caller
+ * time a sample of its steps, since two event records per launch are not free.                          */
+zgr_status zgr_profile_pause(zgr_ctx* ctx, int32_t paused);
 /* Synchronises the stream and returns accumulated milliseconds and launch
  * counts per zgr_kernel_class since zgr_profile_enable (HOST arrays of ZGR_K_COUNT). */
 zgr_status zgr_profile_read(zgr_ctx* ctx, double* ms, int64_t* launches);

@@ -58,6 +58,7 @@ SYMBOLS = {
     "zgr_destroy": (None, [C.c_void_p]),
     "zgr_last_error": (C.c_char_p, [C.c_void_p]),
     "zgr_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "zgr_profile_pause": (C.c_int, [C.c_void_p, C.c_int32]),
     "zgr_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "zgr_debug_philox": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p, C.c_int64, C.c_void_p]),
     "zgr_debug_gauss": (C.c_int, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),

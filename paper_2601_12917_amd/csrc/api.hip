@@ -34,7 +34,7 @@ struct Carve {                 // workspace layout (byte offsets)
 };
 
 struct Prof {
-  bool on = false;
+  bool on = false, paused = false;
   std::vector<hipEvent_t> ev;          // pairs
   std::vector<int> cls;
   size_t used = 0;                     // pairs in flight
@@ -232,7 +232,7 @@ struct ProfScope {
   zgr_ctx* c; bool live = false; size_t slot = 0;
   ProfScope(zgr_ctx* ctx, int cls) : c(ctx) {
     Prof& p = c->prof;
-    if (!p.on) return;
+    if (!p.on || p.paused) return;
     if ((p.used + 1) * 2 > p.ev.size()) {
       if (p.ev.size() >= 16384) { (void)hipStreamSynchronize(c->stream); prof_harvest(c); }
       else {
@@ -541,6 +541,13 @@ zgr_status zgr_profile_enable(zgr_ctx* c, int32_t on) {
   c->prof.used = 0;
   for (int i = 0; i < ZGR_K_COUNT; ++i) { c->prof.ms[i] = 0; c->prof.n[i] = 0; }
   c->prof.on = on != 0;
+  c->prof.paused = false;
+  return ZGR_OK;
+}
+
+zgr_status zgr_profile_pause(zgr_ctx* c, int32_t paused) {
+  if (!c) return ZGR_ERR_NULL;
+  c->prof.paused = paused != 0;
   return ZGR_OK;
 }
 

@@ -16,9 +16,9 @@ struct bf16_t { uint16_t bits; };
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
 __device__ __forceinline__ void from_f32(float x, float& o) { o = x; }
-__device__ __forceinline__ void from_f32(float x, bf16_t& o) {
-  const uint32_t b = __float_as_uint(x);
-  o.bits = (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+__device__ __forceinline__ void from_f32(float x, bf16_t& o) {     // round to nearest, ties to even (v_cvt_pk_bf16_f32)
+  const __bf16 h = static_cast<__bf16>(x);
+  o.bits = __builtin_bit_cast(uint16_t, h);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -75,6 +75,50 @@ __global__ void __launch_bounds__(256) layernorm_kernel(const float* __restrict_
   const float rstd = 1.0f / sqrtf(block_sum(v, red) / d + eps);
   T* o = out + (size_t)blockIdx.x * d;
   for (int i = threadIdx.x; i < d; i += 256) from_f32((row[i] - mu) * rstd * to_f32(g[i]) + to_f32(b[i]), o[i]);
+}
+
+// Row held in registers (d % 4 == 0, d <= 8192): one read of x, float4 loads, packed stores.
+template <typename T>
+__global__ void __launch_bounds__(256) layernorm_reg_kernel(const float* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
+                                                            T* __restrict__ out, int d, float eps) {
+  __shared__ float red[4];
+  constexpr int MAXV = 8;
+  const float4* row = reinterpret_cast<const float4*>(x + (size_t)blockIdx.x * d);
+  const int nv = d >> 2;
+  float4 v[MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int i = threadIdx.x + 256 * j;
+    v[j] = i < nv ? row[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+  }
+  const float mu = block_sum(s, red) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int i = threadIdx.x + 256 * j;
+    if (i < nv) {
+      const float a0 = v[j].x - mu, a1 = v[j].y - mu, a2 = v[j].z - mu, a3 = v[j].w - mu;
+      q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(block_sum(q, red) / d + eps);
+  T* o = out + (size_t)blockIdx.x * d;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int i = threadIdx.x + 256 * j;
+    if (i < nv) {
+      struct alignas(sizeof(T) * 4) V4 { T e[4]; };
+      const V4 gg = *reinterpret_cast<const V4*>(g + 4 * i), bb = *reinterpret_cast<const V4*>(b + 4 * i);
+      V4 r;
+      from_f32((v[j].x - mu) * rstd * to_f32(gg.e[0]) + to_f32(bb.e[0]), r.e[0]);
+      from_f32((v[j].y - mu) * rstd * to_f32(gg.e[1]) + to_f32(bb.e[1]), r.e[1]);
+      from_f32((v[j].z - mu) * rstd * to_f32(gg.e[2]) + to_f32(bb.e[2]), r.e[2]);
+      from_f32((v[j].w - mu) * rstd * to_f32(gg.e[3]) + to_f32(bb.e[3]), r.e[3]);
+      *reinterpret_cast<V4*>(o + 4 * i) = r;
+    }
+  }
 }
 
 // ------------------------------------------------------------------ GEMM  C = A W^T (+bias) with epilogues
@@ -637,6 +681,11 @@ hipError_t launch_embed(int dtype, const int32_t* tok, const void* E, const void
 }
 
 hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s) {
+  if (d % 4 == 0 && d <= 8192 && (((uintptr_t)g | (uintptr_t)b | (uintptr_t)out) & 15) == 0) {
+    if (dtype == 0) hipLaunchKernelGGL(layernorm_reg_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps);
+    else            hipLaunchKernelGGL(layernorm_reg_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps);
+    return hipGetLastError();
+  }
   if (dtype == 0) hipLaunchKernelGGL(layernorm_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps);
   else            hipLaunchKernelGGL(layernorm_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps);
   return hipGetLastError();
