@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run the plain 1 GiB copy kernel that HBM traffic counters are scaled by")
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
+    ap.add_argument("--no-fused-line", action="store_true",
+                    help="skip the second, shorter measurement with config.fuse_restore_update = 1 (three passes over the parameters per step)")
     ap.add_argument("--profile-every", type=int, default=5,
                     help="HIP events bracket every kernel launch on one timed step in this many (two event records per "
                          "launch cost about 8 %% of a step, so they are sampled inside the timed region rather than kept on)")
@@ -137,7 +139,6 @@ def main():
             sp.guided = False
     arrays = make_batch_arrays(cfg)
     sess = make_session(cfg, specs, values, bases, bits=args.gauss_bits)
-    del values
     batch = session_batch(sess, cfg, arrays)
     setup_s = time.perf_counter() - t0
 
@@ -229,6 +230,25 @@ def main():
                            "perturb_flat": out.get("roofline_perturb_flat")}.get(dom) or out.get("roofline_gemm") or out.get("roofline_perturb")
         out["dominant_kernel_class"] = dom
     sess.close()
+    del sess, batch
+    if not args.no_fused_line:
+        # the same step with the restoring pass and the update fused into one pass (3 instead of 4 passes over theta);
+        # reported beside the headline value, which keeps the client block and the edge-server update separate
+        fs = make_session(cfg, specs, values, bases, bits=args.gauss_bits, fuse_lr=cfg.lr)
+        fb = session_batch(fs, cfg, arrays)
+        for i in range(max(1, args.warmup)):
+            fs.step(i, fb)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fs.step(args.warmup + i, fb)
+        torch.cuda.synchronize()
+        fe = time.perf_counter() - t0
+        out["fused_restore_update"] = {"value": args.steps / fe, "unit": "steps/s", "ms_per_step": 1e3 * fe / args.steps,
+                                       "passes_over_parameters": 3}
+        fs.close()
+        del fs, fb
+    del values
     if not args.no_cpu_baseline and cfg.arch == I.ARCH_DECODER_LM:
         out["cpu_baseline"] = cpu_baseline(cfg, specs)
     print(json.dumps(out))

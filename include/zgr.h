@@ -104,6 +104,10 @@ typedef struct {
   float    alpha;          /* mixing ratio alpha in [0, 1] (weight of the isotropic term)      */
   int32_t  scale_mode;     /* zgr_scale_mode                                                   */
   int32_t  gauss_bits;     /* 32: 4 Gaussians per Philox call; 16: 8 per call                  */
+  int32_t  fuse_restore_update; /* 0: zgr_step restores theta, zgr_apply_update updates it (two passes);
+                                 * 1: zgr_step's last pass does both at once, theta <- theta + (eps - lr g) Z,
+                                 *    with the client's own g of Eq. (11) (single client, weight 1)            */
+  float    lr;             /* learning rate eta of the fused last pass; ignored when fuse_restore_update = 0  */
 } zgr_config;
 
 /* One mini-batch x_i.  All DEVICE.
@@ -150,7 +154,12 @@ zgr_status zgr_set_basis(zgr_ctx* ctx, int32_t tensor_index, const float* U, int
  * tensors in place by +eps Z, evaluate L+, by -2 eps Z, evaluate L-, restore by
  * +eps Z, Z regenerated from (seed, step) in each pass.  Fills *out.  On
  * return the parameters hold their pre-step values up to rounding of the
- * storage type.  ZGR_ERR_NONFINITE still restores the parameters.              */
+ * storage type.  ZGR_ERR_NONFINITE still restores the parameters.
+ * With config.fuse_restore_update = 1 the last pass adds (eps - lr g) Z instead
+ * (both products in fp32: c = fl(eps - fl(lr g))), which leaves the parameters
+ * updated as restore + zgr_apply_update(step, g, lr) would, with one rounding
+ * of the storage type fewer; zgr_apply_update must then not be called for this
+ * step.  A non-finite loss still restores (adds eps Z) and updates nothing.     */
 zgr_status zgr_step(zgr_ctx* ctx, uint64_t step, const zgr_batch* batch, zgr_result* out);
 
 /* Edge-server block of Algorithm 1 for one client with weight 1:

@@ -56,16 +56,21 @@ class ZgrOracle:
         return self.loss_fn({t.name: t.theta.astype(np.float64) for t in self.tensors})
 
     # -- Algorithm 1 ----------------------------------------------------------
-    def step(self, step: int):
+    def step(self, step: int, fuse_lr=None):
         """Client block.  Returns (L+, L-, g) with g = (L+ - L-)/(2 eps) as fp32;
-        leaves theta restored (to rounding)."""
+        leaves theta restored (to rounding).  With a learning rate fuse_lr the
+        restoring pass and the update of Algorithm 1 (theta - lr g Z) are one
+        pass with the fp32 coefficient eps - lr g, each product rounded to fp32."""
         eps = self.eps
         self.axpy_all(step, eps)
         lp = self.loss()
         self.axpy_all(step, np.float32(-2.0) * eps)
         lm = self.loss()
-        self.axpy_all(step, eps)
         g = np.float32((lp - lm) / (2.0 * np.float64(eps)))
+        if fuse_lr is None:
+            self.axpy_all(step, eps)
+        else:
+            self.axpy_all(step, np.float32(eps - np.float32(np.float32(fuse_lr) * g)))
         return lp, lm, g
 
     def apply_update(self, step: int, g, lr):

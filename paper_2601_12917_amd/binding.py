@@ -34,7 +34,7 @@ class zgr_model(C.Structure):
 
 class zgr_config(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("eps", C.c_float), ("alpha", C.c_float), ("scale_mode", C.c_int32),
-                ("gauss_bits", C.c_int32)]
+                ("gauss_bits", C.c_int32), ("fuse_restore_update", C.c_int32), ("lr", C.c_float)]
 
 
 class zgr_batch(C.Structure):

@@ -161,6 +161,8 @@ zgr_status check_config(zgr_ctx* c, const zgr_config& cfg) {
   if (!(cfg.alpha >= 0.f && cfg.alpha <= 1.f)) return fail(c, ZGR_ERR_CONFIG, "alpha must lie in [0, 1]");
   if (cfg.scale_mode != ZGR_SCALE_UNIT && cfg.scale_mode != ZGR_SCALE_PAPER) return fail(c, ZGR_ERR_CONFIG, "unknown scale_mode");
   if (cfg.gauss_bits != 32 && cfg.gauss_bits != 16) return fail(c, ZGR_ERR_CONFIG, "gauss_bits must be 32 or 16");
+  if (cfg.fuse_restore_update != 0 && cfg.fuse_restore_update != 1) return fail(c, ZGR_ERR_CONFIG, "fuse_restore_update must be 0 or 1");
+  if (cfg.fuse_restore_update && !std::isfinite(cfg.lr)) return fail(c, ZGR_ERR_CONFIG, "lr must be finite");
   return ZGR_OK;
 }
 
@@ -506,16 +508,28 @@ zgr_status zgr_step(zgr_ctx* c, uint64_t step, const zgr_batch* b, zgr_result* o
   st = forward_loss(c, b, 0);
   zgr_status st2 = perturb_pass(c, step, -2.0f * eps);                        // W - eps Z
   if (st == ZGR_OK && st2 == ZGR_OK) st = forward_loss(c, b, 1);
-  zgr_status st3 = perturb_pass(c, step, eps);                                // restore
-  if (st == ZGR_OK) st = st2 != ZGR_OK ? st2 : st3;
-  if (st != ZGR_OK) return st;
+  const bool fuse = c->cfg.fuse_restore_update != 0;
+  zgr_status st3 = ZGR_OK;
+  if (!fuse || st != ZGR_OK || st2 != ZGR_OK) {
+    st3 = perturb_pass(c, step, eps);                                         // restore
+    if (st == ZGR_OK) st = st2 != ZGR_OK ? st2 : st3;
+    if (st != ZGR_OK) return st;
+  }
   HIP_TRY(c, hipMemcpyAsync(c->host_loss, c->ws + c->cv.loss, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
-  if (c->prof.on) prof_harvest(c);
   out->loss_plus = c->host_loss[0];
   out->loss_minus = c->host_loss[1];
   out->g = (float)((out->loss_plus - out->loss_minus) / (2.0 * (double)eps));
-  if (!std::isfinite(out->loss_plus) || !std::isfinite(out->loss_minus)) return fail(c, ZGR_ERR_NONFINITE, "a loss is not finite (L+ = %g, L- = %g)", out->loss_plus, out->loss_minus);
+  const bool finite = std::isfinite(out->loss_plus) && std::isfinite(out->loss_minus);
+  if (fuse) {
+    // restore and update in one pass: + eps Z - lr g Z; a non-finite loss only restores
+    const float lg = c->cfg.lr * out->g;
+    const float coef = finite ? eps - lg : eps;
+    if ((st = perturb_pass(c, step, coef)) != ZGR_OK) return st;
+    if (c->prof.on) HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  if (c->prof.on) prof_harvest(c);
+  if (!finite) return fail(c, ZGR_ERR_NONFINITE, "a loss is not finite (L+ = %g, L- = %g)", out->loss_plus, out->loss_minus);
   return ZGR_OK;
 }
 

@@ -27,6 +27,28 @@ __device__ __forceinline__ void from_f32(float x, bf16_t& o) {     // round to n
 
 template <typename T, int P> struct alignas(sizeof(T) * P <= 16 ? sizeof(T) * P : 16) Vec { T v[P]; };
 
+// theta pointers come out of descriptors in memory, so the compiler cannot know that they point to global
+// memory and would emit FLAT accesses (which also tie up the LDS counter); say so explicitly.
+template <typename V> __device__ __forceinline__ V load_global(const void* p) {
+  typedef uint32_t R __attribute__((ext_vector_type(sizeof(V) / 4)));
+  typedef const R __attribute__((address_space(1))) GR;
+  const R r = *reinterpret_cast<GR*>(reinterpret_cast<uintptr_t>(p));
+  V v;
+  __builtin_memcpy(&v, &r, sizeof(V));
+  return v;
+}
+template <> __device__ __forceinline__ float load_global<float>(const void* p) {
+  typedef const float __attribute__((address_space(1))) GF;
+  return *reinterpret_cast<GF*>(reinterpret_cast<uintptr_t>(p));
+}
+template <typename V> __device__ __forceinline__ void store_global(void* p, const V& v) {
+  typedef uint32_t R __attribute__((ext_vector_type(sizeof(V) / 4)));
+  typedef R __attribute__((address_space(1))) GR;
+  R r;
+  __builtin_memcpy(&r, &v, sizeof(V));
+  *reinterpret_cast<GR*>(reinterpret_cast<uintptr_t>(p)) = r;
+}
+
 template <int P> __device__ __forceinline__ void gaussP(const u32x4 w, const RadiusEntry* tab, float* g);
 template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss4(w, tab, g); }
 template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
@@ -51,11 +73,10 @@ __global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, float 
       if (WRITE_Z) {
         for (int j = 0; j < P; ++j) if (e0 + j < n) zout[e0 + j] = G[j];
       } else if (e0 + P <= n) {
-        Vec<T, P>* p = reinterpret_cast<Vec<T, P>*>(th + e0);
-        Vec<T, P> x = *p;
+        Vec<T, P> x = load_global<Vec<T, P>>(th + e0);
 #pragma unroll
         for (int j = 0; j < P; ++j) from_f32(__builtin_fmaf(c, G[j], to_f32(x.v[j])), x.v[j]);
-        *p = x;
+        store_global(th + e0, x);
       } else {
         for (int j = 0; j < P; ++j)
           if (e0 + j < n) { T x = th[e0 + j]; from_f32(__builtin_fmaf(c, G[j], to_f32(x)), x); th[e0 + j] = x; }
@@ -78,14 +99,13 @@ __device__ __forceinline__ void finish_row(const TensorDesc& d, T* __restrict__ 
 #pragma unroll
     for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], ur[j]);
   } else {
-    Vec<T, P>* p = reinterpret_cast<Vec<T, P>*>(th + e0);
-    Vec<T, P> x = *p;
+    Vec<T, P> x = load_global<Vec<T, P>>(th + e0);
 #pragma unroll
     for (int j = 0; j < P; ++j) {
       const float z = __builtin_fmaf(d.a, G[j], ur[j]);
       from_f32(__builtin_fmaf(c, z, to_f32(x.v[j])), x.v[j]);
     }
-    *p = x;
+    store_global(th + e0, x);
   }
 }
 
@@ -200,7 +220,7 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
   for (int s0 = 0; s0 < kq4; s0 += 2) {
     float ua[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) ua[i] = (uvalid && rg * kq4 + s0 + i < k) ? up[s0 + i] : 0.f;
+    for (int i = 0; i < 2; ++i) ua[i] = (uvalid && rg * kq4 + s0 + i < k) ? load_global<float>(up + s0 + i) : 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const float* rrow = Rs + (rg * kq4 + s0 + i) * TC + P * n16;
@@ -218,7 +238,7 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
       if (FULL || (rbase + v < nrows && row0 + rbase + v < d.rows && col0 + g * GC + P * n16 < d.cols)) {
         const int64_t e0 = ebase + (int64_t)v * d.cols + g * GC;
         Vec<T, P> xv;
-        if (!WRITE_Z) xv = *reinterpret_cast<const Vec<T, P>*>(th + e0);
+        if (!WRITE_Z) xv = load_global<Vec<T, P>>(th + e0);
         float G[P];
         gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
         if (WRITE_Z) {
@@ -230,7 +250,7 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
             const float z = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
             from_f32(__builtin_fmaf(c, z, to_f32(xv.v[j])), xv.v[j]);
           }
-          *reinterpret_cast<Vec<T, P>*>(th + e0) = xv;
+          store_global(th + e0, xv);
         }
       }
 }

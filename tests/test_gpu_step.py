@@ -116,6 +116,38 @@ def test_step_and_update_match_oracle(cfg, bits):
     sess.close()
 
 
+@pytest.mark.parametrize("cfg", [I.CONFIGS["cfg1"], I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS], ids=lambda c: c.name)
+def test_fused_restore_update_matches_oracle(cfg):
+    """zgr_step with fuse_restore_update = 1: the last pass adds (eps - lr g) Z.  Each side uses its own g
+    (it cannot be injected), so the parameter bound carries lr |Z| |g - g_oracle| on top of the usual one."""
+    lr = cfg.lr if cfg.dtype == "f32" else 1e-4        # large enough to move bf16 weights
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays))
+    sess = make_session(cfg, specs, values, bases, fuse_lr=lr)
+    batch = session_batch(sess, cfg, arrays)
+    for step in range(2):
+        before = [t.theta.copy() for t in o.tensors]
+        lp, lm, g = sess.step(step, batch)
+        olp, olm, og = o.step(step, fuse_lr=lr)
+        assert abs(lp - olp) <= LOSS_RTOL[cfg.dtype] * abs(olp) and abs(lm - olm) <= LOSS_RTOL[cfg.dtype] * abs(olm)
+        moved = 0
+        for i, t in enumerate(o.tensors):
+            z = np.abs(o.z_of(t, step))
+            got = sess.get_theta(i)
+            slack = lr * z * abs(g - og)
+            if cfg.dtype == "f32":
+                assert np.all(np.abs(got - t.theta) <= PARAM_RTOL["f32"] * (np.abs(t.theta) + PARAM_SCALE) + slack), t.name
+            else:
+                mag = np.abs(t.theta) + np.float32(cfg.eps) * z
+                # the device's own g shifts the pre-rounding value by slack: allow that plus one bf16 ulp of it
+                assert np.all(np.abs(got - t.theta) <= PARAM_RTOL["bf16"] * mag + 1.01 * slack + 1e-30), t.name
+            moved += int(np.sum(t.theta != before[i]))
+            t.theta = got.copy()
+        assert moved > 0 and og != 0
+    sess.close()
+
+
 def test_cfg2_full_trajectory_with_own_g():
     """20 steps of cfg2 driven by the device's own g; the deviation from the oracle's trajectory is
     bounded by lr |Z| |dL_err| / (2 eps) per step and reported."""

@@ -65,6 +65,41 @@ def test_step_restores_parameters_fp32_and_bf16():
     assert np.mean(after == before) > 0.3
 
 
+def test_fused_restore_update_equals_restore_then_update():
+    """One pass with eps - lr g equals the restoring pass followed by the update: in fp32 to rounding,
+    and against the exact theta0 - lr g Z it is at least as close as the two-pass sequence."""
+    lr = 1e-2
+    a, _, _ = _cfg1_oracle()
+    b, _, _ = _cfg1_oracle()
+    theta0 = a.tensors[0].theta.astype(np.float64)
+    lp, lm, g = a.step(5)
+    a.apply_update(5, g, lr)
+    lp2, lm2, g2 = b.step(5, fuse_lr=lr)
+    assert (lp, lm, g) == (lp2, lm2, g2) and g != 0
+    Z = a.z_of(a.tensors[0], 5).astype(np.float64)
+    exact = theta0 - np.float64(np.float32(lr) * g) * Z
+    scale = np.spacing(np.maximum(np.abs(theta0) + 1e-3 * np.abs(Z), np.abs(exact)).astype(np.float32))
+    # storage roundings (three against two) plus, fused, the rounding of the coefficient eps - lr g
+    assert np.all(np.abs(a.tensors[0].theta - exact) <= 3 * scale)
+    assert np.all(np.abs(b.tensors[0].theta - exact) <= 3 * scale)
+    # a wrong sign of the lr g term would move theta the other way
+    assert np.sum((b.tensors[0].theta - theta0) * (-g * Z)) > 0
+    # bf16 storage: same statement with bf16 spacing
+    ab, _, _ = _cfg1_oracle(dtype="bf16"); bb, _, _ = _cfg1_oracle(dtype="bf16")
+    for o in (ab, bb):
+        o.tensors[0].theta = P.bf16_round(o.tensors[0].theta)
+    t0 = ab.tensors[0].theta.astype(np.float64)
+    _, _, gb = ab.step(5); ab.apply_update(5, gb, lr)
+    _, _, gb2 = bb.step(5, fuse_lr=lr)
+    assert gb == gb2
+    Zb = ab.z_of(ab.tensors[0], 5).astype(np.float64)
+    exact = t0 - np.float64(np.float32(lr) * gb) * Zb
+    mag = np.maximum(np.abs(t0) + 1e-3 * np.abs(Zb), np.abs(exact))
+    assert np.all(np.abs(bb.tensors[0].theta - exact) <= 3.1 * 2.0 ** -8 * mag)
+    assert np.abs(bb.tensors[0].theta - exact).mean() <= np.abs(ab.tensors[0].theta - exact).mean()
+    assert np.array_equal(bb.tensors[0].theta.view(np.uint32) & 0xFFFF, np.zeros(t0.shape, np.uint32))
+
+
 def test_update_is_collinear_with_z():
     o, _, _ = _cfg1_oracle()
     before = o.tensors[0].theta.astype(np.float64)

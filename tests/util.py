@@ -39,7 +39,7 @@ def make_batch_arrays(cfg, data_seed=0):
     return {"x": tok, "y": I.make_labels(cfg, data_seed), "lengths": I.make_lengths(cfg, data_seed, lo=min(32, max(1, cfg.seq // 8)))}
 
 
-def make_session(cfg, specs, values, bases, bits=32, scale_mode=None, arch=None):
+def make_session(cfg, specs, values, bases, bits=32, scale_mode=None, arch=None, fuse_lr=None):
     from paper_2601_12917_amd.session import ParamSpec, Session
     params = [ParamSpec(s.name, s.role, s.layer, s.tensor_id, v, u, cfg.k if u is not None else 0)
               for s, v, u in zip(specs, values, bases)]
@@ -48,7 +48,7 @@ def make_session(cfg, specs, values, bases, bits=32, scale_mode=None, arch=None)
                    cfg.scale_mode if scale_mode is None else scale_mode, bits,
                    n_layer=cfg.n_layer, d_model=cfg.d_model, n_head=cfg.n_head, d_ff=cfg.d_ff, vocab=cfg.vocab,
                    max_pos=cfg.max_pos, n_class=cfg.n_class, ln_eps=cfg.ln_eps,
-                   max_batch=max(cfg.batch, 1), max_seq=max(cfg.seq, 2), pack_after=pack)
+                   max_batch=max(cfg.batch, 1), max_seq=max(cfg.seq, 2), pack_after=pack, fuse_lr=fuse_lr)
 
 
 def session_batch(sess, cfg, arrays):
