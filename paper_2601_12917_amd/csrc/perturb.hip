@@ -53,27 +53,34 @@ template <int P> __device__ __forceinline__ void gaussP(const u32x4 w, const Rad
 template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss4(w, tab, g); }
 template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
 
+// The work list and the tensor descriptors are separate __restrict__ kernel parameters (besides being members
+// of PerturbArgs): only then can the compiler tell that the stores to theta do not change them, and fetch them
+// with scalar loads.  Fetched through the struct they become vector loads behind an s_waitcnt vmcnt(0), which
+// drains every outstanding load and store of the wave once per work item.
 // ------------------------------------------------------------------ flat
 template <typename T, int P, bool WRITE_Z>
-__global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
-                                                           float* __restrict__ zout) {
+__global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
+                                                           float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout) {
   __shared__ RadiusEntry tab[kRadiusTabEntries];
   load_radius_table(tab, gtab);
   __syncthreads();
   for (int w = blockIdx.x; w < a.n_flat; w += gridDim.x) {
-    const WorkItem it = a.flat[w];
-    const TensorDesc d = a.descs[it.tensor];
+    const WorkItem it = items[w];
+    const TensorDesc d = descs[it.tensor];
     const int64_t n = d.rows * d.cols;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
     for (int g = threadIdx.x; g < it.count; g += 256) {
       const int64_t q = it.first + g;
       const int64_t e0 = q * P;
+      // the load goes out ahead of the generator's arithmetic, which then covers its latency
+      const bool whole = !WRITE_Z && e0 + P <= n;
+      Vec<T, P> x;
+      if (whole) x = load_global<Vec<T, P>>(th + e0);
       float G[P];
       gaussP<P>(philox_call((uint64_t)q, d.id, a.step, a.k0, a.k1), tab, G);
       if (WRITE_Z) {
         for (int j = 0; j < P; ++j) if (e0 + j < n) zout[e0 + j] = G[j];
-      } else if (e0 + P <= n) {
-        Vec<T, P> x = load_global<Vec<T, P>>(th + e0);
+      } else if (whole) {
 #pragma unroll
         for (int j = 0; j < P; ++j) from_f32(__builtin_fmaf(c, G[j], to_f32(x.v[j])), x.v[j]);
         store_global(th + e0, x);
@@ -112,8 +119,8 @@ __device__ __forceinline__ void finish_row(const TensorDesc& d, T* __restrict__ 
 // Lane layout inside a wave's 32-row slab: column group cg = lane % 32 owns P
 // consecutive columns; register v of the lane is row 8*(v/4) + 4*(lane/32) + v%4.
 template <typename T, int P, bool WRITE_Z>
-__global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
-                                                           float* __restrict__ zout, int kp) {
+__global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
+                                                           float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout, int kp) {
   extern __shared__ float smem[];
   RadiusEntry* tab = reinterpret_cast<RadiusEntry*>(smem);
   float* Us = smem + kRadiusTabEntries * 3;          // [128][kp]
@@ -125,8 +132,8 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, float 
   const int cg = lane & 31, rh = lane >> 5;
 
   for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
-    const WorkItem it = a.tiles[w];
-    const TensorDesc d = a.descs[it.tensor];
+    const WorkItem it = items[w];
+    const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
     const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
@@ -256,8 +263,8 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
 }
 
 template <typename T, int P, bool WRITE_Z>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) perturb_tile_mfma_kernel(PerturbArgs a, float c, const RadiusEntry* __restrict__ gtab,
-                                                                float* __restrict__ zout, int kp) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) perturb_tile_mfma_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
+                                                                float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout, int kp) {
   extern __shared__ float smem[];
   RadiusEntry* tab = reinterpret_cast<RadiusEntry*>(smem);
   float* Rs = smem + kRadiusTabEntries * 3;          // [kp][TC]
@@ -266,8 +273,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, rg = lane >> 4;
   for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
-    const WorkItem it = a.tiles[w];
-    const TensorDesc d = a.descs[it.tensor];
+    const WorkItem it = items[w];
+    const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
     const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kq4 = kpt >> 2;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
@@ -384,36 +391,46 @@ hipError_t ensure_radius_table(const RadiusEntry** dev_ptr) {
 }
 
 namespace {
+// Resident blocks of 256 threads per CU for a persistent kernel: the grid is sized to what the register and
+// LDS budget really admits, because a block that has to wait for a slot would start its share of the work
+// list only after another block has finished all of its own.
+template <typename K>
+int resident_blocks_per_cu(K kern, size_t dyn_lds, int cap) {
+  int nb = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 256, dyn_lds) != hipSuccess || nb < 1) nb = 1;
+  return nb < cap ? nb : cap;
+}
+
 template <typename T, int P>
 hipError_t launch_flat_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
-  const int grid = a.n_flat < n_cu * 8 ? a.n_flat : n_cu * 8;
-  if (zout) hipLaunchKernelGGL((perturb_flat_kernel<T, P, true>), dim3(grid), dim3(256), 0, s, a, c, tab, zout);
-  else      hipLaunchKernelGGL((perturb_flat_kernel<T, P, false>), dim3(grid), dim3(256), 0, s, a, c, tab, zout);
+  auto kern = zout ? perturb_flat_kernel<T, P, true> : perturb_flat_kernel<T, P, false>;
+  static int per[2] = {0, 0};
+  int& nb = per[zout ? 1 : 0];
+  if (nb == 0) nb = resident_blocks_per_cu(kern, 0, 8);
+  const int grid = a.n_flat < n_cu * nb ? a.n_flat : n_cu * nb;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, c, tab, zout);
   return hipGetLastError();
 }
 template <typename T, int P>
 hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
   const int kp = (a.max_k + 7) & ~7;
   const size_t lds = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kTileRowsPerIter * kp + (size_t)kp * 32 * P);
-  int per_cu = (int)((160 * 1024) / lds);
-  if (per_cu > 4) per_cu = 4;
-  if (per_cu < 1) per_cu = 1;
-  const int grid = a.n_tiles < n_cu * per_cu ? a.n_tiles : n_cu * per_cu;
   if (a.min_k >= kMfmaMinK) {
     const size_t lds_m = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kp * 32 * P);
-    int per = (int)((160 * 1024) / lds_m);
-    per = per > 5 ? 5 : (per < 1 ? 1 : per);
-    const int grid_m = a.n_tiles < n_cu * per ? a.n_tiles : n_cu * per;
     auto km = zout ? perturb_tile_mfma_kernel<T, P, true> : perturb_tile_mfma_kernel<T, P, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, c, tab, zout, kp);
+    const int per = resident_blocks_per_cu(km, lds_m, 8);
+    const int grid_m = a.n_tiles < n_cu * per ? a.n_tiles : n_cu * per;
+    hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, a.descs, a.tiles, c, tab, zout, kp);
     return hipGetLastError();
   }
   auto kern = zout ? perturb_tile_kernel<T, P, true> : perturb_tile_kernel<T, P, false>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, c, tab, zout, kp);
+  const int per_cu = resident_blocks_per_cu(kern, lds, 4);
+  const int grid = a.n_tiles < n_cu * per_cu ? a.n_tiles : n_cu * per_cu;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, a.descs, a.tiles, c, tab, zout, kp);
   return hipGetLastError();
 }
 }  // namespace
