@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run the plain 1 GiB copy kernel that HBM traffic counters are scaled by")
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
+    ap.add_argument("--batched-update", type=int, default=4,
+                    help="also time zgr_apply_updates over this many (step, g) pairs against as many zgr_apply_update calls (0: skip)")
     ap.add_argument("--no-fused-line", action="store_true",
                     help="skip the second, shorter measurement with config.fuse_restore_update = 1 (three passes over the parameters per step)")
     ap.add_argument("--profile-every", type=int, default=5,
@@ -229,6 +231,26 @@ def main():
         out["roofline"] = {"gemm": out.get("roofline_gemm"), "perturb_tile": out.get("roofline_perturb"),
                            "perturb_flat": out.get("roofline_perturb_flat")}.get(dom) or out.get("roofline_gemm") or out.get("roofline_perturb")
         out["dominant_kernel_class"] = dom
+    if args.batched_update > 0:
+        # edge-server aggregation over n (step, g) pairs: one pass per 8 perturbations against n single passes
+        nb = args.batched_update
+        bsteps = list(range(1000, 1000 + nb))
+        bg = [1e-3 * (1 + i) for i in range(nb)]
+        def timed(fn, reps=3):
+            fn(); torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t) / reps
+        def sequential():
+            for st, g in zip(bsteps, bg):
+                sess.apply_update(st, g, cfg.lr)
+        ms_seq = timed(sequential)
+        ms_bat = timed(lambda: sess.apply_updates(bsteps, bg, cfg.lr))
+        out["batched_update"] = {"n": nb, "ms_batched": ms_bat, "ms_sequential": ms_seq, "speedup": ms_seq / ms_bat,
+                                 "perturbations_per_s": nb / (ms_bat * 1e-3),
+                                 "hbm_bytes_algorithmic": 2.0 * (guided_elems + flat_elems) * es * ((nb + 7) // 8) + u_bytes * ((nb + 7) // 8)}
     sess.close()
     del sess, batch
     if not args.no_fused_line:

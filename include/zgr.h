@@ -168,6 +168,19 @@ zgr_status zgr_step(zgr_ctx* ctx, uint64_t step, const zgr_batch* batch, zgr_res
  * product lr*g is formed in fp32.  Asynchronous.                                */
 zgr_status zgr_apply_update(zgr_ctx* ctx, uint64_t step, float g, float lr);
 
+/* Edge-server block of Algorithm 1 with its sum over local steps t (and over
+ * clients, whose weights w_i the caller folds into g):
+ *   theta <- theta - lr * sum_q g[q] Z(seed, steps[q]),   q = 0 .. n-1,
+ * in ONE read-modify-write pass over the parameters per group of ZGR_MAX_BATCH
+ * perturbations (n may exceed it; n = 0 is a no-op): every Z(seed, steps[q]) is
+ * regenerated from the seed, the sum is accumulated in fp32 in list order and
+ * the result is rounded to the storage type once per pass.  steps, g: HOST
+ * arrays of n entries, steps[q] < 2^32; each product lr*g[q] is formed in fp32.
+ * The bases must be those of the steps named (one guidance interval).
+ * Asynchronous.  n = 1 equals zgr_apply_update.                                */
+#define ZGR_MAX_BATCH 8
+zgr_status zgr_apply_updates(zgr_ctx* ctx, int32_t n, const uint64_t* steps, const float* g, float lr);
+
 /* theta <- theta + c Z(seed, step) for all tensors: the single pass that
  * zgr_step and zgr_apply_update are made of.  Asynchronous.                    */
 zgr_status zgr_perturb(zgr_ctx* ctx, uint64_t step, float c);

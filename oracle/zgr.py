@@ -17,7 +17,7 @@ memory claim rests on holding only the model itself, Sec. 4.3).
 import numpy as np
 
 from . import forward as F
-from .perturbation import SCALE_UNIT, axpy_inplace_value, hybrid_z
+from .perturbation import SCALE_UNIT, axpy_inplace_value, bf16_round, hybrid_z
 
 
 class Tensor:
@@ -78,6 +78,20 @@ class ZgrOracle:
         theta <- theta - lr g Z(seed, step); the product lr*g is formed in fp32."""
         c = np.float32(-(np.float32(lr) * np.float32(g)))
         self.axpy_all(step, c)
+
+
+    def apply_updates(self, steps, gs, lr):
+        """Edge-server block with its sum over local steps (Algorithm 1, aggregation
+        line): theta <- theta - lr * sum_q g_q Z(seed, step_q), the sum taken
+        exactly (fp64 over the fp32 perturbations, each coefficient -(lr g_q) an
+        fp32 product), rounded to fp32 and then to the storage type once."""
+        coefs = [np.float64(np.float32(-(np.float32(lr) * np.float32(g)))) for g in gs]
+        for t in self.tensors:
+            acc = t.theta.astype(np.float64)
+            for step, c in zip(steps, coefs):
+                acc = acc + c * self.z_of(t, int(step)).astype(np.float64)
+            v = acc.astype(np.float32)
+            t.theta = bf16_round(v) if self.dtype == "bf16" else v
 
 
 # ---------------------------------------------------------------- loss adapters

@@ -15,6 +15,7 @@ ZGR_OK, ZGR_ERR_NULL, ZGR_ERR_SHAPE, ZGR_ERR_DTYPE, ZGR_ERR_CONFIG = 0, 1, 2, 3,
 ZGR_ERR_WORKSPACE, ZGR_ERR_DEVICE, ZGR_ERR_NONFINITE, ZGR_ERR_STATE = 5, 6, 7, 8
 ZGR_F32, ZGR_BF16 = 0, 1
 ZGR_SCALE_UNIT, ZGR_SCALE_PAPER = 0, 1
+ZGR_MAX_BATCH = 8
 ZGR_ARCH_NONE, ZGR_ARCH_LINEAR_LSQ, ZGR_ARCH_DECODER_LM, ZGR_ARCH_ENCODER_CLS = -1, 0, 1, 2
 ZGR_K_PERTURB_TILE, ZGR_K_PERTURB_FLAT, ZGR_K_GEMM, ZGR_K_ATTN, ZGR_K_NORM, ZGR_K_EMBED, ZGR_K_LOSS, ZGR_K_COUNT = range(8)
 KERNEL_CLASS_NAMES = ("perturb_tile", "perturb_flat", "gemm", "attention", "norm", "embed", "loss")
@@ -53,6 +54,7 @@ SYMBOLS = {
     "zgr_set_basis": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32]),
     "zgr_step": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(zgr_batch), C.POINTER(zgr_result)]),
     "zgr_apply_update": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float, C.c_float]),
+    "zgr_apply_updates": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.c_float]),
     "zgr_perturb": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float]),
     "zgr_loss": (C.c_int, [C.c_void_p, C.POINTER(zgr_batch), C.POINTER(C.c_double)]),
     "zgr_destroy": (None, [C.c_void_p]),

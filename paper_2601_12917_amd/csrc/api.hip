@@ -282,6 +282,18 @@ zgr_status perturb_pass(zgr_ctx* c, uint64_t step, float coef) {
   return ZGR_OK;
 }
 
+// One pass theta += sum_i coef[i] Z(seed, steps[i]), n <= kMaxBatch.
+zgr_status perturb_pass_batched(zgr_ctx* c, int n, const uint64_t* steps, const float* coef) {
+  zgr_status st = upload_lists(c);
+  if (st != ZGR_OK) return st;
+  PerturbArgs a = perturb_args(c, 0);
+  a.n_q = n;
+  for (int i = 0; i < n; ++i) { a.qstep[i] = (uint32_t)steps[i]; a.qcoef[i] = coef[i]; }
+  { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(a, 1.0f, nullptr, c->stream, c->n_cu)); }
+  { ProfScope ps(c, ZGR_K_PERTURB_FLAT); HIP_TRY(c, launch_perturb_flat(a, 1.0f, nullptr, c->stream, c->n_cu)); }
+  return ZGR_OK;
+}
+
 // ---------------------------------------------------------------- forward
 const void* T(zgr_ctx* c, int idx) { return c->t[idx].theta; }
 
@@ -538,6 +550,27 @@ zgr_status zgr_apply_update(zgr_ctx* c, uint64_t step, float g, float lr) {
   if (!std::isfinite(g) || !std::isfinite(lr)) return fail(c, ZGR_ERR_NONFINITE, "g or lr is not finite");
   const float coef = -(lr * g);
   return perturb_pass(c, step, coef);
+}
+
+zgr_status zgr_apply_updates(zgr_ctx* c, int32_t n, const uint64_t* steps, const float* g, float lr) {
+  if (!c) return ZGR_ERR_NULL;
+  if (n < 0) return fail(c, ZGR_ERR_SHAPE, "n must be >= 0");
+  if (n == 0) return ZGR_OK;
+  if (!steps || !g) return fail(c, ZGR_ERR_NULL, "steps or g is NULL");
+  if (!std::isfinite(lr)) return fail(c, ZGR_ERR_NONFINITE, "lr is not finite");
+  for (int i = 0; i < n; ++i) {
+    if (steps[i] >> 32) return fail(c, ZGR_ERR_CONFIG, "step must be < 2^32");
+    if (!std::isfinite(g[i])) return fail(c, ZGR_ERR_NONFINITE, "g[%d] is not finite", i);
+  }
+  // kMaxBatch perturbations per pass over the parameters; each pass rounds to the storage type once
+  for (int i0 = 0; i0 < n; i0 += kMaxBatch) {
+    const int m = n - i0 < kMaxBatch ? n - i0 : kMaxBatch;
+    float coef[kMaxBatch];
+    for (int i = 0; i < m; ++i) coef[i] = -(lr * g[i0 + i]);
+    zgr_status st = perturb_pass_batched(c, m, steps + i0, coef);
+    if (st != ZGR_OK) return st;
+  }
+  return ZGR_OK;
 }
 
 void zgr_destroy(zgr_ctx* c) {

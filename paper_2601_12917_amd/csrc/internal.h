@@ -30,6 +30,7 @@ struct WorkItem {
 constexpr int kFlatGroupsPerItem = 2048;   // Philox calls per flat work item (8 per thread)
 constexpr int kTileRowsPerIter   = 128;    // rows one block covers per iteration (4 waves x 32)
 constexpr int kMaxK              = 64;
+constexpr int kMaxBatch          = 8;      // perturbations summed in one pass (zgr_apply_updates)
 
 struct PerturbArgs {
   const TensorDesc* descs;     // device
@@ -42,6 +43,10 @@ struct PerturbArgs {
   int32_t           dtype;
   int32_t           max_k;     // largest k among tiled tensors
   int32_t           min_k;     // smallest k among tiled tensors
+  // batched pass: theta += sum_i qcoef[i] Z(seed, qstep[i]); n_q == 0: the single pass theta += c Z(seed, step)
+  int32_t           n_q;
+  uint32_t          qstep[kMaxBatch];
+  float             qcoef[kMaxBatch];
 };
 
 // theta += c * Z for everything in the flat / tile work list.  zout != nullptr:

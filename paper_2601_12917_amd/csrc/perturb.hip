@@ -53,12 +53,32 @@ template <int P> __device__ __forceinline__ void gaussP(const u32x4 w, const Rad
 template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss4(w, tab, g); }
 template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
 
+// The P Gaussians of Philox call q of one stream.  BATCH: instead the combination sum_i qcoef[i] * (those of step
+// qstep[i]), accumulated in the order of the list; since Z is linear in (G, R), a batched pass is the single
+// pass with this combination in place of G and of R and the coefficient 1.
+template <int P, bool BATCH>
+__device__ __forceinline__ void draw(uint64_t q, uint32_t id_stream, const PerturbArgs& a, const RadiusEntry* tab, float* g) {
+  if (!BATCH) {
+    gaussP<P>(philox_call(q, id_stream, a.step, a.k0, a.k1), tab, g);
+  } else {
+#pragma unroll
+    for (int j = 0; j < P; ++j) g[j] = 0.f;
+    for (int i = 0; i < a.n_q; ++i) {
+      float t[P];
+      gaussP<P>(philox_call(q, id_stream, a.qstep[i], a.k0, a.k1), tab, t);
+      const float ci = a.qcoef[i];
+#pragma unroll
+      for (int j = 0; j < P; ++j) g[j] = __builtin_fmaf(ci, t[j], g[j]);
+    }
+  }
+}
+
 // The work list and the tensor descriptors are separate __restrict__ kernel parameters (besides being members
 // of PerturbArgs): only then can the compiler tell that the stores to theta do not change them, and fetch them
 // with scalar loads.  Fetched through the struct they become vector loads behind an s_waitcnt vmcnt(0), which
 // drains every outstanding load and store of the wave once per work item.
 // ------------------------------------------------------------------ flat
-template <typename T, int P, bool WRITE_Z>
+template <typename T, int P, bool WRITE_Z, bool BATCH>
 __global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
                                                            float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout) {
   __shared__ RadiusEntry tab[kRadiusTabEntries];
@@ -77,7 +97,7 @@ __global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const 
       Vec<T, P> x;
       if (whole) x = load_global<Vec<T, P>>(th + e0);
       float G[P];
-      gaussP<P>(philox_call((uint64_t)q, d.id, a.step, a.k0, a.k1), tab, G);
+      draw<P, BATCH>((uint64_t)q, d.id, a, tab, G);
       if (WRITE_Z) {
         for (int j = 0; j < P; ++j) if (e0 + j < n) zout[e0 + j] = G[j];
       } else if (whole) {
@@ -97,11 +117,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kMfmaMinK = 16;      // from this rank on the U R contraction runs on the matrix cores
 
 // One lane's P consecutive elements starting at flat index e0: G from the seed, Z = a G + (b U R), axpy.
-template <typename T, int P, bool WRITE_Z>
+template <typename T, int P, bool WRITE_Z, bool BATCH>
 __device__ __forceinline__ void finish_row(const TensorDesc& d, T* __restrict__ th, float* __restrict__ zout, int64_t e0, const float* ur,
                                            float c, const PerturbArgs& a, const RadiusEntry* tab) {
   float G[P];
-  gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
+  draw<P, BATCH>((uint64_t)e0 / P, d.id, a, tab, G);
   if (WRITE_Z) {
 #pragma unroll
     for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], ur[j]);
@@ -118,7 +138,7 @@ __device__ __forceinline__ void finish_row(const TensorDesc& d, T* __restrict__ 
 
 // Lane layout inside a wave's 32-row slab: column group cg = lane % 32 owns P
 // consecutive columns; register v of the lane is row 8*(v/4) + 4*(lane/32) + v%4.
-template <typename T, int P, bool WRITE_Z>
+template <typename T, int P, bool WRITE_Z, bool BATCH>
 __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
                                                            float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout, int kp) {
   extern __shared__ float smem[];
@@ -147,7 +167,7 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
       for (int j = 0; j < P; ++j) r[j] = 0.f;
       if (l < k && col < d.cols) {
         const uint64_t q = (uint64_t)((int64_t)l * d.cols + col) / P;
-        gaussP<P>(philox_call(q, d.id | 0x80000000u, a.step, a.k0, a.k1), tab, r);
+        draw<P, BATCH>(q, d.id | 0x80000000u, a, tab, r);
 #pragma unroll
         for (int j = 0; j < P; ++j) r[j] *= d.b;
       }
@@ -195,7 +215,7 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
             const int vv = vb + v;
             const int rloc = 32 * wave + 8 * (vv >> 2) + 4 * rh + (vv & 3);
             const int64_t row = row0 + r0 + rloc;
-            if (r0 + rloc < nrows && row < d.rows) finish_row<T, P, WRITE_Z>(d, th, zout, row * d.cols + col, acc[v], c, a, tab);
+            if (r0 + rloc < nrows && row < d.rows) finish_row<T, P, WRITE_Z, BATCH>(d, th, zout, row * d.cols + col, acc[v], c, a, tab);
           }
         }
       }
@@ -211,7 +231,7 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
 // of its row of U from global memory and one row of the R slice from LDS per step.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <typename T, int P, bool WRITE_Z, bool FULL>
+template <typename T, int P, bool WRITE_Z, bool BATCH, bool FULL>
 __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const PerturbArgs& a, float c, const RadiusEntry* tab, const float* Rs,
                                                T* __restrict__ th, float* __restrict__ zout, int64_t row0, int64_t col0, int r0, int nrows,
                                                int k, int kq4, int wave, int n16, int rg) {
@@ -247,7 +267,7 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
         Vec<T, P> xv;
         if (!WRITE_Z) xv = load_global<Vec<T, P>>(th + e0);
         float G[P];
-        gaussP<P>(philox_call((uint64_t)e0 / P, d.id, a.step, a.k0, a.k1), tab, G);
+        draw<P, BATCH>((uint64_t)e0 / P, d.id, a, tab, G);
         if (WRITE_Z) {
 #pragma unroll
           for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
@@ -262,7 +282,7 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
       }
 }
 
-template <typename T, int P, bool WRITE_Z>
+template <typename T, int P, bool WRITE_Z, bool BATCH>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) perturb_tile_mfma_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
                                                                 float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout, int kp) {
   extern __shared__ float smem[];
@@ -286,7 +306,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
       for (int j = 0; j < P; ++j) r[j] = 0.f;
       if (l < k && col < d.cols) {
-        gaussP<P>(philox_call((uint64_t)((int64_t)l * d.cols + col) / P, d.id | 0x80000000u, a.step, a.k0, a.k1), tab, r);
+        draw<P, BATCH>((uint64_t)((int64_t)l * d.cols + col) / P, d.id | 0x80000000u, a, tab, r);
 #pragma unroll
         for (int j = 0; j < P; ++j) r[j] *= d.b;
       }
@@ -296,8 +316,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
     __syncthreads();
     const bool full = (nrows % 64 == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
     for (int r0 = 0; r0 < nrows; r0 += 64) {
-      if (full) mfma_row_block<T, P, WRITE_Z, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
-      else      mfma_row_block<T, P, WRITE_Z, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
+      if (full) mfma_row_block<T, P, WRITE_Z, BATCH, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
+      else      mfma_row_block<T, P, WRITE_Z, BATCH, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
     }
   }
 }
@@ -403,9 +423,9 @@ int resident_blocks_per_cu(K kern, size_t dyn_lds, int cap) {
 
 template <typename T, int P>
 hipError_t launch_flat_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
-  auto kern = zout ? perturb_flat_kernel<T, P, true> : perturb_flat_kernel<T, P, false>;
-  static int per[2] = {0, 0};
-  int& nb = per[zout ? 1 : 0];
+  auto kern = zout ? perturb_flat_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_flat_kernel<T, P, false, true> : perturb_flat_kernel<T, P, false, false>);
+  static int per[3] = {0, 0, 0};
+  int& nb = per[zout ? 1 : (a.n_q > 0 ? 2 : 0)];
   if (nb == 0) nb = resident_blocks_per_cu(kern, 0, 8);
   const int grid = a.n_flat < n_cu * nb ? a.n_flat : n_cu * nb;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, c, tab, zout);
@@ -417,7 +437,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
   const size_t lds = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kTileRowsPerIter * kp + (size_t)kp * 32 * P);
   if (a.min_k >= kMfmaMinK) {
     const size_t lds_m = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kp * 32 * P);
-    auto km = zout ? perturb_tile_mfma_kernel<T, P, true> : perturb_tile_mfma_kernel<T, P, false>;
+    auto km = zout ? perturb_tile_mfma_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_tile_mfma_kernel<T, P, false, true> : perturb_tile_mfma_kernel<T, P, false, false>);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);
     if (e != hipSuccess) return e;
     const int per = resident_blocks_per_cu(km, lds_m, 8);
@@ -425,7 +445,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
     hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, a.descs, a.tiles, c, tab, zout, kp);
     return hipGetLastError();
   }
-  auto kern = zout ? perturb_tile_kernel<T, P, true> : perturb_tile_kernel<T, P, false>;
+  auto kern = zout ? perturb_tile_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_tile_kernel<T, P, false, true> : perturb_tile_kernel<T, P, false, false>);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   const int per_cu = resident_blocks_per_cu(kern, lds, 4);
@@ -437,6 +457,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
 
 hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu) {
   if (a.n_flat <= 0) return hipSuccess;
+  if (a.n_q < 0 || a.n_q > kMaxBatch || (a.n_q > 0 && zout)) return hipErrorInvalidValue;
   const RadiusEntry* tab = nullptr;
   hipError_t e = ensure_radius_table(&tab);
   if (e != hipSuccess) return e;
@@ -447,6 +468,7 @@ hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipSt
 hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu) {
   if (a.n_tiles <= 0) return hipSuccess;
   if (a.max_k < 1 || a.max_k > kMaxK) return hipErrorInvalidValue;
+  if (a.n_q < 0 || a.n_q > kMaxBatch || (a.n_q > 0 && zout)) return hipErrorInvalidValue;
   const RadiusEntry* tab = nullptr;
   hipError_t e = ensure_radius_table(&tab);
   if (e != hipSuccess) return e;

@@ -101,6 +101,12 @@ class Session:
     def apply_update(self, step, g, lr):
         B.check(self.lib.zgr_apply_update(self.ctx, step, g, lr), self.ctx)
 
+    def apply_updates(self, steps, gs, lr):
+        n = len(steps)
+        sa = (C.c_uint64 * max(n, 1))(*[int(x) for x in steps])
+        ga = (C.c_float * max(n, 1))(*[float(x) for x in gs])
+        B.check(self.lib.zgr_apply_updates(self.ctx, n, sa, ga, lr), self.ctx)
+
     def perturb(self, step, c):
         B.check(self.lib.zgr_perturb(self.ctx, step, c), self.ctx)
 

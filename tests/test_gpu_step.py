@@ -148,6 +148,58 @@ def test_fused_restore_update_matches_oracle(cfg):
     sess.close()
 
 
+@pytest.mark.parametrize("cfg", [I.CONFIGS["cfg1"], I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS], ids=lambda c: c.name)
+@pytest.mark.parametrize("n,bits", [(1, 32), (3, 32), (8, 16), (11, 32)])
+def test_batched_update_matches_oracle(cfg, n, bits):
+    """zgr_apply_updates: theta - lr sum_q g_q Z(seed, step_q) in one pass per 8 perturbations (n = 11 takes two
+    passes; the oracle is then applied in the same two groups)."""
+    rng = np.random.default_rng(100 + n)
+    steps = [int(x) for x in rng.integers(0, 1000, size=n)]
+    gs = [float(x) for x in rng.standard_normal(n)]
+    lr = cfg.lr if cfg.dtype == "f32" else 3e-3          # moves bf16 weights by several ulps
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays), bits=bits)
+    sess = make_session(cfg, specs, values, bases, bits=bits, arch=-1)
+    before = [t.theta.copy() for t in o.tensors]
+    sess.apply_updates(steps, gs, lr)
+    for i0 in range(0, n, 8):
+        o.apply_updates(steps[i0:i0 + 8], gs[i0:i0 + 8], lr)
+    moved = 0
+    for i, t in enumerate(o.tensors):
+        got = sess.get_theta(i)
+        if cfg.dtype == "f32":
+            assert np.all(np.abs(got - t.theta) <= PARAM_RTOL["f32"] * (np.abs(t.theta) + PARAM_SCALE)), t.name
+            # far tighter in fact: two roundings of theta plus 1e-5 of the coefficients (2-ulp Gaussians and k-term
+            # fp32 dot products, both O(1) before scaling; a G and U R may cancel in Z, so |Z| itself is no yardstick)
+            csum = sum(abs(np.float32(lr) * np.float32(g)) for g in gs)
+            assert np.all(np.abs(got - t.theta) <= 2 * np.spacing(np.abs(t.theta)) + 1e-5 * csum), t.name
+        else:
+            # relative to the magnitude of what was summed: theta and the update may cancel
+            mag = np.abs(before[i]).astype(np.float64)
+            for st, g in zip(steps, gs):
+                mag = mag + abs(np.float32(lr) * np.float32(g)) * np.abs(o.z_of(t, st))
+            assert _close_params(got, t.theta, "bf16", mag), t.name
+        moved += int(np.sum(t.theta != before[i]))
+    assert moved > 0.2 * sum(t.theta.size for t in o.tensors)
+    sess.close()
+
+
+def test_batched_update_rejects_bad_arguments():
+    cfg = I.CONFIGS["cfg1"]
+    specs, values, bases = inputs_of(cfg)
+    sess = make_session(cfg, specs, values, bases, arch=-1)
+    before = sess.get_theta(0).copy()
+    sess.apply_updates([], [], 1e-2)                       # n = 0: no-op
+    assert np.array_equal(sess.get_theta(0), before)
+    with pytest.raises(Exception):
+        sess.apply_updates([1 << 32], [1.0], 1e-2)
+    with pytest.raises(Exception):
+        sess.apply_updates([1, 2], [1.0, float("nan")], 1e-2)
+    assert np.array_equal(sess.get_theta(0), before)
+    sess.close()
+
+
 def test_cfg2_full_trajectory_with_own_g():
     """20 steps of cfg2 driven by the device's own g; the deviation from the oracle's trajectory is
     bounded by lr |Z| |dL_err| / (2 eps) per step and reported."""

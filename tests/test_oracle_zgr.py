@@ -100,6 +100,42 @@ def test_fused_restore_update_equals_restore_then_update():
     assert np.array_equal(bb.tensors[0].theta.view(np.uint32) & 0xFFFF, np.zeros(t0.shape, np.uint32))
 
 
+def test_batched_update_is_the_sum_of_single_updates():
+    """theta - lr sum_q g_q Z_q in one pass: n = 1 is apply_update bit for bit; n = 3 matches three
+    successive updates to a few roundings, is within one rounding of the exact sum, and in bf16 is closer
+    to the exact sum than three passes that each round to bf16."""
+    steps, gs = [4, 9, 2], [0.75, -1.5, 0.3125]
+    for dtype in ("f32", "bf16"):
+        lr = 1e-2 if dtype == "f32" else 2.0          # large enough to move bf16 weights by many ulps
+        a, _, _ = _cfg1_oracle(dtype=dtype); b, _, _ = _cfg1_oracle(dtype=dtype); c, _, _ = _cfg1_oracle(dtype=dtype)
+        if dtype == "bf16":
+            for o in (a, b, c):
+                o.tensors[0].theta = P.bf16_round(o.tensors[0].theta)
+        theta0 = a.tensors[0].theta.astype(np.float64)
+        a.apply_update(7, gs[0], lr); b.apply_updates([7], [gs[0]], lr)
+        assert np.array_equal(a.tensors[0].theta, b.tensors[0].theta)
+        a.tensors[0].theta = theta0.astype(np.float32); b.tensors[0].theta = theta0.astype(np.float32)
+        for s, g in zip(steps, gs):
+            a.apply_update(s, g, lr)
+        b.apply_updates(steps, gs, lr)
+        exact = theta0.copy()
+        mag = np.abs(theta0)
+        for s, g in zip(steps, gs):
+            term = np.float64(np.float32(np.float32(lr) * np.float32(g))) * c.z_of(c.tensors[0], s).astype(np.float64)
+            exact -= term
+            mag = mag + np.abs(term)
+        ulp_mag = np.spacing(mag.astype(np.float32)).astype(np.float64) * (1.0 if dtype == "f32" else 2.0 ** 16)
+        ulp = np.spacing(np.abs(exact).astype(np.float32)).astype(np.float64) * (1.0 if dtype == "f32" else 2.0 ** 16)
+        assert np.all(np.abs(b.tensors[0].theta - exact) <= 0.5001 * ulp + 1e-12)          # one rounding (+ the fp32 one)
+        assert np.all(np.abs(a.tensors[0].theta - b.tensors[0].theta) <= 2.0 * ulp_mag)    # three roundings at intermediate magnitudes
+        assert np.abs(b.tensors[0].theta - exact).mean() <= np.abs(a.tensors[0].theta - exact).mean()
+        assert np.mean(np.abs(b.tensors[0].theta - theta0) > 4 * ulp) > 0.5                 # the update is not a no-op
+    # the same step twice is one step with the summed coefficient (linearity in g)
+    d1, _, _ = _cfg1_oracle(); d2, _, _ = _cfg1_oracle()
+    d1.apply_updates([5, 5], [0.5, 0.25], 1e-2); d2.apply_updates([5], [0.75], 1e-2)
+    assert np.allclose(d1.tensors[0].theta, d2.tensors[0].theta, rtol=0, atol=2e-8)
+
+
 def test_update_is_collinear_with_z():
     o, _, _ = _cfg1_oracle()
     before = o.tensors[0].theta.astype(np.float64)
