@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run the plain 1 GiB copy kernel that HBM traffic counters are scaled by")
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
+    ap.add_argument("--q4-basis", action="store_true",
+                    help="send the bases compressed: quantise every basis to 4-bit codes on the device and let the kernels restore them while loading")
     ap.add_argument("--batched-update", type=int, default=4,
                     help="also time zgr_apply_updates over this many (step, g) pairs against as many zgr_apply_update calls (0: skip)")
     ap.add_argument("--no-fused-line", action="store_true",
@@ -142,6 +144,10 @@ def main():
     arrays = make_batch_arrays(cfg)
     sess = make_session(cfg, specs, values, bases, bits=args.gauss_bits)
     batch = session_batch(sess, cfg, arrays)
+    if args.q4_basis:
+        for i, sp in enumerate(specs):
+            if sp.guided:
+                sess.compress_basis(i)
     setup_s = time.perf_counter() - t0
 
     def one_step(i):
@@ -186,13 +192,13 @@ def main():
     es = 4 if cfg.dtype == "f32" else 2
     guided_elems = sum(s.numel for s in specs if s.guided)
     flat_elems = sum(s.numel for s in specs if not s.guided)
-    u_bytes = sum(s.rows * cfg.k * 4 for s in specs if s.guided)
+    u_bytes = sum(s.rows * cfg.k * (0.5 if args.q4_basis else 4) for s in specs if s.guided)
     out = {
         "metric": "ZGR steps/sec", "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {I.CONFIGS[args.config].n_layer}-layer d={cfg.d_model} decoder, batch {cfg.batch} x seq {cfg.seq}, "
-                               f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns), gauss_bits={args.gauss_bits}"
+                               f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns{', 4-bit codes' if args.q4_basis else ''}), gauss_bits={args.gauss_bits}"
                    if cfg.arch != I.ARCH_LINEAR_LSQ else f"{cfg.name}: linear least squares {cfg.lsq_out}x{cfg.lsq_in}",
                    "params": int(guided_elems + flat_elems), "tokens_per_step": int(cfg.batch * max(cfg.seq, 1))},
         "tokens_per_s": steps_per_s * cfg.batch * max(cfg.seq, 1),

@@ -150,6 +150,27 @@ zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* ten
  * isotropic (non-guided round).                                                */
 zgr_status zgr_set_basis(zgr_ctx* ctx, int32_t tensor_index, const float* U, int32_t k, int32_t ldu);
 
+/* Guided round with the basis sent compressed (Data Transmission Controller,
+ * Sec. 4.4, first equation): Uq holds 4-bit codes, rows x ldq BYTES, element l
+ * of a row in byte l/2 (low nibble for even l); the kernels restore
+ * U[r][l] = lambda * (code - delta) in fp32 while loading the operand, so no
+ * fp32 copy of the basis is ever stored.  Uq is DEVICE memory owned by the
+ * caller and must stay valid while installed.  Same shape rules as
+ * zgr_set_basis (k <= 64, k <= rows, ldq >= (k+1)/2).  zgr_set_basis on the
+ * same tensor replaces it.                                                     */
+zgr_status zgr_set_basis_q4(zgr_ctx* ctx, int32_t tensor_index, const uint8_t* Uq, int32_t k, int32_t ldq,
+                            float lambda, float delta);
+
+/* The cloud's side of the same equation, on the device: codes
+ * round(U/lambda + delta) clipped to [0, 15] with lambda = (max - min) / 15 and
+ * delta = round(-min / lambda) over the first k columns of U [rows, ldu]
+ * (fp32 arithmetic, round to nearest even; the zero point as printed in the
+ * paper is not a code, this is the reading that maps min to code 0).  U, Uq
+ * (rows x ldq bytes) and minmax_dev (2 floats of scratch) are DEVICE memory;
+ * lambda_out, delta_out are HOST.  Synchronises the stream once.                */
+zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t ldu, uint8_t* Uq, int32_t ldq,
+                              float* minmax_dev, float* lambda_out, float* delta_out, void* hip_stream);
+
 /* Client block of Algorithm 1 for round/step `step` (< 2^32): perturb all
  * tensors in place by +eps Z, evaluate L+, by -2 eps Z, evaluate L-, restore by
  * +eps Z, Z regenerated from (seed, step) in each pass.  Fills *out.  On

@@ -52,6 +52,9 @@ SYMBOLS = {
     "zgr_init": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(zgr_model), C.POINTER(zgr_tensor), C.c_int32, C.POINTER(zgr_config),
                            C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p]),
     "zgr_set_basis": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32]),
+    "zgr_set_basis_q4": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_float]),
+    "zgr_quantize_basis": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                     C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p]),
     "zgr_step": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(zgr_batch), C.POINTER(zgr_result)]),
     "zgr_apply_update": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float, C.c_float]),
     "zgr_apply_updates": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.c_float]),

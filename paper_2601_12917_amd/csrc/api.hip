@@ -48,6 +48,8 @@ struct zgr_ctx {
   zgr_model model{};
   zgr_config cfg{};
   std::vector<zgr_tensor> t;
+  struct QBasis { const uint8_t* q = nullptr; float lambda = 0.f, delta = 0.f; };
+  std::vector<QBasis> qb;      // per tensor: 4-bit basis (then t[i].U is NULL, t[i].k its rank, t[i].ldu its row stride in bytes)
   std::vector<TensorDesc> descs;
   std::vector<WorkItem> flat, tiles;
   bool lists_dirty = true;
@@ -88,8 +90,8 @@ zgr_status fail(zgr_ctx* c, zgr_status st, const char* fmt, ...) {
 size_t elem_size(int dtype) { return dtype == ZGR_F32 ? 4 : 2; }
 
 // (a, b) of Z = a G + b U R for one tensor; isotropic tensors get (1, 0).
-void mix_coefficients(const zgr_config& cfg, const zgr_tensor& t, float* a, float* b) {
-  if (!t.U || t.k <= 0) { *a = 1.f; *b = 0.f; return; }
+void mix_coefficients(const zgr_config& cfg, const zgr_tensor& t, bool guided, float* a, float* b) {
+  if (!guided) { *a = 1.f; *b = 0.f; return; }
   const double al = cfg.alpha, rows = (double)t.rows, cols = (double)t.cols, k = (double)t.k;
   if (cfg.scale_mode == ZGR_SCALE_UNIT) { *a = (float)std::sqrt(al); *b = (float)std::sqrt((1.0 - al) * rows / k); }
   else { *a = (float)std::sqrt(al / (rows * cols)); *b = (float)std::sqrt((1.0 - al) / (k * cols)); }
@@ -120,7 +122,9 @@ void append_items(const zgr_tensor& t, int index, bool guided, int P, std::vecto
   }
 }
 
-bool is_guided(const zgr_tensor& t) { return t.U != nullptr && t.k > 0; }
+bool is_guided(const zgr_ctx* c, size_t i) {
+  return (c->t[i].U != nullptr || (i < c->qb.size() && c->qb[i].q != nullptr)) && c->t[i].k > 0;
+}
 
 // Host work lists + descriptors from the tensor table.
 void build_lists(zgr_ctx* c) {
@@ -130,12 +134,15 @@ void build_lists(zgr_ctx* c) {
   for (size_t i = 0; i < c->t.size(); ++i) {
     const zgr_tensor& t = c->t[i];
     TensorDesc& d = c->descs[i];
-    d.theta = t.theta; d.U = is_guided(t) ? t.U : nullptr; d.rows = t.rows; d.cols = t.cols; d.id = t.tensor_id;
-    d.k = is_guided(t) ? t.k : 0; d.ldu = t.ldu; d.dtype = t.dtype;
-    mix_coefficients(c->cfg, t, &d.a, &d.b);
-    append_items(t, (int)i, is_guided(t), P, c->flat, c->tiles);
-    if (is_guided(t) && t.k > c->max_k) c->max_k = t.k;
-    if (is_guided(t) && t.k < c->min_k) c->min_k = t.k;
+    const bool guided = is_guided(c, i);
+    const bool q4 = guided && t.U == nullptr;
+    d.theta = t.theta; d.U = guided ? t.U : nullptr; d.rows = t.rows; d.cols = t.cols; d.id = t.tensor_id;
+    d.Uq = q4 ? c->qb[i].q : nullptr; d.qlambda = q4 ? c->qb[i].lambda : 0.f; d.qdelta = q4 ? c->qb[i].delta : 0.f;
+    d.k = guided ? t.k : 0; d.ldu = t.ldu; d.dtype = t.dtype;
+    mix_coefficients(c->cfg, t, guided, &d.a, &d.b);
+    append_items(t, (int)i, guided, P, c->flat, c->tiles);
+    if (guided && t.k > c->max_k) c->max_k = t.k;
+    if (guided && t.k < c->min_k) c->min_k = t.k;
   }
   c->lists_dirty = true;
 }
@@ -207,7 +214,10 @@ Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int
     cv.qkv = take(M * 3 * d * es);
     cv.ctx = take(M * d * es);
     cv.ff = take(M * (size_t)m.d_ff * es);
-    cv.logits = take(m.arch == ZGR_ARCH_DECODER_LM ? M * (size_t)m.vocab * 4 : (size_t)max_batch * m.n_class * 4);
+    // fp32 storage: full fp32 logits; bf16: only the softmax partials (float2 per 128-row strip of the vocabulary
+    // and token) and the target logits of the fused cross-entropy
+    const size_t lm_logits = dtype == ZGR_BF16 ? M * ((size_t)2 * ce_partials_per_row(m.vocab) + 1) * 4 : M * (size_t)m.vocab * 4;
+    cv.logits = take(m.arch == ZGR_ARCH_DECODER_LM ? lm_logits : (size_t)max_batch * m.n_class * 4);
     cv.row_loss = take(M * 4);
     cv.targets = take(M * 4);
   } else if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
@@ -456,7 +466,7 @@ zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* ten
   if ((uintptr_t)workspace & 255) return fail(nullptr, ZGR_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   zgr_ctx* c = new (std::nothrow) zgr_ctx();
   if (!c) return fail(nullptr, ZGR_ERR_DEVICE, "out of host memory");
-  c->model = *model; c->cfg = *config; c->t.assign(tensors, tensors + n_t); c->dtype = tensors[0].dtype;
+  c->model = *model; c->cfg = *config; c->t.assign(tensors, tensors + n_t); c->qb.assign((size_t)n_t, zgr_ctx::QBasis{}); c->dtype = tensors[0].dtype;
   c->max_batch = max_batch; c->max_seq = max_seq; c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->cv = carve(*model, tensors, n_t, max_batch, max_seq, config->gauss_bits);
   if (workspace_bytes < c->cv.total) {
@@ -486,8 +496,47 @@ zgr_status zgr_set_basis(zgr_ctx* c, int32_t idx, const float* U, int32_t k, int
   zgr_status st = check_tensor(c, t, idx, c->cfg.gauss_bits, true);
   if (st != ZGR_OK) return st;
   c->t[idx] = t;
+  c->qb[idx] = zgr_ctx::QBasis{};
   build_lists(c);
   if (c->flat.size() > c->cv.cap_flat || c->tiles.size() > c->cv.cap_tiles) return fail(c, ZGR_ERR_WORKSPACE, "work lists outgrew the workspace");
+  return ZGR_OK;
+}
+
+zgr_status zgr_set_basis_q4(zgr_ctx* c, int32_t idx, const uint8_t* Uq, int32_t k, int32_t ldq, float lambda, float delta) {
+  if (!c) return ZGR_ERR_NULL;
+  if (idx < 0 || idx >= (int)c->t.size()) return fail(c, ZGR_ERR_SHAPE, "tensor_index %d out of range", idx);
+  if (!Uq) return fail(c, ZGR_ERR_NULL, "Uq is NULL");
+  if (k < 1) return fail(c, ZGR_ERR_SHAPE, "k must be >= 1");
+  if (ldq < (k + 1) / 2) return fail(c, ZGR_ERR_SHAPE, "ldq = %d bytes < (k + 1) / 2 = %d", ldq, (k + 1) / 2);
+  if (!std::isfinite(lambda) || !(lambda > 0.f) || !std::isfinite(delta)) return fail(c, ZGR_ERR_CONFIG, "lambda must be positive and finite, delta finite");
+  zgr_tensor t = c->t[idx];
+  t.U = nullptr; t.k = k; t.ldu = ldq;
+  if (t.k > kMaxK) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds %d", idx, t.k, kMaxK);
+  if (t.k > t.rows) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds rows = %lld", idx, t.k, (long long)t.rows);
+  if (t.cols % group_size(c->cfg.gauss_bits)) return fail(c, ZGR_ERR_SHAPE, "tensor %d: a guided tensor needs cols %% %d == 0", idx, group_size(c->cfg.gauss_bits));
+  c->t[idx] = t;
+  c->qb[idx].q = Uq; c->qb[idx].lambda = lambda; c->qb[idx].delta = delta;
+  build_lists(c);
+  if (c->flat.size() > c->cv.cap_flat || c->tiles.size() > c->cv.cap_tiles) return fail(c, ZGR_ERR_WORKSPACE, "work lists outgrew the workspace");
+  return ZGR_OK;
+}
+
+zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t ldu, uint8_t* Uq, int32_t ldq, float* minmax_dev,
+                              float* lambda_out, float* delta_out, void* hip_stream) {
+  if (!U || !Uq || !minmax_dev || !lambda_out || !delta_out) return fail(nullptr, ZGR_ERR_NULL, "a pointer is NULL");
+  if (rows < 1 || k < 1 || k > kMaxK || ldu < k || ldq < (k + 1) / 2) return fail(nullptr, ZGR_ERR_SHAPE, "bad basis shape");
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  HIP_TRY(nullptr, launch_basis_minmax(U, rows, k, ldu, minmax_dev, s));
+  float mm[2] = {0.f, 0.f};
+  HIP_TRY(nullptr, hipMemcpyAsync(mm, minmax_dev, sizeof mm, hipMemcpyDeviceToHost, s));
+  HIP_TRY(nullptr, hipStreamSynchronize(s));
+  if (!std::isfinite(mm[0]) || !std::isfinite(mm[1])) return fail(nullptr, ZGR_ERR_NONFINITE, "the basis holds a non-finite value");
+  // lambda = (max - min) / (2^4 - 1), delta = round(-min / lambda), all in fp32 (a constant basis gets lambda = 1)
+  float lambda = (mm[1] - mm[0]) / 15.0f;
+  if (!(lambda > 0.f)) lambda = 1.0f;
+  const float delta = std::nearbyintf(-mm[0] / lambda);
+  HIP_TRY(nullptr, launch_basis_quantize(U, rows, k, ldu, lambda, delta, Uq, ldq, s));
+  *lambda_out = lambda; *delta_out = delta;
   return ZGR_OK;
 }
 
@@ -634,7 +683,7 @@ zgr_status zgr_debug_fill_z(zgr_ctx* c, int32_t idx, uint64_t step, float* Z) {
   zgr_status st = upload_lists(c);
   if (st != ZGR_OK) return st;
   std::vector<WorkItem> fl, tl;
-  append_items(c->t[idx], idx, is_guided(c->t[idx]), group_size(c->cfg.gauss_bits), fl, tl);
+  append_items(c->t[idx], idx, is_guided(c, (size_t)idx), group_size(c->cfg.gauss_bits), fl, tl);
   std::vector<WorkItem>& items = fl.empty() ? tl : fl;
   if (items.size() > c->cv.cap_dbg) return fail(c, ZGR_ERR_WORKSPACE, "debug list outgrew the workspace");
   HIP_TRY(c, hipMemcpyAsync(c->ws + c->cv.dbg, items.data(), sizeof(WorkItem) * items.size(), hipMemcpyHostToDevice, c->stream));

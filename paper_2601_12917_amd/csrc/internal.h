@@ -10,10 +10,13 @@ namespace zgr {
 // Device-visible description of one parameter tensor for the perturbation pass.
 struct TensorDesc {
   void*        theta;
-  const float* U;        // nullptr or k == 0: isotropic, Z = G
+  const float* U;        // fp32 basis, or nullptr
+  const uint8_t* Uq;     // 4-bit codes of the basis (two per byte, element l in byte l/2, low nibble first), or nullptr;
+                         // U == nullptr && Uq == nullptr or k == 0: isotropic, Z = G
+  float        qlambda, qdelta;   // U[r][l] = qlambda * (code - qdelta) when Uq is set
   int64_t      rows, cols;
   uint32_t     id;       // < 2^31
-  int32_t      k, ldu;
+  int32_t      k, ldu;   // ldu: row stride of U in floats, of Uq in bytes
   float        a, b;     // Z = a G + b U R   (a = 1, b = 0 when isotropic)
   int32_t      dtype;    // 0 fp32, 1 bf16
 };
@@ -62,6 +65,9 @@ hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t 
                               float* out, hipStream_t s);
 hipError_t launch_debug_radius_table(int bits, float* out, hipStream_t s);
 hipError_t launch_debug_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// affine quantiser of a basis: min / max of U[rows, k] (row stride ldu) into minmax[2] (device), then the 4-bit codes
+hipError_t launch_basis_minmax(const float* U, int64_t rows, int k, int ldu, float* minmax, hipStream_t s);
+hipError_t launch_basis_quantize(const float* U, int64_t rows, int k, int ldu, float lambda, float delta, uint8_t* Uq, int ldq, hipStream_t s);
 hipError_t launch_debug_cossin_table(int bits, float* c, float* sn, hipStream_t s);
 
 }  // namespace zgr

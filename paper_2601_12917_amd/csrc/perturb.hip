@@ -53,6 +53,17 @@ template <int P> __device__ __forceinline__ void gaussP(const u32x4 w, const Rad
 template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss4(w, tab, g); }
 template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
 
+// Element [row][l] of the basis: fp32 as stored, or restored from its 4-bit code as lambda (code - delta)
+// (Sec. 4.4, first equation): the restore is fused into the operand load, the fp32 basis never exists in memory.
+__device__ __forceinline__ float basis_at(const TensorDesc& d, int64_t row, int l) {
+  if (d.Uq) {
+    const uint32_t byte = d.Uq[row * d.ldu + (l >> 1)];
+    const uint32_t code = (l & 1) ? (byte >> 4) : (byte & 15u);
+    return d.qlambda * ((float)code - d.qdelta);
+  }
+  return load_global<float>(d.U + row * d.ldu + l);
+}
+
 // The P Gaussians of Philox call q of one stream.  BATCH: instead the combination sum_i qcoef[i] * (those of step
 // qstep[i]), accumulated in the order of the list; since Z is linear in (G, R), a batched pass is the single
 // pass with this combination in place of G and of R and the coefficient 1.
@@ -179,7 +190,7 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
       for (int idx = tid; idx < kTileRowsPerIter * kpt; idx += 256) {
         const int r = idx / kpt, l = idx - r * kpt;
         const int64_t row = row0 + r0 + r;
-        Us[r * kp + l] = (l < k && r0 + r < nrows && row < d.rows) ? d.U[row * d.ldu + l] : 0.f;
+        Us[r * kp + l] = (l < k && r0 + r < nrows && row < d.rows) ? basis_at(d, row, l) : 0.f;
       }
       __syncthreads();
       const int64_t col = col0 + (int64_t)cg * P;
@@ -238,7 +249,8 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
   constexpr int TC = 32 * P, GC = 16 * P;                     // tile columns, columns per group
   const int mrow = r0 + 16 * wave + n16;                      // A operand: this lane feeds row (lane % 16) of the slab
   const bool uvalid = FULL || (mrow < nrows && row0 + mrow < d.rows);
-  const float* up = d.U + (row0 + mrow) * d.ldu + rg * kq4;
+  const int64_t urow = row0 + mrow;
+  const int ucol = rg * kq4;
   const int rbase = r0 + 16 * wave + 4 * rg;                  // first of this lane's 4 rows (tile-relative)
   const int64_t ebase = (row0 + rbase) * d.cols + col0 + (int64_t)P * n16;
   f32x4 acc[2 * P];
@@ -247,7 +259,7 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
   for (int s0 = 0; s0 < kq4; s0 += 2) {
     float ua[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) ua[i] = (uvalid && rg * kq4 + s0 + i < k) ? load_global<float>(up + s0 + i) : 0.f;
+    for (int i = 0; i < 2; ++i) ua[i] = (uvalid && ucol + s0 + i < k) ? basis_at(d, urow, ucol + s0 + i) : 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const float* rrow = Rs + (rg * kq4 + s0 + i) * TC + P * n16;
@@ -319,6 +331,53 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
       if (full) mfma_row_block<T, P, WRITE_Z, BATCH, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
       else      mfma_row_block<T, P, WRITE_Z, BATCH, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
     }
+  }
+}
+
+// ------------------------------------------------------------------ affine quantiser of a basis (cloud side of Sec. 4.4)
+// min / max as order-preserving integers, so that integer atomics reduce them
+__device__ __forceinline__ int32_t float_order(float x) { const int32_t b = __float_as_int(x); return b >= 0 ? b : (int32_t)(0x80000000u - (uint32_t)b); }
+__device__ __forceinline__ float order_float(int32_t o) { return __int_as_float(o >= 0 ? o : (int32_t)(0x80000000u - (uint32_t)o)); }
+
+__global__ void basis_minmax_init_kernel(int32_t* mm) { mm[0] = 0x7FFFFFFF; mm[1] = (int32_t)0x80000000; }
+__global__ void __launch_bounds__(256) basis_minmax_kernel(const float* __restrict__ U, int64_t rows, int k, int ldu, int32_t* __restrict__ mm) {
+  int32_t lo = 0x7FFFFFFF, hi = (int32_t)0x80000000;
+  const int64_t n = rows * k;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int32_t o = float_order(U[(i / k) * ldu + (i % k)]);
+    lo = o < lo ? o : lo; hi = o > hi ? o : hi;
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    const int32_t l2 = __shfl_xor(lo, off, 64), h2 = __shfl_xor(hi, off, 64);
+    lo = l2 < lo ? l2 : lo; hi = h2 > hi ? h2 : hi;
+  }
+  if ((threadIdx.x & 63) == 0) { atomicMin(mm, lo); atomicMax(mm + 1, hi); }
+}
+__global__ void basis_minmax_finish_kernel(int32_t* mm) {
+  float* f = reinterpret_cast<float*>(mm);
+  const float lo = order_float(mm[0]), hi = order_float(mm[1]);
+  f[0] = lo; f[1] = hi;
+}
+// one thread per output byte: codes of elements 2j and 2j + 1 of a row, round(x / lambda + delta) clipped to [0, 15]
+__global__ void __launch_bounds__(256) basis_quantize_kernel(const float* __restrict__ U, int64_t rows, int k, int ldu, float lambda, float delta,
+                                                             uint8_t* __restrict__ Uq, int ldq) {
+#pragma clang fp contract(off)   // x / lambda is rounded before delta is added, as the definition has it
+  const int kb = (k + 1) >> 1;
+  const int64_t n = rows * kb;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / kb;
+    const int j = (int)(i % kb);
+    uint32_t byte = 0;
+    for (int h = 0; h < 2; ++h) {
+      const int l = 2 * j + h;
+      if (l < k) {
+        const float t = U[r * ldu + l] / lambda;
+        float q = __builtin_rintf(t + delta);
+        q = q < 0.f ? 0.f : (q > 15.f ? 15.f : q);
+        byte |= (uint32_t)q << (4 * h);
+      }
+    }
+    Uq[r * ldq + j] = (uint8_t)byte;
   }
 }
 
@@ -474,6 +533,23 @@ hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipSt
   if (e != hipSuccess) return e;
   if (a.dtype == 0) return a.bits == 32 ? launch_tile_t<float, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<float, 8>(a, c, zout, s, n_cu, tab);
   return a.bits == 32 ? launch_tile_t<bf16_t, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<bf16_t, 8>(a, c, zout, s, n_cu, tab);
+}
+
+hipError_t launch_basis_minmax(const float* U, int64_t rows, int k, int ldu, float* minmax, hipStream_t s) {
+  int32_t* mm = reinterpret_cast<int32_t*>(minmax);
+  hipLaunchKernelGGL(basis_minmax_init_kernel, dim3(1), dim3(1), 0, s, mm);
+  const int64_t n = rows * k;
+  const int grid = (int)(n / 256 + 1 < 1024 ? n / 256 + 1 : 1024);
+  hipLaunchKernelGGL(basis_minmax_kernel, dim3(grid), dim3(256), 0, s, U, rows, k, ldu, mm);
+  hipLaunchKernelGGL(basis_minmax_finish_kernel, dim3(1), dim3(1), 0, s, mm);
+  return hipGetLastError();
+}
+
+hipError_t launch_basis_quantize(const float* U, int64_t rows, int k, int ldu, float lambda, float delta, uint8_t* Uq, int ldq, hipStream_t s) {
+  const int64_t n = rows * ((k + 1) / 2);
+  const int grid = (int)(n / 256 + 1 < 1024 ? n / 256 + 1 : 1024);
+  hipLaunchKernelGGL(basis_quantize_kernel, dim3(grid), dim3(256), 0, s, U, rows, k, ldu, lambda, delta, Uq, ldq);
+  return hipGetLastError();
 }
 
 hipError_t launch_debug_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {

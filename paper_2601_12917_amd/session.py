@@ -123,6 +123,41 @@ class Session:
         self.U[index] = t
         B.check(self.lib.zgr_set_basis(self.ctx, index, t.data_ptr(), k, U.shape[1]), self.ctx)
 
+    def set_basis_q4(self, index, codes_packed: np.ndarray, k, lam, delta):
+        """codes_packed: uint8 [rows, ldq] (two 4-bit codes per byte)."""
+        t = torch.from_numpy(np.ascontiguousarray(codes_packed, dtype=np.uint8)).to(self.dev)
+        self.Uq = getattr(self, "Uq", {})
+        self.Uq[index] = t
+        B.check(self.lib.zgr_set_basis_q4(self.ctx, index, t.data_ptr(), k, codes_packed.shape[1], float(lam), float(delta)), self.ctx)
+
+    def quantize_basis(self, U: np.ndarray, k):
+        """Device quantiser: returns (packed codes uint8 [rows, (k+1)//2], lambda, delta)."""
+        u = torch.from_numpy(np.ascontiguousarray(U, dtype=np.float32)).to(self.dev)
+        rows, ldu = u.shape
+        ldq = (k + 1) // 2
+        q = torch.zeros(rows, ldq, dtype=torch.uint8, device=self.dev)
+        mm = torch.zeros(2, dtype=torch.float32, device=self.dev)
+        lam, delta = C.c_float(0), C.c_float(0)
+        B.check(self.lib.zgr_quantize_basis(u.data_ptr(), rows, k, ldu, q.data_ptr(), ldq, mm.data_ptr(), C.byref(lam), C.byref(delta),
+                                            self.stream.cuda_stream), None)
+        torch.cuda.synchronize(self.dev)
+        return q.cpu().numpy(), lam.value, delta.value
+
+    def compress_basis(self, index):
+        """Quantise the installed fp32 basis of one tensor to 4 bits on the device and install the codes in its place."""
+        u, k = self.U[index], self.params[index].k
+        rows, ldu = u.shape
+        ldq = (k + 1) // 2
+        q = torch.zeros(rows, ldq, dtype=torch.uint8, device=self.dev)
+        mm = torch.zeros(2, dtype=torch.float32, device=self.dev)
+        lam, delta = C.c_float(0), C.c_float(0)
+        B.check(self.lib.zgr_quantize_basis(u.data_ptr(), rows, k, ldu, q.data_ptr(), ldq, mm.data_ptr(), C.byref(lam), C.byref(delta),
+                                            self.stream.cuda_stream), None)
+        self.Uq = getattr(self, "Uq", {})
+        self.Uq[index] = q
+        B.check(self.lib.zgr_set_basis_q4(self.ctx, index, q.data_ptr(), k, ldq, lam.value, delta.value), self.ctx)
+        return lam.value, delta.value
+
     def fill_z(self, index, step):
         rows, cols = self.params[index].values.shape
         z = torch.empty(rows, cols, dtype=torch.float32, device=self.dev)
