@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="leave the HIP-event timing of kernel classes off")
     ap.add_argument("--q4-basis", action="store_true",
                     help="send the bases compressed: quantise every basis to 4-bit codes on the device and let the kernels restore them while loading")
+    ap.add_argument("--stream-bases", action="store_true",
+                    help="keep the bases in pinned host memory and stream them layer by layer during every pass (with --q4-basis: as 4-bit codes)")
     ap.add_argument("--batched-update", type=int, default=4,
                     help="also time zgr_apply_updates over this many (step, g) pairs against as many zgr_apply_update calls (0: skip)")
     ap.add_argument("--no-fused-line", action="store_true",
@@ -144,7 +146,18 @@ def main():
     arrays = make_batch_arrays(cfg)
     sess = make_session(cfg, specs, values, bases, bits=args.gauss_bits)
     batch = session_batch(sess, cfg, arrays)
-    if args.q4_basis:
+    if args.stream_bases:
+        layers = {}
+        for i, sp in enumerate(specs):
+            if sp.guided and bases[i] is not None:
+                layers.setdefault(sp.layer, []).append(i)
+        for layer, idx in layers.items():
+            if args.q4_basis:
+                q = [sess.quantize_basis(bases[i], cfg.k) for i in idx]
+                sess.set_layer_bases_host(idx, [x[0] for x in q], cfg.k, codes=True, lams=[x[1] for x in q], deltas=[x[2] for x in q])
+            else:
+                sess.set_layer_bases_host(idx, [bases[i] for i in idx], cfg.k)
+    elif args.q4_basis:
         for i, sp in enumerate(specs):
             if sp.guided:
                 sess.compress_basis(i)
@@ -198,7 +211,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {I.CONFIGS[args.config].n_layer}-layer d={cfg.d_model} decoder, batch {cfg.batch} x seq {cfg.seq}, "
-                               f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns{', 4-bit codes' if args.q4_basis else ''}), gauss_bits={args.gauss_bits}"
+                               f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns{', 4-bit codes' if args.q4_basis else ''}{', streamed from host memory per layer' if args.stream_bases else ''}), gauss_bits={args.gauss_bits}"
                    if cfg.arch != I.ARCH_LINEAR_LSQ else f"{cfg.name}: linear least squares {cfg.lsq_out}x{cfg.lsq_in}",
                    "params": int(guided_elems + flat_elems), "tokens_per_step": int(cfg.batch * max(cfg.seq, 1))},
         "tokens_per_s": steps_per_s * cfg.batch * max(cfg.seq, 1),

@@ -30,6 +30,7 @@ struct Carve {                 // workspace layout (byte offsets)
   size_t descs = 0, flat = 0, tiles = 0, dbg = 0;
   size_t cap_flat = 0, cap_tiles = 0, cap_dbg = 0;   // capacities in items
   size_t x = 0, h = 0, qkv = 0, ctx = 0, ff = 0, logits = 0, row_loss = 0, targets = 0, loss = 0;
+  size_t spc[2] = {0, 0}, spc_bytes = 0;   // two staging slots for the bases of one layer each (streamed bases)
   size_t total = 0;
 };
 
@@ -50,6 +51,15 @@ struct zgr_ctx {
   std::vector<zgr_tensor> t;
   struct QBasis { const uint8_t* q = nullptr; float lambda = 0.f, delta = 0.f; };
   std::vector<QBasis> qb;      // per tensor: 4-bit basis (then t[i].U is NULL, t[i].k its rank, t[i].ldu its row stride in bytes)
+  // Bases that stay in HOST memory and are streamed layer by layer during a pass (t[i].U NULL, t[i].k the rank)
+  struct HostBasis { const void* host = nullptr; int bits = 0, ld = 0; float lambda = 0.f, delta = 0.f; size_t slot_off = 0; };
+  std::vector<HostBasis> hb;
+  struct Group { int layer = 0; std::vector<int> tensors; size_t tile_begin = 0, tile_end = 0; int max_k = 0, min_k = 0; };
+  std::vector<Group> groups;   // streamed groups in pass order; their tiles follow the resident ones in `tiles`
+  size_t resident_tiles = 0;
+  int res_max_k = 0, res_min_k = 0;
+  hipStream_t copy_stream = nullptr;
+  hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_used[2] = {nullptr, nullptr};
   std::vector<TensorDesc> descs;
   std::vector<WorkItem> flat, tiles;
   bool lists_dirty = true;
@@ -123,26 +133,62 @@ void append_items(const zgr_tensor& t, int index, bool guided, int P, std::vecto
 }
 
 bool is_guided(const zgr_ctx* c, size_t i) {
-  return (c->t[i].U != nullptr || (i < c->qb.size() && c->qb[i].q != nullptr)) && c->t[i].k > 0;
+  return (c->t[i].U != nullptr || (i < c->qb.size() && c->qb[i].q != nullptr) || (i < c->hb.size() && c->hb[i].host != nullptr)) && c->t[i].k > 0;
 }
+bool is_streamed(const zgr_ctx* c, size_t i) { return i < c->hb.size() && c->hb[i].host != nullptr && c->t[i].k > 0; }
 
 // Host work lists + descriptors from the tensor table.
 void build_lists(zgr_ctx* c) {
   const int P = group_size(c->cfg.gauss_bits);
-  c->flat.clear(); c->tiles.clear(); c->descs.resize(c->t.size());
-  c->max_k = 0; c->min_k = kMaxK + 1;
+  c->flat.clear(); c->tiles.clear(); c->descs.resize(c->t.size()); c->groups.clear();
+  c->max_k = 0; c->min_k = kMaxK + 1; c->res_max_k = 0; c->res_min_k = kMaxK + 1;
+  // streamed tensors: groups by layer in order of first appearance, slot offsets inside the group
   for (size_t i = 0; i < c->t.size(); ++i) {
+    if (!is_streamed(c, i)) continue;
+    zgr_ctx::Group* g = nullptr;
+    for (auto& gg : c->groups) if (gg.layer == c->t[i].layer) g = &gg;
+    if (!g) { c->groups.push_back({}); g = &c->groups.back(); g->layer = c->t[i].layer; g->min_k = kMaxK + 1; }
+    g->tensors.push_back((int)i);
+  }
+  for (size_t gi = 0; gi < c->groups.size(); ++gi) {
+    size_t off = 0;
+    for (int i : c->groups[gi].tensors) {
+      c->hb[i].slot_off = off;
+      const size_t row_bytes = c->hb[i].bits == 4 ? (size_t)(c->t[i].k + 1) / 2 : (size_t)c->t[i].k * 4;
+      off += align_up((size_t)c->t[i].rows * row_bytes);
+    }
+  }
+  auto describe = [&](size_t i, int group_index) {
     const zgr_tensor& t = c->t[i];
     TensorDesc& d = c->descs[i];
     const bool guided = is_guided(c, i);
-    const bool q4 = guided && t.U == nullptr;
+    const bool streamed = is_streamed(c, i);
+    const bool q4 = guided && !streamed && t.U == nullptr;
     d.theta = t.theta; d.U = guided ? t.U : nullptr; d.rows = t.rows; d.cols = t.cols; d.id = t.tensor_id;
     d.Uq = q4 ? c->qb[i].q : nullptr; d.qlambda = q4 ? c->qb[i].lambda : 0.f; d.qdelta = q4 ? c->qb[i].delta : 0.f;
     d.k = guided ? t.k : 0; d.ldu = t.ldu; d.dtype = t.dtype;
+    if (streamed) {
+      // the basis of a streamed tensor is read from the staging slot of its group's parity, compact rows
+      unsigned char* slot = c->ws + c->cv.spc[group_index & 1] + c->hb[i].slot_off;
+      if (c->hb[i].bits == 4) { d.U = nullptr; d.Uq = slot; d.qlambda = c->hb[i].lambda; d.qdelta = c->hb[i].delta; d.ldu = (t.k + 1) / 2; }
+      else { d.U = reinterpret_cast<const float*>(slot); d.Uq = nullptr; d.ldu = t.k; }
+    }
     mix_coefficients(c->cfg, t, guided, &d.a, &d.b);
     append_items(t, (int)i, guided, P, c->flat, c->tiles);
     if (guided && t.k > c->max_k) c->max_k = t.k;
     if (guided && t.k < c->min_k) c->min_k = t.k;
+  };
+  for (size_t i = 0; i < c->t.size(); ++i) {
+    if (is_streamed(c, i)) continue;
+    describe(i, 0);
+    if (is_guided(c, i)) { c->res_max_k = std::max(c->res_max_k, c->t[i].k); c->res_min_k = std::min(c->res_min_k, c->t[i].k); }
+  }
+  c->resident_tiles = c->tiles.size();
+  for (size_t gi = 0; gi < c->groups.size(); ++gi) {
+    zgr_ctx::Group& g = c->groups[gi];
+    g.tile_begin = c->tiles.size();
+    for (int i : g.tensors) { describe((size_t)i, (int)gi); g.max_k = std::max(g.max_k, c->t[i].k); g.min_k = std::min(g.min_k, c->t[i].k); }
+    g.tile_end = c->tiles.size();
   }
   c->lists_dirty = true;
 }
@@ -206,6 +252,19 @@ Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int
   cv.tiles = take(sizeof(WorkItem) * std::max<size_t>(nt, 1));
   cv.dbg = take(sizeof(WorkItem) * std::max<size_t>(nd, 1));
   cv.loss = take(sizeof(double) * 2);
+  {
+    // largest per-layer sum of basis bytes (compact rows x k fp32), from the ranks in the tensor table
+    std::vector<std::pair<int, size_t>> per_layer;
+    for (int i = 0; i < n_t; ++i) {
+      if (t[i].k <= 0 || t[i].cols % P) continue;
+      const size_t bytes = align_up((size_t)t[i].rows * (size_t)t[i].k * 4);
+      bool found = false;
+      for (auto& pl : per_layer) if (pl.first == t[i].layer) { pl.second += bytes; found = true; }
+      if (!found) per_layer.push_back({t[i].layer, bytes});
+    }
+    for (const auto& pl : per_layer) cv.spc_bytes = std::max(cv.spc_bytes, pl.second);
+    cv.spc[0] = take(cv.spc_bytes); cv.spc[1] = take(cv.spc_bytes);
+  }
   const size_t es = elem_size(dtype);
   if (is_transformer(m.arch)) {
     const size_t M = (size_t)max_batch * max_seq, d = m.d_model;
@@ -282,14 +341,77 @@ PerturbArgs perturb_args(zgr_ctx* c, uint64_t step) {
   return a;
 }
 
+// H2D transfer of the bases of streamed group gi into its staging slot, on the copy stream, once the kernel
+// that last read that slot has finished.
+zgr_status stage_group(zgr_ctx* c, size_t gi) {
+  const int slot = (int)(gi & 1);
+  HIP_TRY(c, hipStreamWaitEvent(c->copy_stream, c->ev_used[slot], 0));
+  // Compact bases that lie in host memory exactly as they lie in the slot (same order, same 256-byte padding)
+  // travel as one linear transfer: the fixed cost of a transfer, not its size, is what a layer's stage is made of.
+  unsigned char* run_dst = nullptr; const unsigned char* run_src = nullptr; size_t run_bytes = 0;
+  auto flush = [&]() -> hipError_t {
+    if (run_bytes == 0) return hipSuccess;
+    const hipError_t e = hipMemcpyAsync(run_dst, run_src, run_bytes, hipMemcpyHostToDevice, c->copy_stream);
+    run_bytes = 0;
+    return e;
+  };
+  for (int i : c->groups[gi].tensors) {
+    const zgr_ctx::HostBasis& h = c->hb[i];
+    const zgr_tensor& t = c->t[i];
+    const size_t width = h.bits == 4 ? (size_t)(t.k + 1) / 2 : (size_t)t.k * 4;
+    const size_t spitch = h.bits == 4 ? (size_t)h.ld : (size_t)h.ld * 4;
+    unsigned char* dst = c->ws + c->cv.spc[slot] + h.slot_off;
+    const unsigned char* src = static_cast<const unsigned char*>(h.host);
+    if (spitch != width) {                                   // strided rows: a 2-D transfer of its own
+      HIP_TRY(c, flush());
+      HIP_TRY(c, hipMemcpy2DAsync(dst, width, src, spitch, width, (size_t)t.rows, hipMemcpyHostToDevice, c->copy_stream));
+      continue;
+    }
+    const size_t bytes = width * (size_t)t.rows;
+    if (run_bytes > 0 && dst - run_dst == src - run_src && (size_t)(dst - run_dst) >= run_bytes && (size_t)(dst - run_dst) <= align_up(run_bytes)) {
+      run_bytes = (size_t)(dst - run_dst) + bytes;           // continues the run (the padding in between is copied along)
+    } else {
+      HIP_TRY(c, flush());
+      run_dst = dst; run_src = src; run_bytes = bytes;
+    }
+  }
+  HIP_TRY(c, flush());
+  HIP_TRY(c, hipEventRecord(c->ev_copied[slot], c->copy_stream));
+  return ZGR_OK;
+}
+
+// One pass over all parameters with the arguments `a` (single or batched) and coefficient coef: resident guided
+// tensors and isotropic tensors in one launch each, then the streamed groups layer by layer (Sec. 4.3): while the
+// kernel of layer l runs, the bases of layer l + 1 arrive in the other staging slot.
+zgr_status run_pass(zgr_ctx* c, PerturbArgs a, float coef) {
+  const WorkItem* tiles = a.tiles;
+  a.n_tiles = (int32_t)c->resident_tiles; a.max_k = c->res_max_k; a.min_k = c->res_min_k;
+  zgr_status st = ZGR_OK;
+  if (!c->groups.empty()) {
+    // the bases of the first two layers start moving before any kernel of this pass is queued
+    if ((st = stage_group(c, 0)) != ZGR_OK) return st;
+    if (c->groups.size() > 1 && (st = stage_group(c, 1)) != ZGR_OK) return st;
+  }
+  if (a.n_tiles > 0) { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(a, coef, nullptr, c->stream, c->n_cu)); }
+  { ProfScope ps(c, ZGR_K_PERTURB_FLAT); HIP_TRY(c, launch_perturb_flat(a, coef, nullptr, c->stream, c->n_cu)); }
+  for (size_t gi = 0; gi < c->groups.size(); ++gi) {
+    const zgr_ctx::Group& g = c->groups[gi];
+    const int slot = (int)(gi & 1);
+    HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_copied[slot], 0));
+    PerturbArgs ag = a;
+    ag.tiles = tiles + g.tile_begin; ag.n_tiles = (int32_t)(g.tile_end - g.tile_begin); ag.n_flat = 0; ag.max_k = g.max_k; ag.min_k = g.min_k;
+    if (ag.n_tiles > 0) { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(ag, coef, nullptr, c->stream, c->n_cu)); }
+    HIP_TRY(c, hipEventRecord(c->ev_used[slot], c->stream));
+    if (gi + 2 < c->groups.size() && (st = stage_group(c, gi + 2)) != ZGR_OK) return st;
+  }
+  return ZGR_OK;
+}
+
 zgr_status perturb_pass(zgr_ctx* c, uint64_t step, float coef) {
   if (step >> 32) return fail(c, ZGR_ERR_CONFIG, "step must be < 2^32");
   zgr_status st = upload_lists(c);
   if (st != ZGR_OK) return st;
-  const PerturbArgs a = perturb_args(c, step);
-  { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(a, coef, nullptr, c->stream, c->n_cu)); }
-  { ProfScope ps(c, ZGR_K_PERTURB_FLAT); HIP_TRY(c, launch_perturb_flat(a, coef, nullptr, c->stream, c->n_cu)); }
-  return ZGR_OK;
+  return run_pass(c, perturb_args(c, step), coef);
 }
 
 // One pass theta += sum_i coef[i] Z(seed, steps[i]), n <= kMaxBatch.
@@ -299,9 +421,7 @@ zgr_status perturb_pass_batched(zgr_ctx* c, int n, const uint64_t* steps, const 
   PerturbArgs a = perturb_args(c, 0);
   a.n_q = n;
   for (int i = 0; i < n; ++i) { a.qstep[i] = (uint32_t)steps[i]; a.qcoef[i] = coef[i]; }
-  { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(a, 1.0f, nullptr, c->stream, c->n_cu)); }
-  { ProfScope ps(c, ZGR_K_PERTURB_FLAT); HIP_TRY(c, launch_perturb_flat(a, 1.0f, nullptr, c->stream, c->n_cu)); }
-  return ZGR_OK;
+  return run_pass(c, a, 1.0f);
 }
 
 // ---------------------------------------------------------------- forward
@@ -466,7 +586,7 @@ zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* ten
   if ((uintptr_t)workspace & 255) return fail(nullptr, ZGR_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   zgr_ctx* c = new (std::nothrow) zgr_ctx();
   if (!c) return fail(nullptr, ZGR_ERR_DEVICE, "out of host memory");
-  c->model = *model; c->cfg = *config; c->t.assign(tensors, tensors + n_t); c->qb.assign((size_t)n_t, zgr_ctx::QBasis{}); c->dtype = tensors[0].dtype;
+  c->model = *model; c->cfg = *config; c->t.assign(tensors, tensors + n_t); c->qb.assign((size_t)n_t, zgr_ctx::QBasis{}); c->hb.assign((size_t)n_t, zgr_ctx::HostBasis{}); c->dtype = tensors[0].dtype;
   c->max_batch = max_batch; c->max_seq = max_seq; c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->cv = carve(*model, tensors, n_t, max_batch, max_seq, config->gauss_bits);
   if (workspace_bytes < c->cv.total) {
@@ -497,6 +617,7 @@ zgr_status zgr_set_basis(zgr_ctx* c, int32_t idx, const float* U, int32_t k, int
   if (st != ZGR_OK) return st;
   c->t[idx] = t;
   c->qb[idx] = zgr_ctx::QBasis{};
+  c->hb[idx] = zgr_ctx::HostBasis{};
   build_lists(c);
   if (c->flat.size() > c->cv.cap_flat || c->tiles.size() > c->cv.cap_tiles) return fail(c, ZGR_ERR_WORKSPACE, "work lists outgrew the workspace");
   return ZGR_OK;
@@ -516,6 +637,47 @@ zgr_status zgr_set_basis_q4(zgr_ctx* c, int32_t idx, const uint8_t* Uq, int32_t 
   if (t.cols % group_size(c->cfg.gauss_bits)) return fail(c, ZGR_ERR_SHAPE, "tensor %d: a guided tensor needs cols %% %d == 0", idx, group_size(c->cfg.gauss_bits));
   c->t[idx] = t;
   c->qb[idx].q = Uq; c->qb[idx].lambda = lambda; c->qb[idx].delta = delta;
+  c->hb[idx] = zgr_ctx::HostBasis{};
+  build_lists(c);
+  if (c->flat.size() > c->cv.cap_flat || c->tiles.size() > c->cv.cap_tiles) return fail(c, ZGR_ERR_WORKSPACE, "work lists outgrew the workspace");
+  return ZGR_OK;
+}
+
+zgr_status zgr_set_basis_host(zgr_ctx* c, int32_t idx, const void* U_host, int32_t k, int32_t ld, int32_t bits, float lambda, float delta) {
+  if (!c) return ZGR_ERR_NULL;
+  if (idx < 0 || idx >= (int)c->t.size()) return fail(c, ZGR_ERR_SHAPE, "tensor_index %d out of range", idx);
+  if (!U_host) return fail(c, ZGR_ERR_NULL, "U_host is NULL");
+  if (bits != 32 && bits != 4) return fail(c, ZGR_ERR_CONFIG, "bits must be 32 (fp32 basis) or 4 (codes)");
+  if (k < 1) return fail(c, ZGR_ERR_SHAPE, "k must be >= 1");
+  if (ld < (bits == 4 ? (k + 1) / 2 : k)) return fail(c, ZGR_ERR_SHAPE, "row stride %d too small for k = %d", ld, k);
+  if (bits == 4 && (!std::isfinite(lambda) || !(lambda > 0.f) || !std::isfinite(delta))) return fail(c, ZGR_ERR_CONFIG, "lambda must be positive and finite, delta finite");
+  zgr_tensor t = c->t[idx];
+  if (k > kMaxK) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds %d", idx, k, kMaxK);
+  if (k > t.rows) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds rows = %lld", idx, k, (long long)t.rows);
+  if (t.cols % group_size(c->cfg.gauss_bits)) return fail(c, ZGR_ERR_SHAPE, "tensor %d: a guided tensor needs cols %% %d == 0", idx, group_size(c->cfg.gauss_bits));
+  if (!c->copy_stream) {
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+    for (int i = 0; i < 2; ++i) {
+      HIP_TRY(c, hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming));
+      HIP_TRY(c, hipEventCreateWithFlags(&c->ev_used[i], hipEventDisableTiming));
+    }
+  }
+  // the group this tensor joins must still fit a staging slot
+  const zgr_ctx::HostBasis old_hb = c->hb[idx];
+  const zgr_tensor old_t = c->t[idx];
+  const zgr_ctx::QBasis old_qb = c->qb[idx];
+  t.U = nullptr; t.k = k; t.ldu = bits == 4 ? (k + 1) / 2 : k;
+  c->t[idx] = t;
+  c->qb[idx] = zgr_ctx::QBasis{};
+  c->hb[idx].host = U_host; c->hb[idx].bits = bits; c->hb[idx].ld = ld; c->hb[idx].lambda = lambda; c->hb[idx].delta = delta;
+  size_t need = 0;
+  for (size_t i = 0; i < c->t.size(); ++i)
+    if (is_streamed(c, i) && c->t[i].layer == t.layer)
+      need += align_up((size_t)c->t[i].rows * (c->hb[i].bits == 4 ? (size_t)(c->t[i].k + 1) / 2 : (size_t)c->t[i].k * 4));
+  if (need > c->cv.spc_bytes) {
+    c->t[idx] = old_t; c->hb[idx] = old_hb; c->qb[idx] = old_qb;
+    return fail(c, ZGR_ERR_WORKSPACE, "the bases of layer %d need %zu bytes of staging, the workspace holds %zu (sized from the ranks given to zgr_workspace_bytes)", t.layer, need, c->cv.spc_bytes);
+  }
   build_lists(c);
   if (c->flat.size() > c->cv.cap_flat || c->tiles.size() > c->cv.cap_tiles) return fail(c, ZGR_ERR_WORKSPACE, "work lists outgrew the workspace");
   return ZGR_OK;
@@ -626,6 +788,11 @@ void zgr_destroy(zgr_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  if (c->copy_stream) {
+    (void)hipStreamSynchronize(c->copy_stream);
+    for (int i = 0; i < 2; ++i) { (void)hipEventDestroy(c->ev_copied[i]); (void)hipEventDestroy(c->ev_used[i]); }
+    (void)hipStreamDestroy(c->copy_stream);
+  }
   delete c;
 }
 
@@ -691,7 +858,19 @@ zgr_status zgr_debug_fill_z(zgr_ctx* c, int32_t idx, uint64_t step, float* Z) {
   PerturbArgs a = perturb_args(c, step);
   const WorkItem* dbg = reinterpret_cast<const WorkItem*>(c->ws + c->cv.dbg);
   if (!fl.empty()) { a.flat = dbg; a.n_flat = (int32_t)fl.size(); a.n_tiles = 0; HIP_TRY(c, launch_perturb_flat(a, 0.f, Z, c->stream, c->n_cu)); }
-  else { a.tiles = dbg; a.n_tiles = (int32_t)tl.size(); a.n_flat = 0; a.max_k = a.min_k = c->t[idx].k; HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu)); }
+  else {
+    a.tiles = dbg; a.n_tiles = (int32_t)tl.size(); a.n_flat = 0; a.max_k = a.min_k = c->t[idx].k;
+    int slot = -1;
+    if (is_streamed(c, (size_t)idx)) {
+      // bring the bases of this tensor's layer into their staging slot first
+      for (size_t gi = 0; gi < c->groups.size(); ++gi)
+        for (int i : c->groups[gi].tensors)
+          if (i == idx) { if ((st = stage_group(c, gi)) != ZGR_OK) return st; slot = (int)(gi & 1); }
+      if (slot >= 0) HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_copied[slot], 0));
+    }
+    HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu));
+    if (slot >= 0) HIP_TRY(c, hipEventRecord(c->ev_used[slot], c->stream));
+  }
   return ZGR_OK;
 }
 

@@ -143,6 +143,36 @@ class Session:
         torch.cuda.synchronize(self.dev)
         return q.cpu().numpy(), lam.value, delta.value
 
+    def set_basis_host(self, index, U: np.ndarray, k, codes=None, lam=0.0, delta=0.0):
+        """Keep the basis of one tensor in pinned host memory and stream it per layer during the passes.
+        codes: packed 4-bit codes [rows, ldq] instead of U (then lam, delta are their scale and zero point)."""
+        src = np.ascontiguousarray(codes, dtype=np.uint8) if codes is not None else np.ascontiguousarray(U, dtype=np.float32)
+        t = torch.from_numpy(src).pin_memory()
+        self.Uhost = getattr(self, "Uhost", {})
+        self.Uhost[index] = t
+        B.check(self.lib.zgr_set_basis_host(self.ctx, index, t.data_ptr(), k, src.shape[1], 4 if codes is not None else 32,
+                                            float(lam), float(delta)), self.ctx)
+
+    def set_layer_bases_host(self, indices, arrays, k, codes=False, lams=None, deltas=None):
+        """Stream the bases of one layer from ONE pinned block laid out like the staging slot (tensor order, compact
+        rows, each tensor padded to 256 bytes), so that the whole layer travels as a single transfer.
+        arrays: fp32 [rows, >= k] per tensor, or packed 4-bit codes [rows, (k+1)//2] when codes=True."""
+        width = (k + 1) // 2 if codes else 4 * k
+        offs, off = [], 0
+        for a in arrays:
+            offs.append(off)
+            off += _align(a.shape[0] * width)
+        block = torch.zeros(off, dtype=torch.uint8).pin_memory()
+        view = block.numpy()
+        for a, o in zip(arrays, offs):
+            src = np.ascontiguousarray(a[:, :(k + 1) // 2], dtype=np.uint8) if codes else np.ascontiguousarray(a[:, :k], dtype=np.float32)
+            view[o:o + src.nbytes] = src.view(np.uint8).reshape(-1)
+        self.Uhost = getattr(self, "Uhost", {})
+        for j, (i, o) in enumerate(zip(indices, offs)):
+            self.Uhost[i] = block
+            B.check(self.lib.zgr_set_basis_host(self.ctx, i, block.data_ptr() + o, k, width if codes else k, 4 if codes else 32,
+                                                float(lams[j]) if codes else 0.0, float(deltas[j]) if codes else 0.0), self.ctx)
+
     def compress_basis(self, index):
         """Quantise the installed fp32 basis of one tensor to 4 bits on the device and install the codes in its place."""
         u, k = self.U[index], self.params[index].k

@@ -1,0 +1,113 @@
+"""Bases streamed from host memory layer by layer (Sec. 4.3): the result of every pass is bit-identical
+to the resident-basis path (same kernels, same operands), for fp32 bases and for 4-bit codes, over several
+passes so that both staging slots are reused; the resident path itself is checked against the oracle
+elsewhere."""
+import numpy as np
+import pytest
+
+import zgr_inputs as I
+from oracle import dtc as D
+from tests.util import inputs_of, make_batch_arrays, make_session, session_batch
+
+pytestmark = pytest.mark.gpu
+
+DEEP_F32 = I.shrink(I.CONFIGS["cfg2"], name="deep_f32", n_layer=5, d_model=64, n_head=4, d_ff=128, vocab=211,
+                    max_pos=32, batch=2, seq=16, k=8, k_full=8)
+DEEP_BF16 = I.shrink(I.CONFIGS["cfg3"], name="deep_bf16", n_layer=4, d_model=128, n_head=2, d_ff=256, vocab=500,
+                     max_pos=32, batch=2, seq=24, k=16, k_full=24)
+
+
+def _guided(specs, bases):
+    return [i for i, (s, u) in enumerate(zip(specs, bases)) if u is not None]
+
+
+@pytest.mark.parametrize("cfg", [DEEP_F32, DEEP_BF16], ids=lambda c: c.name)
+@pytest.mark.parametrize("mode", ["f32", "q4", "mixed"])
+def test_streamed_bases_give_identical_steps(cfg, mode):
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    res = make_session(cfg, specs, values, bases)
+    spc = make_session(cfg, specs, values, bases)
+    for i in _guided(specs, bases):
+        k = cfg.k
+        if mode == "q4" or (mode == "mixed" and specs[i].layer % 2 == 1):
+            lam, delta = D.affine_params(bases[i][:, :k], 4)
+            packed = D.pack_nibbles(D.quantize(bases[i][:, :k], lam, delta, 4))
+            res.set_basis_q4(i, packed, k, lam, delta)
+            if mode == "q4":
+                spc.set_basis_host(i, None, k, codes=packed, lam=lam, delta=delta)
+            else:
+                spc.set_basis_q4(i, packed, k, lam, delta)          # odd layers stay resident (compressed)
+        else:
+            spc.set_basis_host(i, bases[i], k)                       # full rows of k_full columns, first k used
+    bres, bspc = session_batch(res, cfg, arrays), session_batch(spc, cfg, arrays)
+    for step in range(3):
+        r = res.step(step, bres); s = spc.step(step, bspc)
+        assert r == s, (step, r, s)
+        res.apply_update(step, r[2], 10 * cfg.lr); spc.apply_update(step, s[2], 10 * cfg.lr)
+        for i in range(len(specs)):
+            assert np.array_equal(res.get_theta(i), spc.get_theta(i)), (step, specs[i].name)
+    res.apply_updates([7, 8, 9], [0.5, -0.25, 1.0], cfg.lr); spc.apply_updates([7, 8, 9], [0.5, -0.25, 1.0], cfg.lr)
+    for i in range(len(specs)):
+        assert np.array_equal(res.get_theta(i), spc.get_theta(i)), specs[i].name
+    g = _guided(specs, bases)
+    assert len({specs[i].layer for i in g}) >= 4
+    i = g[len(g) // 2]
+    assert np.array_equal(res.fill_z(i, 3), spc.fill_z(i, 3))
+    res.close(); spc.close()
+
+
+@pytest.mark.parametrize("codes", [False, True])
+def test_layer_blocks_travel_as_one_transfer_and_give_identical_steps(codes):
+    """A layer's bases packed in one pinned block in staging-slot layout (the single-transfer path)."""
+    cfg = DEEP_BF16
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    res = make_session(cfg, specs, values, bases)
+    spc = make_session(cfg, specs, values, bases)
+    layers = {}
+    for i in _guided(specs, bases):
+        layers.setdefault(specs[i].layer, []).append(i)
+    for layer, idx in layers.items():
+        if codes:
+            q = []
+            for i in idx:
+                lam, delta = D.affine_params(bases[i][:, :cfg.k], 4)
+                packed = D.pack_nibbles(D.quantize(bases[i][:, :cfg.k], lam, delta, 4))
+                res.set_basis_q4(i, packed, cfg.k, lam, delta)
+                q.append((packed, lam, delta))
+            spc.set_layer_bases_host(idx, [x[0] for x in q], cfg.k, codes=True, lams=[x[1] for x in q], deltas=[x[2] for x in q])
+        else:
+            spc.set_layer_bases_host(idx, [bases[i] for i in idx], cfg.k)
+    bres, bspc = session_batch(res, cfg, arrays), session_batch(spc, cfg, arrays)
+    for step in range(3):
+        r = res.step(step, bres); s = spc.step(step, bspc)
+        assert r == s
+        res.apply_update(step, r[2], 10 * cfg.lr); spc.apply_update(step, s[2], 10 * cfg.lr)
+    for i in range(len(specs)):
+        assert np.array_equal(res.get_theta(i), spc.get_theta(i)), specs[i].name
+    res.close(); spc.close()
+
+
+def test_streamed_basis_can_be_replaced_and_is_bounded_by_the_workspace():
+    cfg = DEEP_F32
+    specs, values, bases = inputs_of(cfg)
+    sess = make_session(cfg, specs, values, bases)
+    g = _guided(specs, bases)
+    i = g[0]
+    z_res = sess.fill_z(i, 5)
+    sess.set_basis_host(i, bases[i], cfg.k)
+    assert np.array_equal(sess.fill_z(i, 5), z_res)
+    sess.set_basis(i, bases[i], cfg.k)                               # back to a resident basis
+    assert np.array_equal(sess.fill_z(i, 5), z_res)
+    rows = bases[i].shape[0]
+    for j in g:
+        if specs[j].layer == specs[i].layer:
+            sess.set_basis_host(j, bases[j], cfg.k)                  # the whole layer streamed: its staging slot is full
+    wide = np.linalg.qr(np.random.default_rng(0).standard_normal((rows, 4 * cfg.k)))[0].astype(np.float32)
+    with pytest.raises(Exception):
+        sess.set_basis_host(i, wide, 4 * cfg.k)                      # four times the rank the slots were sized for
+    assert np.array_equal(sess.fill_z(i, 5), z_res)                  # the refused call changed nothing
+    with pytest.raises(Exception):
+        sess.set_basis_host(i, bases[i], cfg.k, codes=np.zeros((rows, 1), np.uint8), lam=1.0)   # row stride too small
+    sess.close()
