@@ -164,18 +164,23 @@ zgr_status zgr_set_basis_q4(zgr_ctx* ctx, int32_t tensor_index, const uint8_t* U
 /* System-level Pipeline Controller (Sec. 4.3), client side: the basis of this
  * tensor stays in HOST memory (where the link from the cloud delivers it) and
  * is brought to the device layer by layer during every perturbation pass.
- * Tensors with the same `layer` form one stage: while the kernel of layer l
- * runs, the bases of layer l + 1 are copied (on a second stream the context
- * owns) into the other of two staging slots in the workspace, so that only two
- * layers' bases are ever resident.  bits = 32: U_host is fp32 [rows, ld];
- * bits = 4: U_host holds the 4-bit codes of zgr_set_basis_q4, [rows, ld BYTES],
- * with their lambda and delta.  U_host is owned by the caller, must stay valid
- * and unchanged while installed, and should be pinned (hipHostMalloc) for the
- * copies to overlap.  The staging slots are sized by zgr_workspace_bytes from
- * the ranks k of the tensor table given to it: a layer whose bases need more
- * is refused with ZGR_ERR_WORKSPACE.  Results are identical to a resident
- * basis.  zgr_set_basis / zgr_set_basis_q4 on the same tensor undo it.          */
-zgr_status zgr_set_basis_host(zgr_ctx* ctx, int32_t tensor_index, const void* U_host, int32_t k, int32_t ld,
+ * Tensors with the same `layer` form one stage: the kernel launch that perturbs
+ * layer l also reads the bases of layer l + 1 out of host memory into the other
+ * of two staging slots in the workspace, so the transfer runs under the
+ * arithmetic of layer l and only two layers' bases are ever resident.
+ * bits = 32: U_host is fp32 [rows, k]; bits = 4: U_host holds the 4-bit codes
+ * of zgr_set_basis_q4, [rows, (k+1)/2 bytes], with their lambda and delta
+ * (ignored for bits = 32).  Rows are compact (no row stride).  U_host is owned
+ * by the caller, must be PINNED host memory the device can read
+ * (hipHostMalloc), 16-byte aligned, and stay valid and unchanged while
+ * installed.  Bases of one layer that lie in one host allocation in tensor-table
+ * order, each padded to a multiple of 256 bytes, are fetched as one piece.  At
+ * most 16 streamed tensors per layer.  The staging slots are sized by
+ * zgr_workspace_bytes from the ranks k of the tensor table given to it: a layer
+ * whose bases need more is refused with ZGR_ERR_WORKSPACE.  Results are
+ * identical to a resident basis.  zgr_set_basis / zgr_set_basis_q4 on the same
+ * tensor undo it.                                                              */
+zgr_status zgr_set_basis_host(zgr_ctx* ctx, int32_t tensor_index, const void* U_host, int32_t k,
                               int32_t bits, float lambda, float delta);
 
 /* The cloud's side of the same equation, on the device: codes

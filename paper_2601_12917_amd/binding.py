@@ -53,7 +53,7 @@ SYMBOLS = {
                            C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p]),
     "zgr_set_basis": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32]),
     "zgr_set_basis_q4": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_float]),
-    "zgr_set_basis_host": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_float]),
+    "zgr_set_basis_host": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_float]),
     "zgr_quantize_basis": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                      C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p]),
     "zgr_step": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(zgr_batch), C.POINTER(zgr_result)]),

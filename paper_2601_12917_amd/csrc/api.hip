@@ -21,6 +21,8 @@ std::string g_init_error;   // message of the last failed zgr_init / context-fre
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+constexpr int kSpcSlots = 2;   // layers' worth of streamed bases resident at once: the one in use and the one arriving
+
 struct Layer {
   int ln1_g = -1, ln1_b = -1, wq = -1, bq = -1, wk = -1, bk = -1, wv = -1, bv = -1, wo = -1, bo = -1;
   int ln2_g = -1, ln2_b = -1, w1 = -1, b1 = -1, w2 = -1, b2 = -1;
@@ -30,7 +32,7 @@ struct Carve {                 // workspace layout (byte offsets)
   size_t descs = 0, flat = 0, tiles = 0, dbg = 0;
   size_t cap_flat = 0, cap_tiles = 0, cap_dbg = 0;   // capacities in items
   size_t x = 0, h = 0, qkv = 0, ctx = 0, ff = 0, logits = 0, row_loss = 0, targets = 0, loss = 0;
-  size_t spc[2] = {0, 0}, spc_bytes = 0;   // two staging slots for the bases of one layer each (streamed bases)
+  size_t spc[kSpcSlots] = {}, spc_bytes = 0;   // staging slots for the bases of one layer each (streamed bases)
   size_t total = 0;
 };
 
@@ -52,14 +54,13 @@ struct zgr_ctx {
   struct QBasis { const uint8_t* q = nullptr; float lambda = 0.f, delta = 0.f; };
   std::vector<QBasis> qb;      // per tensor: 4-bit basis (then t[i].U is NULL, t[i].k its rank, t[i].ldu its row stride in bytes)
   // Bases that stay in HOST memory and are streamed layer by layer during a pass (t[i].U NULL, t[i].k the rank)
-  struct HostBasis { const void* host = nullptr; int bits = 0, ld = 0; float lambda = 0.f, delta = 0.f; size_t slot_off = 0; };
+  struct HostBasis { const void* host = nullptr; const unsigned char* dev = nullptr; int bits = 0; float lambda = 0.f, delta = 0.f; size_t slot_off = 0; };
   std::vector<HostBasis> hb;
-  struct Group { int layer = 0; std::vector<int> tensors; size_t tile_begin = 0, tile_end = 0; int max_k = 0, min_k = 0; };
+  struct Group { int layer = 0; std::vector<int> tensors; size_t tile_begin = 0, tile_end = 0; int max_k = 0, min_k = 0;
+                 std::vector<StageCopy> copies; };   // host -> staging-slot pieces, contiguous runs merged
   std::vector<Group> groups;   // streamed groups in pass order; their tiles follow the resident ones in `tiles`
   size_t resident_tiles = 0;
   int res_max_k = 0, res_min_k = 0;
-  hipStream_t copy_stream = nullptr;
-  hipEvent_t ev_copied[2] = {nullptr, nullptr}, ev_used[2] = {nullptr, nullptr};
   std::vector<TensorDesc> descs;
   std::vector<WorkItem> flat, tiles;
   bool lists_dirty = true;
@@ -158,6 +159,20 @@ void build_lists(zgr_ctx* c) {
       off += align_up((size_t)c->t[i].rows * row_bytes);
     }
   }
+  for (size_t gi = 0; gi < c->groups.size(); ++gi) {
+    // bases that lie in host memory as they lie in the slot (same order, same 256-byte padding) form one piece
+    std::vector<StageCopy>& cp = c->groups[gi].copies;
+    cp.clear();
+    for (int i : c->groups[gi].tensors) {
+      const size_t bytes = (size_t)c->t[i].rows * (c->hb[i].bits == 4 ? (size_t)(c->t[i].k + 1) / 2 : (size_t)c->t[i].k * 4);
+      unsigned char* dst = c->ws + c->cv.spc[gi % kSpcSlots] + c->hb[i].slot_off;
+      const unsigned char* src = c->hb[i].dev;
+      if (!cp.empty() && dst - cp.back().dst == src - cp.back().src && (size_t)(dst - cp.back().dst) == align_up((size_t)cp.back().bytes))
+        cp.back().bytes = (uint64_t)(dst - cp.back().dst) + bytes;     // the padding in between is copied along
+      else
+        cp.push_back(StageCopy{src, dst, (uint64_t)bytes});
+    }
+  }
   auto describe = [&](size_t i, int group_index) {
     const zgr_tensor& t = c->t[i];
     TensorDesc& d = c->descs[i];
@@ -168,8 +183,8 @@ void build_lists(zgr_ctx* c) {
     d.Uq = q4 ? c->qb[i].q : nullptr; d.qlambda = q4 ? c->qb[i].lambda : 0.f; d.qdelta = q4 ? c->qb[i].delta : 0.f;
     d.k = guided ? t.k : 0; d.ldu = t.ldu; d.dtype = t.dtype;
     if (streamed) {
-      // the basis of a streamed tensor is read from the staging slot of its group's parity, compact rows
-      unsigned char* slot = c->ws + c->cv.spc[group_index & 1] + c->hb[i].slot_off;
+      // the basis of a streamed tensor is read from the staging slot its group rotates into, compact rows
+      unsigned char* slot = c->ws + c->cv.spc[group_index % kSpcSlots] + c->hb[i].slot_off;
       if (c->hb[i].bits == 4) { d.U = nullptr; d.Uq = slot; d.qlambda = c->hb[i].lambda; d.qdelta = c->hb[i].delta; d.ldu = (t.k + 1) / 2; }
       else { d.U = reinterpret_cast<const float*>(slot); d.Uq = nullptr; d.ldu = t.k; }
     }
@@ -263,7 +278,7 @@ Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int
       if (!found) per_layer.push_back({t[i].layer, bytes});
     }
     for (const auto& pl : per_layer) cv.spc_bytes = std::max(cv.spc_bytes, pl.second);
-    cv.spc[0] = take(cv.spc_bytes); cv.spc[1] = take(cv.spc_bytes);
+    for (int i = 0; i < kSpcSlots; ++i) cv.spc[i] = take(cv.spc_bytes);
   }
   const size_t es = elem_size(dtype);
   if (is_transformer(m.arch)) {
@@ -341,68 +356,42 @@ PerturbArgs perturb_args(zgr_ctx* c, uint64_t step) {
   return a;
 }
 
-// H2D transfer of the bases of streamed group gi into its staging slot, on the copy stream, once the kernel
-// that last read that slot has finished.
-zgr_status stage_group(zgr_ctx* c, size_t gi) {
-  const int slot = (int)(gi & 1);
-  HIP_TRY(c, hipStreamWaitEvent(c->copy_stream, c->ev_used[slot], 0));
-  // Compact bases that lie in host memory exactly as they lie in the slot (same order, same 256-byte padding)
-  // travel as one linear transfer: the fixed cost of a transfer, not its size, is what a layer's stage is made of.
-  unsigned char* run_dst = nullptr; const unsigned char* run_src = nullptr; size_t run_bytes = 0;
-  auto flush = [&]() -> hipError_t {
-    if (run_bytes == 0) return hipSuccess;
-    const hipError_t e = hipMemcpyAsync(run_dst, run_src, run_bytes, hipMemcpyHostToDevice, c->copy_stream);
-    run_bytes = 0;
-    return e;
-  };
-  for (int i : c->groups[gi].tensors) {
-    const zgr_ctx::HostBasis& h = c->hb[i];
-    const zgr_tensor& t = c->t[i];
-    const size_t width = h.bits == 4 ? (size_t)(t.k + 1) / 2 : (size_t)t.k * 4;
-    const size_t spitch = h.bits == 4 ? (size_t)h.ld : (size_t)h.ld * 4;
-    unsigned char* dst = c->ws + c->cv.spc[slot] + h.slot_off;
-    const unsigned char* src = static_cast<const unsigned char*>(h.host);
-    if (spitch != width) {                                   // strided rows: a 2-D transfer of its own
-      HIP_TRY(c, flush());
-      HIP_TRY(c, hipMemcpy2DAsync(dst, width, src, spitch, width, (size_t)t.rows, hipMemcpyHostToDevice, c->copy_stream));
-      continue;
-    }
-    const size_t bytes = width * (size_t)t.rows;
-    if (run_bytes > 0 && dst - run_dst == src - run_src && (size_t)(dst - run_dst) >= run_bytes && (size_t)(dst - run_dst) <= align_up(run_bytes)) {
-      run_bytes = (size_t)(dst - run_dst) + bytes;           // continues the run (the padding in between is copied along)
-    } else {
-      HIP_TRY(c, flush());
-      run_dst = dst; run_src = src; run_bytes = bytes;
-    }
+// The launch arguments `a` with the staging copies of streamed group gi attached (none past the last group).
+PerturbArgs with_stage(const zgr_ctx* c, PerturbArgs a, size_t gi) {
+  a.n_stage = 0;
+  if (gi < c->groups.size()) {
+    const std::vector<StageCopy>& cp = c->groups[gi].copies;
+    a.n_stage = (int32_t)cp.size();
+    for (size_t j = 0; j < cp.size(); ++j) a.stage[j] = cp[j];
   }
-  HIP_TRY(c, flush());
-  HIP_TRY(c, hipEventRecord(c->ev_copied[slot], c->copy_stream));
-  return ZGR_OK;
+  return a;
 }
 
-// One pass over all parameters with the arguments `a` (single or batched) and coefficient coef: resident guided
-// tensors and isotropic tensors in one launch each, then the streamed groups layer by layer (Sec. 4.3): while the
-// kernel of layer l runs, the bases of layer l + 1 arrive in the other staging slot.
+// One pass over all parameters with the arguments `a` (single or batched) and coefficient coef: isotropic tensors
+// and resident guided tensors in one launch each, then the streamed groups layer by layer (Sec. 4.3): the launch of
+// layer l also pulls the bases of layer l + 1 out of host memory into the other staging slot, so the transfer runs
+// under the arithmetic of layer l and needs no second stream; the first launch of the pass pulls layer 0.
 zgr_status run_pass(zgr_ctx* c, PerturbArgs a, float coef) {
   const WorkItem* tiles = a.tiles;
   a.n_tiles = (int32_t)c->resident_tiles; a.max_k = c->res_max_k; a.min_k = c->res_min_k;
-  zgr_status st = ZGR_OK;
-  if (!c->groups.empty()) {
-    // the bases of the first two layers start moving before any kernel of this pass is queued
-    if ((st = stage_group(c, 0)) != ZGR_OK) return st;
-    if (c->groups.size() > 1 && (st = stage_group(c, 1)) != ZGR_OK) return st;
+  bool staged0 = c->groups.empty();
+  if (a.n_flat > 0) {
+    ProfScope ps(c, ZGR_K_PERTURB_FLAT);
+    HIP_TRY(c, launch_perturb_flat(staged0 ? a : with_stage(c, a, 0), coef, nullptr, c->stream, c->n_cu));
+    staged0 = true;
   }
-  if (a.n_tiles > 0) { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(a, coef, nullptr, c->stream, c->n_cu)); }
-  { ProfScope ps(c, ZGR_K_PERTURB_FLAT); HIP_TRY(c, launch_perturb_flat(a, coef, nullptr, c->stream, c->n_cu)); }
+  if (a.n_tiles > 0) {
+    ProfScope ps(c, ZGR_K_PERTURB_TILE);
+    HIP_TRY(c, launch_perturb_tile(staged0 ? a : with_stage(c, a, 0), coef, nullptr, c->stream, c->n_cu));
+    staged0 = true;
+  }
+  if (!staged0) HIP_TRY(c, launch_stage_only(with_stage(c, a, 0), c->stream));
   for (size_t gi = 0; gi < c->groups.size(); ++gi) {
     const zgr_ctx::Group& g = c->groups[gi];
-    const int slot = (int)(gi & 1);
-    HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_copied[slot], 0));
-    PerturbArgs ag = a;
+    PerturbArgs ag = with_stage(c, a, gi + 1);
     ag.tiles = tiles + g.tile_begin; ag.n_tiles = (int32_t)(g.tile_end - g.tile_begin); ag.n_flat = 0; ag.max_k = g.max_k; ag.min_k = g.min_k;
-    if (ag.n_tiles > 0) { ProfScope ps(c, ZGR_K_PERTURB_TILE); HIP_TRY(c, launch_perturb_tile(ag, coef, nullptr, c->stream, c->n_cu)); }
-    HIP_TRY(c, hipEventRecord(c->ev_used[slot], c->stream));
-    if (gi + 2 < c->groups.size() && (st = stage_group(c, gi + 2)) != ZGR_OK) return st;
+    ProfScope ps(c, ZGR_K_PERTURB_TILE);
+    HIP_TRY(c, launch_perturb_tile(ag, coef, nullptr, c->stream, c->n_cu));
   }
   return ZGR_OK;
 }
@@ -643,39 +632,42 @@ zgr_status zgr_set_basis_q4(zgr_ctx* c, int32_t idx, const uint8_t* Uq, int32_t 
   return ZGR_OK;
 }
 
-zgr_status zgr_set_basis_host(zgr_ctx* c, int32_t idx, const void* U_host, int32_t k, int32_t ld, int32_t bits, float lambda, float delta) {
+zgr_status zgr_set_basis_host(zgr_ctx* c, int32_t idx, const void* U_host, int32_t k, int32_t bits, float lambda, float delta) {
   if (!c) return ZGR_ERR_NULL;
   if (idx < 0 || idx >= (int)c->t.size()) return fail(c, ZGR_ERR_SHAPE, "tensor_index %d out of range", idx);
   if (!U_host) return fail(c, ZGR_ERR_NULL, "U_host is NULL");
   if (bits != 32 && bits != 4) return fail(c, ZGR_ERR_CONFIG, "bits must be 32 (fp32 basis) or 4 (codes)");
   if (k < 1) return fail(c, ZGR_ERR_SHAPE, "k must be >= 1");
-  if (ld < (bits == 4 ? (k + 1) / 2 : k)) return fail(c, ZGR_ERR_SHAPE, "row stride %d too small for k = %d", ld, k);
+  if ((uintptr_t)U_host & 15) return fail(c, ZGR_ERR_SHAPE, "U_host must be 16-byte aligned");
   if (bits == 4 && (!std::isfinite(lambda) || !(lambda > 0.f) || !std::isfinite(delta))) return fail(c, ZGR_ERR_CONFIG, "lambda must be positive and finite, delta finite");
   zgr_tensor t = c->t[idx];
   if (k > kMaxK) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds %d", idx, k, kMaxK);
   if (k > t.rows) return fail(c, ZGR_ERR_SHAPE, "tensor %d: k = %d exceeds rows = %lld", idx, k, (long long)t.rows);
   if (t.cols % group_size(c->cfg.gauss_bits)) return fail(c, ZGR_ERR_SHAPE, "tensor %d: a guided tensor needs cols %% %d == 0", idx, group_size(c->cfg.gauss_bits));
-  if (!c->copy_stream) {
-    HIP_TRY(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
-    for (int i = 0; i < 2; ++i) {
-      HIP_TRY(c, hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming));
-      HIP_TRY(c, hipEventCreateWithFlags(&c->ev_used[i], hipEventDisableTiming));
-    }
+  // the kernels read this memory themselves: it has to be pinned and mapped into the device's address space
+  void* dev = nullptr;
+  if (hipHostGetDevicePointer(&dev, const_cast<void*>(U_host), 0) != hipSuccess || !dev) {
+    (void)hipGetLastError();
+    return fail(c, ZGR_ERR_CONFIG, "U_host is not pinned host memory the device can read (allocate it with hipHostMalloc)");
   }
-  // the group this tensor joins must still fit a staging slot
   const zgr_ctx::HostBasis old_hb = c->hb[idx];
   const zgr_tensor old_t = c->t[idx];
   const zgr_ctx::QBasis old_qb = c->qb[idx];
   t.U = nullptr; t.k = k; t.ldu = bits == 4 ? (k + 1) / 2 : k;
   c->t[idx] = t;
   c->qb[idx] = zgr_ctx::QBasis{};
-  c->hb[idx].host = U_host; c->hb[idx].bits = bits; c->hb[idx].ld = ld; c->hb[idx].lambda = lambda; c->hb[idx].delta = delta;
-  size_t need = 0;
+  c->hb[idx].host = U_host; c->hb[idx].dev = static_cast<const unsigned char*>(dev); c->hb[idx].bits = bits;
+  c->hb[idx].lambda = lambda; c->hb[idx].delta = delta;
+  // the layer this tensor joins must still fit a staging slot and one launch's list of pieces
+  size_t need = 0, members = 0;
   for (size_t i = 0; i < c->t.size(); ++i)
-    if (is_streamed(c, i) && c->t[i].layer == t.layer)
+    if (is_streamed(c, i) && c->t[i].layer == t.layer) {
       need += align_up((size_t)c->t[i].rows * (c->hb[i].bits == 4 ? (size_t)(c->t[i].k + 1) / 2 : (size_t)c->t[i].k * 4));
-  if (need > c->cv.spc_bytes) {
+      ++members;
+    }
+  if (need > c->cv.spc_bytes || members > (size_t)kMaxStage) {
     c->t[idx] = old_t; c->hb[idx] = old_hb; c->qb[idx] = old_qb;
+    if (members > (size_t)kMaxStage) return fail(c, ZGR_ERR_SHAPE, "more than %d streamed tensors in layer %d", kMaxStage, t.layer);
     return fail(c, ZGR_ERR_WORKSPACE, "the bases of layer %d need %zu bytes of staging, the workspace holds %zu (sized from the ranks given to zgr_workspace_bytes)", t.layer, need, c->cv.spc_bytes);
   }
   build_lists(c);
@@ -788,11 +780,6 @@ void zgr_destroy(zgr_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
-  if (c->copy_stream) {
-    (void)hipStreamSynchronize(c->copy_stream);
-    for (int i = 0; i < 2; ++i) { (void)hipEventDestroy(c->ev_copied[i]); (void)hipEventDestroy(c->ev_used[i]); }
-    (void)hipStreamDestroy(c->copy_stream);
-  }
   delete c;
 }
 
@@ -860,16 +847,14 @@ zgr_status zgr_debug_fill_z(zgr_ctx* c, int32_t idx, uint64_t step, float* Z) {
   if (!fl.empty()) { a.flat = dbg; a.n_flat = (int32_t)fl.size(); a.n_tiles = 0; HIP_TRY(c, launch_perturb_flat(a, 0.f, Z, c->stream, c->n_cu)); }
   else {
     a.tiles = dbg; a.n_tiles = (int32_t)tl.size(); a.n_flat = 0; a.max_k = a.min_k = c->t[idx].k;
-    int slot = -1;
     if (is_streamed(c, (size_t)idx)) {
       // bring the bases of this tensor's layer into their staging slot first
       for (size_t gi = 0; gi < c->groups.size(); ++gi)
         for (int i : c->groups[gi].tensors)
-          if (i == idx) { if ((st = stage_group(c, gi)) != ZGR_OK) return st; slot = (int)(gi & 1); }
-      if (slot >= 0) HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_copied[slot], 0));
+          if (i == idx) HIP_TRY(c, launch_stage_only(with_stage(c, a, gi), c->stream));
     }
+    a.n_stage = 0;
     HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu));
-    if (slot >= 0) HIP_TRY(c, hipEventRecord(c->ev_used[slot], c->stream));
   }
   return ZGR_OK;
 }

@@ -34,6 +34,15 @@ constexpr int kFlatGroupsPerItem = 2048;   // Philox calls per flat work item (8
 constexpr int kTileRowsPerIter   = 128;    // rows one block covers per iteration (4 waves x 32)
 constexpr int kMaxK              = 64;
 constexpr int kMaxBatch          = 8;      // perturbations summed in one pass (zgr_apply_updates)
+constexpr int kMaxStage          = 16;     // tensors whose bases one launch may pull in for the next one
+constexpr int kPullBlocks        = 32;     // blocks of such a launch that do the pulling
+
+// One contiguous piece of basis data to copy from (pinned, device-visible) host memory into a staging slot.
+struct StageCopy {
+  const unsigned char* src;
+  unsigned char*       dst;
+  uint64_t             bytes;
+};
 
 struct PerturbArgs {
   const TensorDesc* descs;     // device
@@ -50,6 +59,10 @@ struct PerturbArgs {
   int32_t           n_q;
   uint32_t          qstep[kMaxBatch];
   float             qcoef[kMaxBatch];
+  // bases of the NEXT launch's tensors, pulled over the host link by this launch while it computes
+  int32_t           n_stage;
+  int32_t           pull_blocks;   // set by the launchers: the last pull_blocks blocks of the grid only copy, the others only compute
+  StageCopy         stage[kMaxStage];
 };
 
 // theta += c * Z for everything in the flat / tile work list.  zout != nullptr:
@@ -65,6 +78,8 @@ hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t 
                               float* out, hipStream_t s);
 hipError_t launch_debug_radius_table(int bits, float* out, hipStream_t s);
 hipError_t launch_debug_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// only the staging copies of `a` (used when a pass has no other launch in front of its first streamed layer)
+hipError_t launch_stage_only(const PerturbArgs& a, hipStream_t s);
 // affine quantiser of a basis: min / max of U[rows, k] (row stride ldu) into minmax[2] (device), then the 4-bit codes
 hipError_t launch_basis_minmax(const float* U, int64_t rows, int k, int ldu, float* minmax, hipStream_t s);
 hipError_t launch_basis_quantize(const float* U, int64_t rows, int k, int ldu, float lambda, float delta, uint8_t* Uq, int ldq, hipStream_t s);

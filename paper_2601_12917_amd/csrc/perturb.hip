@@ -64,6 +64,24 @@ __device__ __forceinline__ float basis_at(const TensorDesc& d, int64_t row, int 
   return load_global<float>(d.U + row * d.ldu + l);
 }
 
+// Layer pipeline (Sec. 4.3): a launch also fetches the basis data its successor will need, straight from pinned
+// host memory into the staging slot the successor reads.  The last a.pull_blocks blocks of the grid do nothing
+// else (a block that waited for the host link before computing would delay its share of the tiles by that long);
+// the other blocks share the work list among themselves.  The kernel boundary makes the data visible.
+__device__ __forceinline__ void pull_next_stage(const PerturbArgs& a, int part, int parts) {
+  for (int t = 0; t < a.n_stage; ++t) {
+    const StageCopy sc = a.stage[t];
+    const uint64_t n16 = sc.bytes >> 4;
+    const uint4* src = reinterpret_cast<const uint4*>(sc.src);
+    uint4* dst = reinterpret_cast<uint4*>(sc.dst);
+    for (uint64_t i = (uint64_t)part * blockDim.x + threadIdx.x; i < n16; i += (uint64_t)parts * blockDim.x) dst[i] = src[i];
+    if (part == 0)
+      for (uint64_t i = (n16 << 4) + threadIdx.x; i < sc.bytes; i += blockDim.x) sc.dst[i] = sc.src[i];
+  }
+}
+
+__global__ void __launch_bounds__(256) stage_only_kernel(PerturbArgs a) { pull_next_stage(a, blockIdx.x, gridDim.x); }
+
 // The P Gaussians of Philox call q of one stream.  BATCH: instead the combination sum_i qcoef[i] * (those of step
 // qstep[i]), accumulated in the order of the list; since Z is linear in (G, R), a batched pass is the single
 // pass with this combination in place of G and of R and the coefficient 1.
@@ -93,9 +111,11 @@ template <typename T, int P, bool WRITE_Z, bool BATCH>
 __global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
                                                            float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout) {
   __shared__ RadiusEntry tab[kRadiusTabEntries];
+  const int nblk = (int)gridDim.x - a.pull_blocks;               // computing blocks
+  if ((int)blockIdx.x >= nblk) { pull_next_stage(a, (int)blockIdx.x - nblk, a.pull_blocks); return; }
   load_radius_table(tab, gtab);
   __syncthreads();
-  for (int w = blockIdx.x; w < a.n_flat; w += gridDim.x) {
+  for (int w = blockIdx.x; w < a.n_flat; w += nblk) {
     const WorkItem it = items[w];
     const TensorDesc d = descs[it.tensor];
     const int64_t n = d.rows * d.cols;
@@ -158,11 +178,13 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
   float* Rs = Us + kTileRowsPerIter * kp;            // [kp][TC]
   constexpr int TC = 32 * P;
   constexpr int RB = (P == 4) ? 16 : 8;              // rows a lane holds at once
+  const int nblk = (int)gridDim.x - a.pull_blocks;               // computing blocks
+  if ((int)blockIdx.x >= nblk) { pull_next_stage(a, (int)blockIdx.x - nblk, a.pull_blocks); return; }
   load_radius_table(tab, gtab);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cg = lane & 31, rh = lane >> 5;
 
-  for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
+  for (int w = blockIdx.x; w < a.n_tiles; w += nblk) {
     const WorkItem it = items[w];
     const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
@@ -301,10 +323,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   RadiusEntry* tab = reinterpret_cast<RadiusEntry*>(smem);
   float* Rs = smem + kRadiusTabEntries * 3;          // [kp][TC]
   constexpr int TC = 32 * P;
+  const int nblk = (int)gridDim.x - a.pull_blocks;               // computing blocks
+  if ((int)blockIdx.x >= nblk) { pull_next_stage(a, (int)blockIdx.x - nblk, a.pull_blocks); return; }
   load_radius_table(tab, gtab);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, rg = lane >> 4;
-  for (int w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
+  for (int w = blockIdx.x; w < a.n_tiles; w += nblk) {
     const WorkItem it = items[w];
     const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
@@ -480,18 +504,30 @@ int resident_blocks_per_cu(K kern, size_t dyn_lds, int cap) {
   return nb < cap ? nb : cap;
 }
 
+// Grid of a persistent launch: as many computing blocks as there are items, at most the resident capacity, the
+// last kPullBlocks of that capacity set aside for pulling the next stage's bases when there are any to pull.
+int split_grid(PerturbArgs& a, int items, int capacity) {
+  a.pull_blocks = a.n_stage > 0 ? kPullBlocks : 0;
+  int compute = capacity - a.pull_blocks;
+  if (compute < 1) compute = 1;
+  if (compute > items) compute = items;
+  return compute + a.pull_blocks;
+}
+
 template <typename T, int P>
-hipError_t launch_flat_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
+hipError_t launch_flat_t(const PerturbArgs& a_in, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
+  PerturbArgs a = a_in;
   auto kern = zout ? perturb_flat_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_flat_kernel<T, P, false, true> : perturb_flat_kernel<T, P, false, false>);
   static int per[3] = {0, 0, 0};
   int& nb = per[zout ? 1 : (a.n_q > 0 ? 2 : 0)];
   if (nb == 0) nb = resident_blocks_per_cu(kern, 0, 8);
-  const int grid = a.n_flat < n_cu * nb ? a.n_flat : n_cu * nb;
+  const int grid = split_grid(a, a.n_flat, n_cu * nb);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, c, tab, zout);
   return hipGetLastError();
 }
 template <typename T, int P>
-hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
+hipError_t launch_tile_t(const PerturbArgs& a_in, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
+  PerturbArgs a = a_in;
   const int kp = (a.max_k + 7) & ~7;
   const size_t lds = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kTileRowsPerIter * kp + (size_t)kp * 32 * P);
   if (a.min_k >= kMfmaMinK) {
@@ -500,7 +536,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);
     if (e != hipSuccess) return e;
     const int per = resident_blocks_per_cu(km, lds_m, 8);
-    const int grid_m = a.n_tiles < n_cu * per ? a.n_tiles : n_cu * per;
+    const int grid_m = split_grid(a, a.n_tiles, n_cu * per);
     hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, a.descs, a.tiles, c, tab, zout, kp);
     return hipGetLastError();
   }
@@ -508,7 +544,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   const int per_cu = resident_blocks_per_cu(kern, lds, 4);
-  const int grid = a.n_tiles < n_cu * per_cu ? a.n_tiles : n_cu * per_cu;
+  const int grid = split_grid(a, a.n_tiles, n_cu * per_cu);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, a.descs, a.tiles, c, tab, zout, kp);
   return hipGetLastError();
 }
@@ -517,6 +553,7 @@ hipError_t launch_tile_t(const PerturbArgs& a, float c, float* zout, hipStream_t
 hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu) {
   if (a.n_flat <= 0) return hipSuccess;
   if (a.n_q < 0 || a.n_q > kMaxBatch || (a.n_q > 0 && zout)) return hipErrorInvalidValue;
+  if (a.n_stage < 0 || a.n_stage > kMaxStage) return hipErrorInvalidValue;
   const RadiusEntry* tab = nullptr;
   hipError_t e = ensure_radius_table(&tab);
   if (e != hipSuccess) return e;
@@ -528,6 +565,8 @@ hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipSt
   if (a.n_tiles <= 0) return hipSuccess;
   if (a.max_k < 1 || a.max_k > kMaxK) return hipErrorInvalidValue;
   if (a.n_q < 0 || a.n_q > kMaxBatch || (a.n_q > 0 && zout)) return hipErrorInvalidValue;
+  if (a.n_stage < 0 || a.n_stage > kMaxStage) return hipErrorInvalidValue;
+  if (a.n_stage < 0 || a.n_stage > kMaxStage) return hipErrorInvalidValue;
   const RadiusEntry* tab = nullptr;
   hipError_t e = ensure_radius_table(&tab);
   if (e != hipSuccess) return e;
@@ -549,6 +588,13 @@ hipError_t launch_basis_quantize(const float* U, int64_t rows, int k, int ldu, f
   const int64_t n = rows * ((k + 1) / 2);
   const int grid = (int)(n / 256 + 1 < 1024 ? n / 256 + 1 : 1024);
   hipLaunchKernelGGL(basis_quantize_kernel, dim3(grid), dim3(256), 0, s, U, rows, k, ldu, lambda, delta, Uq, ldq);
+  return hipGetLastError();
+}
+
+hipError_t launch_stage_only(const PerturbArgs& a, hipStream_t s) {
+  if (a.n_stage <= 0) return hipSuccess;
+  if (a.n_stage > kMaxStage) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stage_only_kernel, dim3(kPullBlocks), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -144,13 +144,15 @@ class Session:
         return q.cpu().numpy(), lam.value, delta.value
 
     def set_basis_host(self, index, U: np.ndarray, k, codes=None, lam=0.0, delta=0.0):
-        """Keep the basis of one tensor in pinned host memory and stream it per layer during the passes.
-        codes: packed 4-bit codes [rows, ldq] instead of U (then lam, delta are their scale and zero point)."""
-        src = np.ascontiguousarray(codes, dtype=np.uint8) if codes is not None else np.ascontiguousarray(U, dtype=np.float32)
+        """Keep the basis of one tensor in pinned host memory (compact rows of its first k columns) and let the
+        kernels stream it per layer during the passes.  codes: packed 4-bit codes [rows, (k+1)//2] instead of U
+        (then lam, delta are their scale and zero point)."""
+        src = (np.ascontiguousarray(codes[:, :(k + 1) // 2], dtype=np.uint8) if codes is not None
+               else np.ascontiguousarray(U[:, :k], dtype=np.float32))
         t = torch.from_numpy(src).pin_memory()
         self.Uhost = getattr(self, "Uhost", {})
         self.Uhost[index] = t
-        B.check(self.lib.zgr_set_basis_host(self.ctx, index, t.data_ptr(), k, src.shape[1], 4 if codes is not None else 32,
+        B.check(self.lib.zgr_set_basis_host(self.ctx, index, t.data_ptr(), k, 4 if codes is not None else 32,
                                             float(lam), float(delta)), self.ctx)
 
     def set_layer_bases_host(self, indices, arrays, k, codes=False, lams=None, deltas=None):
@@ -170,7 +172,7 @@ class Session:
         self.Uhost = getattr(self, "Uhost", {})
         for j, (i, o) in enumerate(zip(indices, offs)):
             self.Uhost[i] = block
-            B.check(self.lib.zgr_set_basis_host(self.ctx, i, block.data_ptr() + o, k, width if codes else k, 4 if codes else 32,
+            B.check(self.lib.zgr_set_basis_host(self.ctx, i, block.data_ptr() + o, k, 4 if codes else 32,
                                                 float(lams[j]) if codes else 0.0, float(deltas[j]) if codes else 0.0), self.ctx)
 
     def compress_basis(self, index):

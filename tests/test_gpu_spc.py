@@ -108,6 +108,10 @@ def test_streamed_basis_can_be_replaced_and_is_bounded_by_the_workspace():
     with pytest.raises(Exception):
         sess.set_basis_host(i, wide, 4 * cfg.k)                      # four times the rank the slots were sized for
     assert np.array_equal(sess.fill_z(i, 5), z_res)                  # the refused call changed nothing
-    with pytest.raises(Exception):
-        sess.set_basis_host(i, bases[i], cfg.k, codes=np.zeros((rows, 1), np.uint8), lam=1.0)   # row stride too small
+    # pageable host memory is refused (the kernels read the bases themselves: they must be pinned and mapped)
+    from paper_2601_12917_amd import binding as B
+    pageable = np.ascontiguousarray(bases[i][:, :cfg.k])
+    st = sess.lib.zgr_set_basis_host(sess.ctx, i, pageable.ctypes.data, cfg.k, 32, 0.0, 0.0)
+    assert st == B.ZGR_ERR_CONFIG
+    assert np.array_equal(sess.fill_z(i, 5), z_res)
     sess.close()
