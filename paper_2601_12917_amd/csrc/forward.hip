@@ -279,6 +279,21 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // Residual epilogue on the smaller tiles: this lane's part of the residual stream is requested now, ahead of
+  // every operand transfer (loads complete in order, so the vmcnt counts of the main loop still only see the
+  // transfers), and has long arrived when the epilogue adds to it; only the write-back remains exposed there.
+  constexpr bool PRE_RES = MODE == EPI_RESID && FM * FN <= 4;
+  const bool pre_res = PRE_RES && m0 + BM <= M && n0 + BN <= N;
+  float res[PRE_RES ? FM * FN * 16 : 1];
+  if (PRE_RES && pre_res) {
+    const float* rp = reinterpret_cast<const float*>(out) + (size_t)(m0 + wm * (BM / WM) + 4 * (lane >> 5)) * N + n0 + wn * (BN / WN) + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) res[(i * FN + j) * 16 + v] = rp[(size_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * N + j * 32];
+  }
   const int nk = K / BK;
   auto issue = [&](int kt, int buf) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -365,7 +380,16 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
     bv[j] = (bias && n < N) ? to_f32(bias[n]) : 0.f;
   }
   const int mbase = m0 + wm * (BM / WM) + 4 * (lane >> 5), nbase = n0 + wn * (BN / WN) + l32;
-  if (m0 + BM <= M && n0 + BN <= N) {
+  if (PRE_RES && pre_res) {
+    float* op = reinterpret_cast<float*>(out) + (size_t)mbase * N + nbase;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          op[(size_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * N + j * 32] = res[(i * FN + j) * 16 + v] + (acc[i][j][v] + bv[j]);
+  } else if (m0 + BM <= M && n0 + BN <= N) {
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
