@@ -66,37 +66,44 @@ def cpu_baseline(cfg, specs, budget_note=True):
         pass
     d, ff, V, T = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.seq
     rng = np.random.default_rng(0)
-    # (i) one perturbation pass over one guided d x d matrix
-    q, _ = np.linalg.qr(rng.standard_normal((d, cfg.k)))
-    U = q.astype(np.float32)
-    W = (rng.standard_normal((d, d)) * 0.02).astype(np.float32)
-    t0 = time.perf_counter()
-    Z = P.hybrid_z(cfg.seed, 0, 7, d, d, U, cfg.k, cfg.alpha)
-    P.axpy_inplace_value(W, np.float32(cfg.eps), Z, cfg.dtype)
-    t_pass = time.perf_counter() - t0
+    # (i) one perturbation pass over the guided matrices of one block
+    layer0 = [sp for sp in specs if sp.guided and sp.layer == 0]
+    t_pass, sampled = 0.0, 0
+    for sp in layer0:
+        q, _ = np.linalg.qr(rng.standard_normal((sp.rows, cfg.k)))
+        U = q.astype(np.float32)
+        W = (rng.standard_normal((sp.rows, sp.cols)) * 0.02).astype(np.float32)
+        t0 = time.perf_counter()
+        Z = P.hybrid_z(cfg.seed, 0, sp.tensor_id, sp.rows, sp.cols, U, cfg.k, cfg.alpha)
+        P.axpy_inplace_value(W, np.float32(cfg.eps), Z, cfg.dtype)
+        t_pass += time.perf_counter() - t0
+        sampled += sp.numel
+        del Z, W
     total_params = sum(s.numel for s in specs)
-    # (ii) one transformer block + the vocabulary projection and loss on one sequence
-    one = I.shrink(cfg, name="cpu_sample", n_layer=1, batch=1)
+    # (ii) two transformer blocks + the vocabulary projection and loss on a quarter of the batch
+    nb, nl = max(1, cfg.batch // 4), min(2, cfg.n_layer)
+    one = I.shrink(cfg, name="cpu_sample", n_layer=nl, batch=nb)
     sspecs = I.tensor_specs(one)
     Pd = {s.name: (rng.standard_normal((s.rows, s.cols)) * 0.02) for s in sspecs}
-    for n in ("l0.ln1_g", "l0.ln2_g", "lnf_g"):
+    for n in [f"l{i}.ln1_g" for i in range(nl)] + [f"l{i}.ln2_g" for i in range(nl)] + ["lnf_g"]:
         Pd[n] = Pd[n] + 1.0
-    tok = rng.integers(0, V, size=(1, T))
+    tok = rng.integers(0, V, size=(nb, T))
     t0 = time.perf_counter()
     x = Pd["tok_emb"][tok] + Pd["pos_emb"][:T][None]
-    x = F.block(x, Pd, 0, cfg.n_head, True, None, cfg.ln_eps)
-    t_layer = time.perf_counter() - t0
+    for i in range(nl):
+        x = F.block(x, Pd, i, cfg.n_head, True, None, cfg.ln_eps)
+    t_layers = time.perf_counter() - t0
     t0 = time.perf_counter()
     h = F.layer_norm(x, Pd["lnf_g"], Pd["lnf_b"], cfg.ln_eps)
     logp = F.log_softmax(h[:, :-1] @ Pd["tok_emb"].T)
     float(-np.take_along_axis(logp, tok[:, 1:, None], axis=-1).mean())
     t_head = time.perf_counter() - t0
-    fwd = cfg.batch * (cfg.n_layer * t_layer + t_head)
-    step_s = 4.0 * t_pass * total_params / (d * d) + 2.0 * fwd
+    fwd = (cfg.batch / nb) * (cfg.n_layer / nl * t_layers + t_head)
+    step_s = 4.0 * t_pass * total_params / sampled + 2.0 * fwd
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": (f"one perturbation pass over one {d}x{d} guided matrix ({t_pass:.2f} s) scaled to {total_params} parameters x 4 passes; "
-                       f"one block ({t_layer:.2f} s) and the vocabulary projection + loss ({t_head:.2f} s) on one {T}-token sequence, "
-                       f"scaled to {cfg.n_layer} blocks x {cfg.batch} sequences x 2 forwards")}
+            "sample": (f"one perturbation pass over the {len(layer0)} guided matrices of one block ({sampled} parameters, {t_pass:.2f} s) scaled to "
+                       f"{total_params} parameters x 4 passes; {nl} blocks ({t_layers:.2f} s) and the vocabulary projection + loss ({t_head:.2f} s) on "
+                       f"{nb} sequences of {T} tokens, scaled to {cfg.n_layer} blocks x {cfg.batch} sequences x 2 forwards")}
 
 
 def main():
