@@ -114,7 +114,9 @@ typedef struct {
  *   DECODER_LM : x = int32 tokens [batch, seq]; y, lengths unused (targets are x shifted by one).
  *   ENCODER_CLS: x = int32 tokens [batch, seq]; y = int32 labels [batch]; lengths = int32 [batch],
  *                keys at positions >= lengths[b] are masked out.
- *   LINEAR_LSQ : x = fp32 X [batch, in]; y = fp32 Y [batch, out]; seq ignored.                */
+ *   LINEAR_LSQ : x = fp32 X [batch, in]; y = fp32 Y [batch, out]; seq ignored.
+ * 1 <= batch <= max_batch; seq <= min(max_seq, max_pos), seq >= 2 for DECODER_LM (a next-token
+ * target needs two tokens), seq >= 1 for ENCODER_CLS; lengths[b] in [1, seq].                 */
 typedef struct {
   const void*    x;
   const void*    y;

@@ -482,7 +482,8 @@ zgr_status check_batch(zgr_ctx* c, const zgr_batch* b) {
   if (m.arch == ZGR_ARCH_NONE) return fail(c, ZGR_ERR_STATE, "this context has no model: it can only perturb and update");
   if (b->batch < 1 || b->batch > c->max_batch) return fail(c, ZGR_ERR_SHAPE, "batch = %d outside [1, %d]", b->batch, c->max_batch);
   if (m.arch == ZGR_ARCH_LINEAR_LSQ) { if (!b->y) return fail(c, ZGR_ERR_NULL, "batch->y is NULL"); return ZGR_OK; }
-  if (b->seq < 2 || b->seq > c->max_seq || b->seq > m.max_pos) return fail(c, ZGR_ERR_SHAPE, "seq = %d outside [2, min(%d, %d)]", b->seq, c->max_seq, m.max_pos);
+  const int min_seq = m.arch == ZGR_ARCH_DECODER_LM ? 2 : 1;      // a next-token target needs two tokens; a classifier reads the first
+  if (b->seq < min_seq || b->seq > c->max_seq || b->seq > m.max_pos) return fail(c, ZGR_ERR_SHAPE, "seq = %d outside [%d, min(%d, %d)]", b->seq, min_seq, c->max_seq, m.max_pos);
   if (m.arch == ZGR_ARCH_ENCODER_CLS && (!b->y || !b->lengths)) return fail(c, ZGR_ERR_NULL, "the classifier needs labels and lengths");
   return ZGR_OK;
 }

@@ -63,6 +63,32 @@ def test_loss_and_row_losses_match_oracle(cfg):
     sess.close()
 
 
+@pytest.mark.parametrize("base,kw", [
+    (TINY_LM, dict(batch=1, seq=2)),            # the shortest sequence with a next-token target
+    (TINY_LM, dict(batch=1, seq=13)),           # odd length, a single sequence
+    (SMALL_BF16_LM, dict(batch=1, seq=2)),
+    (SMALL_BF16_LM, dict(batch=2, seq=37)),     # not a multiple of any tile
+    (TINY_CLS, dict(batch=1, seq=1)),           # one token: attention over a single key
+    (SMALL_BF16_CLS, dict(batch=3, seq=5)),
+], ids=lambda x: x.name if hasattr(x, "name") else "-".join(f"{k}{v}" for k, v in x.items()))
+def test_degenerate_batch_shapes(base, kw):
+    """Loss parity at the smallest and at ragged batch shapes, and with every valid length down to one key."""
+    cfg = I.shrink(base, name=base.name + "_edge", max_pos=max(base.max_pos, kw["seq"]), **kw)
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    if arrays["lengths"] is not None:
+        arrays["lengths"] = np.minimum(np.arange(1, cfg.batch + 1, dtype=np.int32), cfg.seq).astype(np.int32)   # 1, 2, 3 ... valid tokens
+    sess = make_session(cfg, specs, values, bases)
+    got = sess.loss(session_batch(sess, cfg, arrays))
+    Pd = _params_dict(specs, values)
+    if cfg.arch == I.ARCH_DECODER_LM:
+        want = F.lm_token_losses(Pd, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps).mean()
+    else:
+        want = F.cls_row_losses(Pd, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps).mean()
+    assert np.isfinite(got) and abs(got - want) <= LOSS_RTOL[cfg.dtype] * abs(want), (got, want)
+    sess.close()
+
+
 def test_cfg1_trajectory_matches_oracle():
     cfg = I.CONFIGS["cfg1"]
     specs, values, bases = inputs_of(cfg)
