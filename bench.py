@@ -25,6 +25,11 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
+# vector instructions per Philox call of 4 elements on the main path of the bf16 / 32-bit-mode kernels (counted in the ISA)
+VALU_PER_CALL = {"perturb_flat": 202, "perturb_tile": 212}
+ALU_PEAK_TINSTR = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
 def load_traffic():
     """HBM bytes per launch from the committed counter runs, or {} when the kernels changed since."""
     try:
@@ -244,6 +249,17 @@ def main():
             gbs = 2.0 * flat_elems * es / (k1["ms_avg"] * 1e-3) / 1e9
             out["roofline_perturb_flat"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                                             "traffic": kernel_traffic(traffic, "perturb_flat"), "kernel": "perturb_flat_kernel"}
+        # What really bounds the perturbation passes: vector-ALU issue.  One Philox call (4 Gaussians, 32-bit mode) costs
+        # VALU_PER_CALL wave64 vector instructions (static count of the kernels' main paths); a SIMD issues one per 4
+        # cycles (16 lanes), i.e. 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instructions/s (the 157.3 TFLOP/s
+        # fp32 vector figure counts packed FMAs as 4 flops per lane-instruction; packed fp32 is not used here).
+        if args.gauss_bits == 32 and cfg.dtype == "bf16":
+            for name, elems, key in (("perturb_tile", guided_elems, "roofline_perturb"), ("perturb_flat", flat_elems, "roofline_perturb_flat")):
+                if name in kern and key in out and elems:
+                    lane_instr = VALU_PER_CALL[name] * elems / 4.0
+                    ach = lane_instr / (kern[name]["ms_avg"] * 1e-3) / 1e12
+                    out[key]["alu"] = {"bound": "alu", "achieved": ach, "peak": ALU_PEAK_TINSTR, "unit": "T lane-instr/s", "frac": ach / ALU_PEAK_TINSTR,
+                                       "valu_instructions_per_philox_call": VALU_PER_CALL[name]}
         if "gemm" in kern and cfg.arch != I.ARCH_LINEAR_LSQ:
             gm = kern["gemm"]
             flops_per_launch = 2.0 * profiled_steps * forward_gemm_flops(cfg) / gm["launches"]
