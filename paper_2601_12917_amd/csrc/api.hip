@@ -127,8 +127,9 @@ void append_items(const zgr_tensor& t, int index, bool guided, int P, std::vecto
       flat.push_back({index, (int32_t)std::min<int64_t>(kFlatGroupsPerItem, groups - g0), g0});
   } else {
     const int64_t tr = tile_rows_of(t.rows), tc = 32 * P;
-    for (int64_t r0 = 0; r0 < t.rows; r0 += tr)
-      for (int64_t c0 = 0; c0 < t.cols; c0 += tc)
+    // column strips outermost: the kernels keep a strip's slice of R in LDS across its consecutive row tiles
+    for (int64_t c0 = 0; c0 < t.cols; c0 += tc)
+      for (int64_t r0 = 0; r0 < t.rows; r0 += tr)
         tiles.push_back({index, (int32_t)std::min<int64_t>(tr, t.rows - r0), (r0 << 32) | c0});
   }
 }

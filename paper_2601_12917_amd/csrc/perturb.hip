@@ -184,15 +184,23 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int cg = lane & 31, rh = lane >> 5;
 
-  for (int w = blockIdx.x; w < a.n_tiles; w += nblk) {
+  // A block takes a contiguous run of the list; the list orders the row tiles of one column strip one after the
+  // other, so the slice of R in LDS is regenerated only when the strip (or the tensor) changes.
+  const int per_block = (a.n_tiles + nblk - 1) / nblk;
+  const int w_end = min(a.n_tiles, ((int)blockIdx.x + 1) * per_block);
+  int prev_tensor = -1;
+  int64_t prev_col0 = -1;
+  for (int w = (int)blockIdx.x * per_block; w < w_end; ++w) {
     const WorkItem it = items[w];
     const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
     const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
-    __syncthreads();                                 // table loaded / previous tile's readers done
-    // this tile's slice of b*R: rows l < k, columns col0 .. col0+TC
-    for (int idx = tid; idx < kpt * 32; idx += 256) {
+    const bool same_strip = it.tensor == prev_tensor && col0 == prev_col0;
+    prev_tensor = it.tensor; prev_col0 = col0;
+    if (!same_strip) __syncthreads();                // table loaded / previous strip's readers of Rs done
+    // this strip's slice of b*R: rows l < k, columns col0 .. col0+TC
+    for (int idx = tid; idx < (same_strip ? 0 : kpt * 32); idx += 256) {
       const int l = idx >> 5, g = idx & 31;
       const int64_t col = col0 + (int64_t)g * P;
       float r[P];
@@ -208,7 +216,7 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
       for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
     }
     for (int r0 = 0; r0 < nrows; r0 += kTileRowsPerIter) {
-      if (r0 > 0) __syncthreads();                   // previous row block's readers of Us done
+      __syncthreads();                               // Rs written / previous row block's readers of Us done
       for (int idx = tid; idx < kTileRowsPerIter * kpt; idx += 256) {
         const int r = idx / kpt, l = idx - r * kpt;
         const int64_t row = row0 + r0 + r;
@@ -328,14 +336,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   load_radius_table(tab, gtab);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, rg = lane >> 4;
-  for (int w = blockIdx.x; w < a.n_tiles; w += nblk) {
+  // contiguous run of the list per block; R slice regenerated only when the column strip changes (see above)
+  const int per_block = (a.n_tiles + nblk - 1) / nblk;
+  const int w_end = min(a.n_tiles, ((int)blockIdx.x + 1) * per_block);
+  int prev_tensor = -1;
+  int64_t prev_col0 = -1;
+  for (int w = (int)blockIdx.x * per_block; w < w_end; ++w) {
     const WorkItem it = items[w];
     const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
     const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kq4 = kpt >> 2;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
-    __syncthreads();                                 // table loaded / previous tile's readers of Rs done
-    for (int idx = tid; idx < kpt * 32; idx += 256) {
+    const bool same_strip = it.tensor == prev_tensor && col0 == prev_col0;
+    prev_tensor = it.tensor; prev_col0 = col0;
+    if (!same_strip) __syncthreads();                // table loaded / previous strip's readers of Rs done
+    for (int idx = tid; idx < (same_strip ? 0 : kpt * 32); idx += 256) {
       const int l = idx >> 5, g = idx & 31;
       const int64_t col = col0 + (int64_t)g * P;
       float r[P];
@@ -349,7 +364,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
       for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
     }
-    __syncthreads();
+    if (!same_strip) __syncthreads();
     const bool full = (nrows % 64 == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
     for (int r0 = 0; r0 < nrows; r0 += 64) {
       if (full) mfma_row_block<T, P, WRITE_Z, BATCH, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
