@@ -503,15 +503,18 @@ __global__ void __launch_bounds__(256) attention_kernel(const T* __restrict__ qk
 // registers into the B operand of the second product (the contraction order of that product is the
 // accumulator's key order, which the V^T operand is read in as well).
 constexpr int AT_LDK = 64 + 8;          // K row stride (bf16): 144 B
-template <int DH>
-__global__ void __launch_bounds__(256) attention_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, const int32_t* __restrict__ lengths,
-                                                             int seq, int d, int n_head, int causal, int kpad) {
+// NW waves per block, 32 queries each: with NW = 8 one block covers 256 queries of a head, so K and V^T of a
+// 256-token sequence are staged once per head instead of once per 128 queries.
+template <int DH, int NW>
+__global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, const int32_t* __restrict__ lengths,
+                                                                 int seq, int d, int n_head, int causal, int kpad) {
   static_assert(DH == 64, "head size 64");
+  constexpr int QB = 32 * NW, NT = 64 * NW;                     // queries and threads per block
   extern __shared__ __attribute__((aligned(16))) unsigned char asm_[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(asm_);                 // [kpad][AT_LDK]
   bf16_t* Vt = Ks + (size_t)kpad * AT_LDK;                      // [DH][kpad + 8]
   const int ldv = kpad + 8;
-  const int qblocks = (seq + 127) / 128;
+  const int qblocks = (seq + QB - 1) / QB;
   const int qb = blockIdx.x % qblocks, h = (blockIdx.x / qblocks) % n_head, b = blockIdx.x / (qblocks * n_head);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
   const int len = lengths ? min(lengths[b], seq) : seq;
@@ -519,10 +522,10 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const bf16_t* __res
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)h * DH;
   // keys this block can need, rounded up to 32
   int kend = len;
-  if (causal) kend = min(kend, qb * 128 + 128);
+  if (causal) kend = min(kend, qb * QB + QB);
   const int kblocks = (kend + 31) / 32;
   // stage K and V^T (zero beyond seq so masked products stay finite)
-  for (int i = tid; i < kblocks * 32 * 8; i += 256) {
+  for (int i = tid; i < kblocks * 32 * 8; i += NT) {
     const int r = i >> 3, c = (i & 7) * 8;
     uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
     if (r < seq) {
@@ -535,7 +538,7 @@ __global__ void __launch_bounds__(256) attention_mfma_kernel(const bf16_t* __res
     for (int j = 0; j < 8; ++j) Vt[(c + j) * ldv + r].bits = ve[j];
   }
   // this wave's queries: B operand of S^T = K Q^T, lane (query l32, k-group half) holds Q[q][16 s + 8 half .. +8]
-  const int q0 = qb * 128 + wave * 32;
+  const int q0 = qb * QB + wave * 32;
   const int qi = q0 + l32;
   bf16x8 qf[DH / 16];
 #pragma unroll
@@ -773,12 +776,19 @@ hipError_t launch_attention(int dtype, const void* qkv, void* ctx, const int32_t
     const size_t lds = sizeof(bf16_t) * ((size_t)kpad * AT_LDK + (size_t)64 * (kpad + 8));
     static bool attr_set = false;
     if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel<64, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel<64, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    const int grid = batch * n_head * ((seq + 127) / 128);
-    hipLaunchKernelGGL(attention_mfma_kernel<64>, dim3(grid), dim3(256), lds, s, (const bf16_t*)qkv, (bf16_t*)ctx, lengths, seq, d, n_head, causal, kpad);
+    if (seq > 128) {      // 256 queries per block: the keys of a head are staged once per 256 queries
+      const int grid = batch * n_head * ((seq + 255) / 256);
+      hipLaunchKernelGGL((attention_mfma_kernel<64, 8>), dim3(grid), dim3(512), lds, s, (const bf16_t*)qkv, (bf16_t*)ctx, lengths, seq, d, n_head, causal, kpad);
+    } else {
+      const int grid = batch * n_head * ((seq + 127) / 128);
+      hipLaunchKernelGGL((attention_mfma_kernel<64, 4>), dim3(grid), dim3(256), lds, s, (const bf16_t*)qkv, (bf16_t*)ctx, lengths, seq, d, n_head, causal, kpad);
+    }
     return hipGetLastError();
   }
   if (dtype == 0) return launch_attention_t<float>((const float*)qkv, (float*)ctx, lengths, batch, seq, d, n_head, causal, s);
