@@ -114,7 +114,9 @@ size_t flat_items_of(int64_t numel, int P) {
   const int64_t groups = (numel + P - 1) / P;
   return (size_t)((groups + kFlatGroupsPerItem - 1) / kFlatGroupsPerItem);
 }
-int tile_rows_of(int64_t rows) { return rows >= 2 * kTileRowsPerIter ? 2 * kTileRowsPerIter : kTileRowsPerIter; }
+// Row tiles of 128 rows: fine enough that a launch over one layer's matrices (a stage of the layer pipeline) still
+// gives every block several tiles; the slice of R is shared by the consecutive row tiles of a strip, so small tiles cost nothing.
+int tile_rows_of(int64_t) { return kTileRowsPerIter; }
 size_t tile_items_of(int64_t rows, int64_t cols, int P) {
   const int64_t tr = tile_rows_of(rows), tc = 32 * P;
   return (size_t)(((rows + tr - 1) / tr) * ((cols + tc - 1) / tc));

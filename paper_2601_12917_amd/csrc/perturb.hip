@@ -519,6 +519,21 @@ int resident_blocks_per_cu(K kern, size_t dyn_lds, int cap) {
   return nb < cap ? nb : cap;
 }
 
+// Launch set-up of one tile-kernel variant, done once per LDS size: the dynamic-LDS limit and the occupancy.
+struct TileLaunchCache {
+  size_t lds = 0;
+  int per_cu = 0;
+};
+template <typename K>
+hipError_t tile_launch_setup(K kern, size_t lds, int cap, TileLaunchCache& cache) {
+  if (cache.per_cu > 0 && cache.lds == lds) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  cache.lds = lds;
+  cache.per_cu = resident_blocks_per_cu(kern, lds, cap);
+  return hipSuccess;
+}
+
 // Grid of a persistent launch: as many computing blocks as there are items, at most the resident capacity, the
 // last kPullBlocks of that capacity set aside for pulling the next stage's bases when there are any to pull.
 int split_grid(PerturbArgs& a, int items, int capacity) {
@@ -547,19 +562,21 @@ hipError_t launch_tile_t(const PerturbArgs& a_in, float c, float* zout, hipStrea
   const size_t lds = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kTileRowsPerIter * kp + (size_t)kp * 32 * P);
   if (a.min_k >= kMfmaMinK) {
     const size_t lds_m = sizeof(float) * ((size_t)kRadiusTabEntries * 3 + (size_t)kp * 32 * P);
+    const int variant = zout ? 1 : (a.n_q > 0 ? 2 : 0);
     auto km = zout ? perturb_tile_mfma_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_tile_mfma_kernel<T, P, false, true> : perturb_tile_mfma_kernel<T, P, false, false>);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(km), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_m);
+    static TileLaunchCache cache_m[3];
+    hipError_t e = tile_launch_setup(km, lds_m, 8, cache_m[variant]);
     if (e != hipSuccess) return e;
-    const int per = resident_blocks_per_cu(km, lds_m, 8);
-    const int grid_m = split_grid(a, a.n_tiles, n_cu * per);
+    const int grid_m = split_grid(a, a.n_tiles, n_cu * cache_m[variant].per_cu);
     hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, a.descs, a.tiles, c, tab, zout, kp);
     return hipGetLastError();
   }
+  const int variant = zout ? 1 : (a.n_q > 0 ? 2 : 0);
   auto kern = zout ? perturb_tile_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_tile_kernel<T, P, false, true> : perturb_tile_kernel<T, P, false, false>);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static TileLaunchCache cache_v[3];
+  hipError_t e = tile_launch_setup(kern, lds, 4, cache_v[variant]);
   if (e != hipSuccess) return e;
-  const int per_cu = resident_blocks_per_cu(kern, lds, 4);
-  const int grid = split_grid(a, a.n_tiles, n_cu * per_cu);
+  const int grid = split_grid(a, a.n_tiles, n_cu * cache_v[variant].per_cu);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, a.descs, a.tiles, c, tab, zout, kp);
   return hipGetLastError();
 }
