@@ -166,10 +166,13 @@ zgr_status zgr_set_basis_q4(zgr_ctx* ctx, int32_t tensor_index, const uint8_t* U
 /* System-level Pipeline Controller (Sec. 4.3), client side: the basis of this
  * tensor stays in HOST memory (where the link from the cloud delivers it) and
  * is brought to the device layer by layer during every perturbation pass.
- * Tensors with the same `layer` form one stage: the kernel launch that perturbs
- * layer l also reads the bases of layer l + 1 out of host memory into the other
- * of two staging slots in the workspace, so the transfer runs under the
- * arithmetic of layer l and only two layers' bases are ever resident.
+ * Tensors with the same `layer` travel together, and consecutive layers are
+ * packed into one stage until the stage is large enough to keep the chip busy
+ * (8192 tiles of 128 x 128 elements: three layers at d = 2048, every layer its
+ * own stage on larger models): the kernel launch that perturbs stage s also
+ * reads the bases of stage s + 1 out of host memory into the other of two
+ * staging slots in the workspace, so the transfer runs under the arithmetic of
+ * stage s and only two stages' bases are ever resident.
  * bits = 32: U_host is fp32 [rows, k]; bits = 4: U_host holds the 4-bit codes
  * of zgr_set_basis_q4, [rows, (k+1)/2 bytes], with their lambda and delta
  * (ignored for bits = 32).  Rows are compact (no row stride).  U_host is owned
@@ -177,7 +180,8 @@ zgr_status zgr_set_basis_q4(zgr_ctx* ctx, int32_t tensor_index, const uint8_t* U
  * (hipHostMalloc), 16-byte aligned, and stay valid and unchanged while
  * installed.  Bases of one layer that lie in one host allocation in tensor-table
  * order, each padded to a multiple of 256 bytes, are fetched as one piece.  At
- * most 16 streamed tensors per layer.  The staging slots are sized by
+ * most 16 pieces per stage (a layer with more closes the stage early), at most
+ * 16 streamed tensors per layer.  The staging slots are sized by
  * zgr_workspace_bytes from the ranks k of the tensor table given to it: a layer
  * whose bases need more is refused with ZGR_ERR_WORKSPACE.  Results are
  * identical to a resident basis.  zgr_set_basis / zgr_set_basis_q4 on the same
@@ -257,6 +261,10 @@ zgr_status zgr_debug_gauss(uint64_t seed, uint64_t step, uint32_t tensor_id, int
                            int64_t first, int64_t n, float* out, void* hip_stream);
 /* Z of one tensor as fp32 [rows, cols] (DEVICE), computed by the same code path as the in-place pass. */
 zgr_status zgr_debug_fill_z(zgr_ctx* ctx, int32_t tensor_index, uint64_t step, float* Z);
+/* Stage size of the layer pipeline of zgr_set_basis_host: consecutive layers share a stage (one launch, one
+ * staging slot) until it holds min_tiles tiles of 128 x 128 (x 256 with gauss_bits 16) elements; default 8192,
+ * 1 gives one stage per layer.  For tests that want many stages on small models.                          */
+zgr_status zgr_debug_set_stage_tiles(zgr_ctx* ctx, int64_t min_tiles);
 /* Per-example losses of the last forward (DEVICE -> HOST copy, synchronises):
  * LM: [batch*(seq-1)] token losses; CLS: [batch]; LSQ: [batch].  n must match. */
 zgr_status zgr_debug_last_row_losses(zgr_ctx* ctx, float* out /* HOST */, int64_t n);

@@ -21,6 +21,7 @@ std::string g_init_error;   // message of the last failed zgr_init / context-fre
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+constexpr size_t kMinStageTiles = 8192;   // tiles that make a tile launch long enough to amortise its start-up and tail
 constexpr int kSpcSlots = 2;   // layers' worth of streamed bases resident at once: the one in use and the one arriving
 
 struct Layer {
@@ -60,6 +61,7 @@ struct zgr_ctx {
                  std::vector<StageCopy> copies; };   // host -> staging-slot pieces, contiguous runs merged
   std::vector<Group> groups;   // streamed groups in pass order; their tiles follow the resident ones in `tiles`
   size_t resident_tiles = 0;
+  size_t min_stage_tiles = kMinStageTiles;   // consecutive layers share a stage until it holds this many tiles
   int res_max_k = 0, res_min_k = 0;
   std::vector<TensorDesc> descs;
   std::vector<WorkItem> flat, tiles;
@@ -146,13 +148,39 @@ void build_lists(zgr_ctx* c) {
   const int P = group_size(c->cfg.gauss_bits);
   c->flat.clear(); c->tiles.clear(); c->descs.resize(c->t.size()); c->groups.clear();
   c->max_k = 0; c->min_k = kMaxK + 1; c->res_max_k = 0; c->res_min_k = kMaxK + 1;
-  // streamed tensors: groups by layer in order of first appearance, slot offsets inside the group
+  // Streamed tensors: layers in order of first appearance; consecutive layers are packed into one stage until the
+  // stage holds min_stage_tiles tiles, as long as its bases fit a staging slot and its pieces one launch's list.
+  struct LayerSet { int layer; std::vector<int> tensors; size_t bytes = 0, tiles = 0, pieces = 0; };
+  std::vector<LayerSet> layers;
   for (size_t i = 0; i < c->t.size(); ++i) {
     if (!is_streamed(c, i)) continue;
-    zgr_ctx::Group* g = nullptr;
-    for (auto& gg : c->groups) if (gg.layer == c->t[i].layer) g = &gg;
-    if (!g) { c->groups.push_back({}); g = &c->groups.back(); g->layer = c->t[i].layer; g->min_k = kMaxK + 1; }
-    g->tensors.push_back((int)i);
+    LayerSet* ls = nullptr;
+    for (auto& l : layers) if (l.layer == c->t[i].layer) ls = &l;
+    if (!ls) { layers.push_back({}); ls = &layers.back(); ls->layer = c->t[i].layer; }
+    const size_t bytes = (size_t)c->t[i].rows * (c->hb[i].bits == 4 ? (size_t)(c->t[i].k + 1) / 2 : (size_t)c->t[i].k * 4);
+    // a tensor continues the previous piece when it lies in host memory where the padded slot layout puts it
+    bool continues = false;
+    if (!ls->tensors.empty()) {
+      const int pv = ls->tensors.back();
+      const size_t pbytes = (size_t)c->t[pv].rows * (c->hb[pv].bits == 4 ? (size_t)(c->t[pv].k + 1) / 2 : (size_t)c->t[pv].k * 4);
+      continues = c->hb[i].dev == c->hb[pv].dev + align_up(pbytes);
+    }
+    ls->tensors.push_back((int)i);
+    ls->bytes += align_up(bytes);
+    ls->tiles += tile_items_of(c->t[i].rows, c->t[i].cols, P);
+    if (!continues) ls->pieces += 1;
+  }
+  {
+    size_t bytes = 0, tiles = 0, pieces = 0;
+    for (const LayerSet& l : layers) {
+      const bool open = !c->groups.empty() && tiles > 0;
+      if (!open || tiles >= c->min_stage_tiles || bytes + l.bytes > c->cv.spc_bytes || pieces + l.pieces > (size_t)kMaxStage) {
+        c->groups.push_back({}); c->groups.back().layer = l.layer; c->groups.back().min_k = kMaxK + 1;
+        bytes = tiles = pieces = 0;
+      }
+      for (int i : l.tensors) c->groups.back().tensors.push_back(i);
+      bytes += l.bytes; tiles += l.tiles; pieces += l.pieces;
+    }
   }
   for (size_t gi = 0; gi < c->groups.size(); ++gi) {
     size_t off = 0;
@@ -271,16 +299,24 @@ Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int
   cv.dbg = take(sizeof(WorkItem) * std::max<size_t>(nd, 1));
   cv.loss = take(sizeof(double) * 2);
   {
-    // largest per-layer sum of basis bytes (compact rows x k fp32), from the ranks in the tensor table
-    std::vector<std::pair<int, size_t>> per_layer;
+    // A staging slot holds the fp32 bases (compact rows x k, ranks from the tensor table) of one stage: consecutive
+    // layers packed until they hold kMinStageTiles tiles.  Sized as if every guidable tensor were streamed.
+    struct PL { int layer; size_t bytes, tiles; };
+    std::vector<PL> per_layer;
     for (int i = 0; i < n_t; ++i) {
       if (t[i].k <= 0 || t[i].cols % P) continue;
       const size_t bytes = align_up((size_t)t[i].rows * (size_t)t[i].k * 4);
+      const size_t tl = tile_items_of(t[i].rows, t[i].cols, P);
       bool found = false;
-      for (auto& pl : per_layer) if (pl.first == t[i].layer) { pl.second += bytes; found = true; }
-      if (!found) per_layer.push_back({t[i].layer, bytes});
+      for (auto& pl : per_layer) if (pl.layer == t[i].layer) { pl.bytes += bytes; pl.tiles += tl; found = true; }
+      if (!found) per_layer.push_back({t[i].layer, bytes, tl});
     }
-    for (const auto& pl : per_layer) cv.spc_bytes = std::max(cv.spc_bytes, pl.second);
+    size_t bytes = 0, tiles = 0;
+    for (const auto& pl : per_layer) {
+      if (tiles >= kMinStageTiles) { bytes = 0; tiles = 0; }
+      bytes += pl.bytes; tiles += pl.tiles;
+      cv.spc_bytes = std::max(cv.spc_bytes, bytes);
+    }
     for (int i = 0; i < kSpcSlots; ++i) cv.spc[i] = take(cv.spc_bytes);
   }
   const size_t es = elem_size(dtype);
@@ -860,6 +896,14 @@ zgr_status zgr_debug_fill_z(zgr_ctx* c, int32_t idx, uint64_t step, float* Z) {
     a.n_stage = 0;
     HIP_TRY(c, launch_perturb_tile(a, 0.f, Z, c->stream, c->n_cu));
   }
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_set_stage_tiles(zgr_ctx* c, int64_t min_tiles) {
+  if (!c) return ZGR_ERR_NULL;
+  if (min_tiles < 1) return fail(c, ZGR_ERR_CONFIG, "min_tiles must be >= 1");
+  c->min_stage_tiles = (size_t)min_tiles;
+  build_lists(c);
   return ZGR_OK;
 }
 

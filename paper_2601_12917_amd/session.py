@@ -175,6 +175,9 @@ class Session:
             B.check(self.lib.zgr_set_basis_host(self.ctx, i, block.data_ptr() + o, k, 4 if codes else 32,
                                                 float(lams[j]) if codes else 0.0, float(deltas[j]) if codes else 0.0), self.ctx)
 
+    def set_stage_tiles(self, min_tiles):
+        B.check(self.lib.zgr_debug_set_stage_tiles(self.ctx, int(min_tiles)), self.ctx)
+
     def compress_basis(self, index):
         """Quantise the installed fp32 basis of one tensor to 4 bits on the device and install the codes in its place."""
         u, k = self.U[index], self.params[index].k

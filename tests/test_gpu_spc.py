@@ -22,12 +22,16 @@ def _guided(specs, bases):
 
 
 @pytest.mark.parametrize("cfg", [DEEP_F32, DEEP_BF16], ids=lambda c: c.name)
-@pytest.mark.parametrize("mode", ["f32", "q4", "mixed"])
-def test_streamed_bases_give_identical_steps(cfg, mode):
+@pytest.mark.parametrize("mode,stage_tiles", [("f32", 1), ("q4", 1), ("mixed", 1), ("f32", 20), ("q4", None)])
+def test_streamed_bases_give_identical_steps(cfg, mode, stage_tiles):
+    """stage_tiles = 1: one pipeline stage per layer; 20: two or three of these small layers per stage;
+    None: the default, which puts all of such a small model into one stage."""
     specs, values, bases = inputs_of(cfg)
     arrays = make_batch_arrays(cfg)
     res = make_session(cfg, specs, values, bases)
     spc = make_session(cfg, specs, values, bases)
+    if stage_tiles is not None:
+        spc.set_stage_tiles(stage_tiles)
     for i in _guided(specs, bases):
         k = cfg.k
         if mode == "q4" or (mode == "mixed" and specs[i].layer % 2 == 1):
@@ -65,6 +69,7 @@ def test_layer_blocks_travel_as_one_transfer_and_give_identical_steps(codes):
     arrays = make_batch_arrays(cfg)
     res = make_session(cfg, specs, values, bases)
     spc = make_session(cfg, specs, values, bases)
+    spc.set_stage_tiles(1)
     layers = {}
     for i in _guided(specs, bases):
         layers.setdefault(specs[i].layer, []).append(i)
@@ -93,6 +98,7 @@ def test_streamed_basis_can_be_replaced_and_is_bounded_by_the_workspace():
     cfg = DEEP_F32
     specs, values, bases = inputs_of(cfg)
     sess = make_session(cfg, specs, values, bases)
+    sess.set_stage_tiles(1)
     g = _guided(specs, bases)
     i = g[0]
     z_res = sess.fill_z(i, 5)
@@ -100,14 +106,22 @@ def test_streamed_basis_can_be_replaced_and_is_bounded_by_the_workspace():
     assert np.array_equal(sess.fill_z(i, 5), z_res)
     sess.set_basis(i, bases[i], cfg.k)                               # back to a resident basis
     assert np.array_equal(sess.fill_z(i, 5), z_res)
-    rows = bases[i].shape[0]
+    # the staging slots were sized for rank cfg.k: a layer streamed at eight times that rank does not fit
+    refused = False
     for j in g:
         if specs[j].layer == specs[i].layer:
-            sess.set_basis_host(j, bases[j], cfg.k)                  # the whole layer streamed: its staging slot is full
-    wide = np.linalg.qr(np.random.default_rng(0).standard_normal((rows, 4 * cfg.k)))[0].astype(np.float32)
-    with pytest.raises(Exception):
-        sess.set_basis_host(i, wide, 4 * cfg.k)                      # four times the rank the slots were sized for
-    assert np.array_equal(sess.fill_z(i, 5), z_res)                  # the refused call changed nothing
+            rows = bases[j].shape[0]
+            wide = np.linalg.qr(np.random.default_rng(j).standard_normal((rows, 8 * cfg.k)))[0].astype(np.float32)
+            try:
+                sess.set_basis_host(j, wide, 8 * cfg.k)
+            except Exception:
+                refused = True
+                break
+    assert refused
+    for j in g:
+        if specs[j].layer == specs[i].layer:
+            sess.set_basis(j, bases[j], cfg.k)
+    assert np.array_equal(sess.fill_z(i, 5), z_res)                  # back on resident bases, nothing else changed
     # pageable host memory is refused (the kernels read the bases themselves: they must be pinned and mapped)
     from paper_2601_12917_amd import binding as B
     pageable = np.ascontiguousarray(bases[i][:, :cfg.k])
