@@ -27,6 +27,24 @@ __device__ __forceinline__ void from_f32(float x, bf16_t& o) {     // round to n
 
 template <typename T, int P> struct alignas(sizeof(T) * P <= 16 ? sizeof(T) * P : 16) Vec { T v[P]; };
 
+// P fp32 results into the storage type: fp32 as they are, bf16 rounded two at a time (one v_cvt_pk_bf16_f32 per pair,
+// which leaves the pair in the dword it is stored from).
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+template <int P> __device__ __forceinline__ void round_into(Vec<float, P>& x, const float* f) {
+#pragma unroll
+  for (int j = 0; j < P; ++j) x.v[j] = f[j];
+}
+template <int P> __device__ __forceinline__ void round_into(Vec<bf16_t, P>& x, const float* f) {
+#pragma unroll
+  for (int j = 0; j < P; j += 2) {
+    const bf16x2_t r = __builtin_convertvector(f32x2_t{f[j], f[j + 1]}, bf16x2_t);
+    const uint32_t bits = __builtin_bit_cast(uint32_t, r);
+    x.v[j].bits = (uint16_t)bits;
+    x.v[j + 1].bits = (uint16_t)(bits >> 16);
+  }
+}
+
 // theta pointers come out of descriptors in memory, so the compiler cannot know that they point to global
 // memory and would emit FLAT accesses (which also tie up the LDS counter); say so explicitly.
 template <typename V> __device__ __forceinline__ V load_global(const void* p) {
@@ -158,11 +176,13 @@ __device__ __forceinline__ void finish_row(const TensorDesc& d, T* __restrict__ 
     for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], ur[j]);
   } else {
     Vec<T, P> x = load_global<Vec<T, P>>(th + e0);
+    float f[P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
       const float z = __builtin_fmaf(d.a, G[j], ur[j]);
-      from_f32(__builtin_fmaf(c, z, to_f32(x.v[j])), x.v[j]);
+      f[j] = __builtin_fmaf(c, z, to_f32(x.v[j]));
     }
+    round_into<P>(x, f);
     store_global(th + e0, x);
   }
 }
@@ -314,11 +334,13 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
 #pragma unroll
           for (int j = 0; j < P; ++j) zout[e0 + j] = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
         } else {
+          float f[P];
 #pragma unroll
           for (int j = 0; j < P; ++j) {
             const float z = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
-            from_f32(__builtin_fmaf(c, z, to_f32(xv.v[j])), xv.v[j]);
+            f[j] = __builtin_fmaf(c, z, to_f32(xv.v[j]));
           }
+          round_into<P>(xv, f);
           store_global(th + e0, xv);
         }
       }
