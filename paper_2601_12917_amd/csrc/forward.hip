@@ -173,10 +173,10 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
     }
 }
 
-// bf16 path: MFMA 32x32x16.  Block tile BM x BN (128 or 256 each), BK = 64, four waves in a 2 x 2 grid,
-// each owning (BM/2) x (BN/2) of the output as FM x FN accumulator fragments of 32 x 32.  Global
-// loads for k-tile t+1 are issued before the MFMAs of tile t and land in the other LDS buffer
-// after them (register-staged double buffering, one barrier per k-tile).
+// bf16 path: MFMA 32x32x16.  Block tile BM x BN, BK = 64, WM x WN waves, each owning (BM / WM) x (BN / WN) of
+// the output as FM x FN accumulator fragments of 32 x 32.  Operands go from global memory straight into LDS
+// (no register staging).  Two main loops: the ping-pong pipeline (PP = 1, eight waves, large tiles) and a plain
+// multi-stage loop with one barrier per k-tile (PP = 0, the 128 x 128 tile of small problems).
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int GB_K = 64;
@@ -227,7 +227,7 @@ template <int N> __device__ __forceinline__ void wait_vmem_upto() {   // at most
 #endif
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int STAGES, int MODE>
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int MODE, int PP = 0>
 __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int M, int N, int K,
                                                                  void* __restrict__ out, const bf16_t* __restrict__ bias,
                                                                  const int32_t* __restrict__ targets, float* __restrict__ tlogit) {
@@ -237,7 +237,7 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   constexpr int RPI = 64 / CPR;                                // rows one global_load_lds instruction fills (1 KiB)
   constexpr int RPB = 256 / (BK * 2);                          // rows per 256 B of LDS (one sweep over all banks)
   constexpr int GA = BM / RPI / NW, GW = BN / RPI / NW;        // instructions per wave per k-tile
-  static_assert(GA >= 1 && GW >= 1 && (STAGES - 2) * (GA + GW) < 64, "tile / stage configuration");
+  static_assert(PP != 0 || (GA >= 1 && GW >= 1 && (STAGES - 2) * (GA + GW) < 64), "tile / stage configuration");
   // LDS: STAGES slabs of [BM + BN][BK] bf16, rows unpadded; the 16-byte chunk c of row r sits in slot
   // c ^ ((r / RPB) % CPR), which makes the MFMA operand reads conflict-free.  The slabs are written by
   // global_load_lds (global memory -> LDS without passing registers): one instruction fills RPI rows, lane L
@@ -245,7 +245,12 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   extern __shared__ __attribute__((aligned(1024))) unsigned char gsm[];
   bf16_t* As = reinterpret_cast<bf16_t*>(gsm);                 // [STAGES][BM][BK]
   bf16_t* Ws = As + STAGES * BM * BK;                          // [STAGES][BN][BK]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+#if defined(__HIP_DEVICE_COMPILE__)
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
+#else
+  const int wave = tid >> 6;
+#endif
   const int wm = wave / WN, wn = wave % WN;
   // XCD-aware tile order.  Consecutive block ids go round-robin to the 8 XCDs, each with its own L2 and
   // about 32 blocks in flight.  Give XCD x the super-tiles x, x+8, ... of GM x GN = 4 x 8 tiles, walked in
@@ -257,21 +262,6 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   const int tm = (st / stn) * GM + w / GN, tn = (st % stn) * GN + w % GN;
   if (tm >= tiles_m || tn >= tiles_n) return;
   const int m0 = tm * BM, n0 = tn * BN;
-  // loader: this lane's source offsets (elements) for the row groups its wave owns
-  const int lrow = lane / CPR, lslot = lane % CPR;
-  uint32_t ao[GA], wo[GW];
-#pragma unroll
-  for (int g = 0; g < GA; ++g) {
-    const int rl = (wave * GA + g) * RPI + lrow;               // row within the tile
-    int r = m0 + rl; r = r < M ? r : M - 1;
-    ao[g] = (uint32_t)r * (uint32_t)K + ((lslot ^ ((rl / RPB) % CPR)) << 3);
-  }
-#pragma unroll
-  for (int g = 0; g < GW; ++g) {
-    const int rl = (wave * GW + g) * RPI + lrow;
-    int c = n0 + rl; c = c < N ? c : N - 1;
-    wo[g] = (uint32_t)c * (uint32_t)K + ((lslot ^ ((rl / RPB) % CPR)) << 3);
-  }
   f32x16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -295,6 +285,162 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
         for (int v = 0; v < 16; ++v) res[(i * FN + j) * 16 + v] = rp[(size_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * N + j * 32];
   }
   const int nk = K / BK;
+  // reader: lane (l32, half) reads row l32 of each fragment, logical chunk 2*ks + half
+  const int l32 = lane & 31, half = lane >> 5, swz = (l32 / RPB) % CPR;
+  int koff[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) koff[ks] = ((2 * ks + half) ^ swz) << 3;
+  if constexpr (PP != 0) {
+    // Ping-pong pipeline.  Two groups of four waves (waves w and w + 4 share a SIMD) take turns: while one group
+    // runs the MFMAs of half a k-tile (one wave per SIMD keeps the matrix pipe busy on its own: the products of
+    // a half are independent), the other reads the operands of its next half from LDS and issues its share of
+    // the global -> LDS transfers.  The groups run one phase apart (the second starts with an extra barrier,
+    // the first ends with one) and every phase ends in a workgroup barrier, so a SIMD always holds one wave of
+    // each kind and the transfers never wait behind a group that is issuing MFMAs.
+    //
+    // LDS is a ring of R units of 8 KiB: 64 rows of one operand over the BK = 64 columns of a k-tile (whole
+    // 128-byte lines of the source).  One transfer
+    // instruction per wave fills a unit (wave w supplies rows 8w .. 8w + 7).  K-tile kt owns the U = (BM + BN) / 64
+    // units kt U .. kt U + U - 1 (A first), at ring positions taken modulo R.  Unit q may be overwritten by unit
+    // q + R once k-tile q / U has been read by both groups, which is the case from the first memory phase of the
+    // next k-tile on; so the two memory phases of k-tile kt issue the units R - U + kt U .. R + kt U - 1, i.e.
+    // R - U units (one and a half k-tiles for 256 x 256 tiles) are in flight or landed ahead of the reader.
+    // K-tile kt + 1 must have landed before the first group starts on it: the second group waits for its shares at
+    // the end of its last memory phase of k-tile kt, the first at the end of its last MFMA phase, in both cases
+    // with the R - 2U units of later k-tiles still in flight; the barrier that follows publishes them.
+    static_assert(NW == 8 && BK == 64 && BM % 64 == 0 && BN % 64 == 0, "ping-pong configuration");
+    constexpr int UA = BM / 64, U = (BM + BN) / 64, R = STAGES, Q0 = R - U;
+    constexpr int UH0 = (U + 1) / 2;                             // units issued in the first memory phase of a k-tile
+    static_assert(R >= 2 * U && R * 8192 <= 160 * 1024, "ring size");
+    const int frow = wave * 8 + (lane >> 3);                     // row this lane supplies within a unit
+    uint32_t uo[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool is_a = u < UA;
+      const int rl = (is_a ? u : u - UA) * 64 + frow;
+      int r = (is_a ? m0 : n0) + rl;
+      const int lim = is_a ? M : N;
+      r = r < lim ? r : lim - 1;
+      uo[u] = ((uint32_t)r * (uint32_t)K + (((lane & 7) ^ ((frow >> 1) & 7)) << 3)) * 2;   // bytes
+    }
+#if defined(__HIP_DEVICE_COMPILE__)
+    // buffer addressing: per-lane byte offset in a register, the k-tile's offset in a scalar, bounds-checked
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, (uint32_t)M * (uint32_t)K * 2u, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, (uint32_t)N * (uint32_t)K * 2u, 0x00020000);
+#endif
+    // Transfers are issued unconditionally, so that every wave's count of outstanding transfers is the same in
+    // every k-tile: a unit past the last k-tile re-reads the last one into a ring slot nobody reads any more.
+    auto issue_unit = [&](int u, int ktile, int pos) {           // u is a compile-time constant after unrolling
+#if defined(__HIP_DEVICE_COMPILE__)
+      const int kc = ktile < nk ? ktile : nk - 1;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(u < UA ? rsA : rsW, (__attribute__((address_space(3))) void*)(gsm + pos * 8192 + wave * 1024), 16, uo[u], kc * (BK * 2), 0, 0);
+#endif
+    };
+    int wpos = 0;                                                // ring position of the next unit to issue
+#pragma unroll
+    for (int q = 0; q < Q0; ++q) {
+      issue_unit(q % U, q / U, wpos);
+      wpos = wpos + 1 == R ? 0 : wpos + 1;
+    }
+    wait_vmem_upto<Q0 - U>();
+    block_barrier();
+    int rbase = 0;                                               // ring position of unit 0 of k-tile kt
+    const int rowA = wm * (BM / WM), rowW = wn * (BN / WN);      // this wave's first row of either operand
+    const int grp = wave >> 2;
+    if (grp) block_barrier();
+    // LDS byte addresses of this lane's fragment reads in the coming memory phase.  They are worked out in the
+    // MFMA phase before it, between the wave's own MFMAs: a vector instruction of the memory phase would queue
+    // behind the other wave's MFMAs on the SIMD, so the memory phases hold LDS reads, transfers and scalar
+    // bookkeeping only.
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte*)gsm;   // LDS address of the ring
+    uint32_t lk[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) lk[ks] = lds0 + (uint32_t)(l32 * BK + koff[ks]) * 2u;
+    uint32_t ra[2][FM], rb[2][FN];
+    auto set_addrs = [&](int base, int h) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        int pos = base + (rowA + i * 32) / 64; pos = pos >= R ? pos - R : pos;
+        const uint32_t sa = (uint32_t)(pos * 8192 + ((rowA + i * 32) % 64) * (BK * 2));
+        ra[0][i] = sa + lk[2 * h]; ra[1][i] = sa + lk[2 * h + 1];
+      }
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        int pos = base + UA + (rowW + j * 32) / 64; pos = pos >= R ? pos - R : pos;
+        const uint32_t sb = (uint32_t)(pos * 8192 + ((rowW + j * 32) % 64) * (BK * 2));
+        rb[0][j] = sb + lk[2 * h]; rb[1][j] = sb + lk[2 * h + 1];
+      }
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {                           // keep the additions where they are written
+#pragma unroll
+        for (int i = 0; i < FM; ++i) asm volatile("" : "+v"(ra[ks][i]));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(rb[ks][j]));
+      }
+#endif
+    };
+    set_addrs(0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      int rnext = rbase + U; rnext = rnext >= R ? rnext - R : rnext;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        bf16x8 a[2][FM], b[2][FN];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+          for (int i = 0; i < FM; ++i) a[ks][i] = *(lds_bf16x8*)(uintptr_t)ra[ks][i];
+#pragma unroll
+          for (int j = 0; j < FN; ++j) b[ks][j] = *(lds_bf16x8*)(uintptr_t)rb[ks][j];
+        }
+#pragma unroll
+        for (int t = 0; t < (h == 0 ? UH0 : U - UH0); ++t) {
+          const int qq = Q0 + (h == 0 ? 0 : UH0) + t;             // unit number relative to kt U
+          issue_unit(qq % U, kt + qq / U, wpos);
+          wpos = wpos + 1 == R ? 0 : wpos + 1;
+        }
+        if (h == 1 && grp) wait_vmem_upto<Q0 - U>();
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+        set_addrs(h == 0 ? rbase : rnext, h == 0 ? 1 : 0);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
+        if (h == 1 && !grp) wait_vmem_upto<Q0 - U>();
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+      }
+      rbase = rnext;
+    }
+    if (!grp) block_barrier();
+  } else {
+  // loader: this lane's source offsets (elements) for the row groups its wave owns
+  const int lrow = lane / CPR, lslot = lane % CPR;
+  uint32_t ao[GA], wo[GW];
+#pragma unroll
+  for (int g = 0; g < GA; ++g) {
+    const int rl = (wave * GA + g) * RPI + lrow;               // row within the tile
+    int r = m0 + rl; r = r < M ? r : M - 1;
+    ao[g] = (uint32_t)r * (uint32_t)K + ((lslot ^ ((rl / RPB) % CPR)) << 3);
+  }
+#pragma unroll
+  for (int g = 0; g < GW; ++g) {
+    const int rl = (wave * GW + g) * RPI + lrow;
+    int c = n0 + rl; c = c < N ? c : N - 1;
+    wo[g] = (uint32_t)c * (uint32_t)K + ((lslot ^ ((rl / RPB) % CPR)) << 3);
+  }
   auto issue = [&](int kt, int buf) {
 #if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll
@@ -309,11 +455,6 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
 #pragma unroll
   for (int p = 0; p < STAGES - 1; ++p)
     if (p < nk) issue(p, p);
-  // reader: lane (l32, half) reads row l32 of each fragment, logical chunk 2*ks + half
-  const int l32 = lane & 31, half = lane >> 5, swz = (l32 / RPB) % CPR;
-  int koff[BK / 16];
-#pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) koff[ks] = ((2 * ks + half) ^ swz) << 3;
   int buf = 0;
   for (int kt = 0; kt < nk; ++kt) {
     // k-tile kt has landed once at most the STAGES - 2 younger tiles are still in flight
@@ -335,6 +476,7 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
         for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     buf = buf + 1 == STAGES ? 0 : buf + 1;
+  }
   }
   if (MODE == EPI_CE) {
     // Cross-entropy partials instead of logits.  The product is taken transposed (rows = vocabulary entries,
@@ -412,17 +554,17 @@ __global__ void __launch_bounds__(64 * WM * WN) gemm_bf16_kernel(const bf16_t* _
   }
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int STAGES>
+template <int BM, int BN, int WM, int WN, int BK, int STAGES, int PP = 0>
 hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bias, void* out, int epi, int M, int N, int K, hipStream_t s,
                               const int32_t* targets = nullptr, float* tlogit = nullptr) {
-  const size_t lds = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
+  const size_t lds = PP ? (size_t)STAGES * 8192 : (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);   // ping-pong: STAGES counts 8 KiB ring units
   // super-tiles of 4 x 8 tiles, rounded up to a multiple of 8 super-tiles (one per XCD)
   const int stm = ((M + BM - 1) / BM + 3) / 4, stn = ((N + BN - 1) / BN + 7) / 8;
   const int grid = ((stm * stn + 7) / 8 * 8) * 32;
 #define ZGR_GEMM_LAUNCH(MODE)                                                                                           \
   {                                                                                                                     \
     static bool attr_set = false;                                                                                       \
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, STAGES, MODE>;                                                                 \
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, STAGES, MODE, PP>;                                                             \
     if (!attr_set) {                                                                                                    \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
       if (e != hipSuccess) return e;                                                                                    \
@@ -730,14 +872,14 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
     const bf16_t* a = (const bf16_t*)A; const bf16_t* w = (const bf16_t*)W; const bf16_t* b = (const bf16_t*)bias;
     // largest tile that still gives every CU a block
     const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256), t128x256 = (long)((M + 127) / 128) * ((N + 255) / 256);
-    if ((size_t)M * K >= ((size_t)1 << 32) || (size_t)N * K >= ((size_t)1 << 32)) return hipErrorInvalidValue;   // 32-bit element offsets
+    if ((size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit byte offsets
     // 256 x 256 tiles unless their count leaves the last round of 256 CUs less than ~85 % full and 256 x 192 tiles fill it better
     const long t192 = (long)((M + 255) / 256) * ((N + 191) / 192);
     auto fill = [](long t) { const long rounds = (t + 255) / 256; return (double)t / (double)(rounds * 256); };
-    if (t256 >= 256 && (fill(t256) >= 0.85 || fill(t192) <= fill(t256))) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 2>(a, w, b, out, epi, M, N, K, s);
-    if (t192 >= 256 && N % 192 == 0) return launch_gemm_bf16_t<256, 192, 4, 2, 64, 2>(a, w, b, out, epi, M, N, K, s);
-    if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 2>(a, w, b, out, epi, M, N, K, s);
-    if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4, 64, 2>(a, w, b, out, epi, M, N, K, s);
+    if (t256 >= 256 && (fill(t256) >= 0.85 || fill(t192) <= fill(t256))) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
+    if (t192 >= 256 && N % 192 == 0) return launch_gemm_bf16_t<256, 192, 4, 2, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
+    if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
+    if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
     return launch_gemm_bf16_t<128, 128, 2, 2, 64, 4>(a, w, b, out, epi, M, N, K, s);
   }
   return hipGetLastError();
@@ -748,9 +890,9 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
 int ce_partials_per_row(int N) { return ((N + 255) / 256) * 2; }
 
 hipError_t launch_gemm_ce_bf16(const void* A, const void* W, const int32_t* targets, void* part, float* tlogit, float* row_loss, int M, int N, int K, hipStream_t s) {
-  if (K % GB_K != 0 || (size_t)M * K >= ((size_t)1 << 32) || (size_t)N * K >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  if (K % GB_K != 0 || (size_t)M * K >= ((size_t)1 << 31) || (size_t)N * K >= ((size_t)1 << 31)) return hipErrorInvalidValue;
   // transposed product: the kernel's rows are the N vocabulary entries, its columns the M tokens
-  hipError_t e = launch_gemm_bf16_t<256, 256, 2, 4, 64, 2>((const bf16_t*)W, (const bf16_t*)A, nullptr, part, EPI_CE, N, M, K, s, targets, tlogit);
+  hipError_t e = launch_gemm_bf16_t<256, 256, 2, 4, 64, 20, 1>((const bf16_t*)W, (const bf16_t*)A, nullptr, part, EPI_CE, N, M, K, s, targets, tlogit);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(ce_combine_kernel, dim3(M), dim3(256), 0, s, (const float2*)part, ce_partials_per_row(N), targets, tlogit, row_loss);
   return hipGetLastError();
