@@ -58,3 +58,45 @@ def unpack_nibbles(b, k):
     q[:, 0::2] = b & 15
     q[:, 1::2] = b >> 4
     return q[:, :k]
+
+
+# ----------------------------------------------------------------------------------------------------
+# How much to compress (Data Transmission Controller, Sec. 4.4, the three latency relations and the
+# memory relation that close the section).  A layer's guided data of D0 bytes crosses a link of B0
+# bytes/s; a share omega of it travels compressed to theta of its size and costs the client T(D0 omega)
+# of restoring on top of its computation T_cc; the transfer hides when T_t <= T_cc + T(D0 omega).
+# Reading: the paper prints T_t = D0 / B0, which does not depend on omega; the transfer time of partly
+# compressed data, D0 (1 - omega (1 - theta)) / B0, is used (the same factor omega (1 - theta) appears in
+# the printed memory relation).  T is taken linear in its argument ("obtained offline": one figure per byte).
+
+def transfer_time(data_bytes, bandwidth, omega, theta):
+    return data_bytes * (1.0 - omega * (1.0 - theta)) / bandwidth
+
+
+def client_time(t_cc, data_bytes, omega, restore_s_per_byte):
+    return t_cc + restore_s_per_byte * data_bytes * omega
+
+
+def choose_omega(data_bytes, bandwidth, t_cc, restore_s_per_byte, theta, iters=200):
+    """Smallest omega in [0, 1] for which the transfer hides, and whether it does at that omega.
+    transfer - client is non-increasing in omega, so the set of good omegas is an interval ending at 1."""
+    def gap(w):
+        return transfer_time(data_bytes, bandwidth, w, theta) - client_time(t_cc, data_bytes, w, restore_s_per_byte)
+    if gap(0.0) <= 0.0:
+        return 0.0, True
+    if gap(1.0) > 0.0:
+        return 1.0, False
+    lo, hi = 0.0, 1.0          # gap(lo) > 0 >= gap(hi)
+    for _ in range(iters):
+        mid = 0.5 * (lo + hi)
+        if gap(mid) > 0.0:
+            lo = mid
+        else:
+            hi = mid
+    return hi, True
+
+
+def memory_factor(n_layers, omega, theta):
+    """Client memory in units of Mem_0: (1 + 2/L) with the layer pipeline alone (omega = 0),
+    (1 + 2/L - omega (1 - theta) / L) with compression."""
+    return 1.0 + 2.0 / n_layers - omega * (1.0 - theta) / n_layers

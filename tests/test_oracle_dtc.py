@@ -74,3 +74,54 @@ def test_quantised_basis_keeps_the_guided_term_in_its_span():
     Q, _ = np.linalg.qr(Uh.astype(np.float64))
     resid = guided - Q @ (Q.T @ guided)
     assert np.abs(resid).max() <= 1e-5 * np.abs(guided).max()
+
+
+# ------------------------------------------------------------------ how much to compress (Sec. 4.4)
+
+def test_omega_zero_when_plain_transfer_already_hides():
+    # 1 MB over 1 GB/s = 1 ms <= T_cc = 2 ms
+    w, ok = D.choose_omega(1e6, 1e9, 2e-3, 0.0, 0.125)
+    assert w == 0.0 and ok
+
+
+def test_omega_closed_form_with_free_restore():
+    # restore costs nothing: D0 (1 - w (1 - theta)) / B0 = T_cc  ->  w = (1 - T_cc B0 / D0) / (1 - theta)
+    D0, B0, Tcc, theta = 8e6, 1e9, 3e-3, 0.125
+    w, ok = D.choose_omega(D0, B0, Tcc, 0.0, theta)
+    assert ok and abs(w - (1 - Tcc * B0 / D0) / (1 - theta)) < 1e-12
+    # at that omega the two sides meet
+    assert abs(D.transfer_time(D0, B0, w, theta) - D.client_time(Tcc, D0, w, 0.0)) < 1e-15
+
+
+def test_omega_closed_form_with_restore_cost():
+    D0, B0, Tcc, tau, theta = 4e6, 5e8, 2e-3, 1e-10, 0.25
+    w, ok = D.choose_omega(D0, B0, Tcc, tau, theta)
+    want = (D0 / B0 - Tcc) / (D0 * (1 - theta) / B0 + tau * D0)
+    assert ok and 0 < want < 1 and abs(w - want) < 1e-12
+
+
+def test_omega_saturates_when_even_full_compression_cannot_hide():
+    # 10 Mbit/s link (1.25e6 B/s), 1 MB, theta = 1/8: 0.1 s even when everything is compressed, T_cc = 1 ms
+    w, ok = D.choose_omega(1e6, 1.25e6, 1e-3, 0.0, 0.125)
+    assert w == 1.0 and not ok
+
+
+def test_omega_is_the_smallest_on_a_grid_and_monotone_in_bandwidth():
+    D0, Tcc, tau, theta = 6e6, 1e-3, 2e-11, 0.125
+    prev = 2.0
+    for B0 in (1e9, 2e9, 4e9, 8e9):
+        w, ok = D.choose_omega(D0, B0, Tcc, tau, theta)
+        grid = np.linspace(0, 1, 100001)
+        good = D.transfer_time(D0, B0, grid, theta) <= D.client_time(Tcc, D0, grid, tau)
+        assert ok == bool(good.any())
+        if ok:
+            assert abs(grid[np.argmax(good)] - w) <= 1e-5 + 1e-12
+        assert w <= prev          # a faster link never needs more compression
+        prev = w
+
+
+def test_memory_factor_matches_the_printed_relations():
+    # layer pipeline alone: (1 + 2/L); with compression: minus omega (1 - theta) / L
+    assert D.memory_factor(24, 0.0, 0.125) == pytest.approx(1 + 2 / 24)
+    assert D.memory_factor(24, 1.0, 0.125) == pytest.approx(1 + 2 / 24 - 0.875 / 24)
+    assert D.memory_factor(12, 0.5, 0.25) == pytest.approx(1 + 2 / 12 - 0.5 * 0.75 / 12)
