@@ -273,6 +273,15 @@ def main():
         out["roofline"] = {"gemm": out.get("roofline_gemm"), "perturb_tile": out.get("roofline_perturb"),
                            "perturb_flat": out.get("roofline_perturb_flat")}.get(dom) or out.get("roofline_gemm") or out.get("roofline_perturb")
         out["dominant_kernel_class"] = dom
+    if prof and "perturb_tile" in out.get("kernel_ms", {}) and cfg.arch != I.ARCH_LINEAR_LSQ and u_bytes:
+        # Sec. 4.4: the share of a layer's basis that would have to travel as 4-bit codes for the transfer to hide
+        # under that layer's part of a perturbation pass, for a few link speeds (the restore is fused into the
+        # pass and costs nothing measurable: a pass over 4-bit bases takes the same time).
+        layer_bytes = sum(s.rows * cfg.k * 4 for s in specs if s.guided) / I.CONFIGS[args.config].n_layer   # uncompressed fp32 basis
+        t_cc = out["kernel_ms"]["perturb_tile"]["ms_avg"] * 1e-3 / I.CONFIGS[args.config].n_layer
+        links = {"10 Mbit/s": 1.25e6, "1 Gbit/s": 1.25e8, "100 Gbit/s": 1.25e10, "PCIe 5 x16 (64 GB/s)": 6.4e10}
+        out["dtc_policy"] = {"layer_basis_bytes": layer_bytes, "t_cc_s": t_cc, "theta": 0.125,
+                             "omega": {name: dict(zip(("omega", "hidden"), B.dtc_omega(layer_bytes, bw, t_cc, 0.0, 0.125))) for name, bw in links.items()}}
     if args.batched_update > 0:
         # edge-server aggregation over n (step, g) pairs: one pass per 8 perturbations against n single passes
         nb = args.batched_update

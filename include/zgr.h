@@ -199,6 +199,26 @@ zgr_status zgr_set_basis_host(zgr_ctx* ctx, int32_t tensor_index, const void* U_
 zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t ldu, uint8_t* Uq, int32_t ldq,
                               float* minmax_dev, float* lambda_out, float* delta_out, void* hip_stream);
 
+/* Sec. 4.4, the latency relations that close the section (host arithmetic only,
+ * no device work): the smallest share omega in [0, 1] of a layer's guided data
+ * of data_bytes bytes that has to travel compressed (to theta of its size,
+ * 0 < theta < 1) over a link of bandwidth_bytes_per_s so that the transfer
+ * hides under the client's work,
+ *     data_bytes (1 - omega (1 - theta)) / bandwidth <= t_cc_s + restore_s_per_byte data_bytes omega
+ * (t_cc_s: the client's perturbation time for that layer; restore_s_per_byte:
+ * measured cost of restoring compressed data, 0 when the restore is fused into
+ * the pass).  The paper prints the left side without the factor in omega; the
+ * transfer time of partly compressed data is the reading taken.  *hidden = 1 if
+ * the relation holds at *omega, 0 if even omega = 1 does not reach it (then
+ * *omega = 1).  ZGR_ERR_CONFIG for non-positive sizes or theta outside (0, 1). */
+zgr_status zgr_dtc_omega(double data_bytes, double bandwidth_bytes_per_s, double t_cc_s, double restore_s_per_byte, double theta,
+                         double* omega, int32_t* hidden);
+
+/* Same section, the memory relation: client memory in units of the model's own
+ * size with the layer pipeline, (1 + 2 / n_layers), less omega (1 - theta) / n_layers
+ * when a share omega travels and is held compressed.  HOST arithmetic.        */
+zgr_status zgr_dtc_memory_factor(int32_t n_layers, double omega, double theta, double* factor);
+
 /* Client block of Algorithm 1 for round/step `step` (< 2^32): perturb all
  * tensors in place by +eps Z, evaluate L+, by -2 eps Z, evaluate L-, restore by
  * +eps Z, Z regenerated from (seed, step) in each pass.  Fills *out.  On

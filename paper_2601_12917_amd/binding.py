@@ -56,6 +56,8 @@ SYMBOLS = {
     "zgr_set_basis_host": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_float]),
     "zgr_quantize_basis": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                      C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p]),
+    "zgr_dtc_omega": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
+    "zgr_dtc_memory_factor": (C.c_int, [C.c_int32, C.c_double, C.c_double, C.POINTER(C.c_double)]),
     "zgr_step": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(zgr_batch), C.POINTER(zgr_result)]),
     "zgr_apply_update": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float, C.c_float]),
     "zgr_apply_updates": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.c_float]),
@@ -105,3 +107,18 @@ def check(status, ctx=None):
     if status != ZGR_OK:
         msg = lib().zgr_last_error(ctx)
         raise ZgrError(status, msg.decode() if msg else "")
+
+
+def dtc_omega(data_bytes, bandwidth_bytes_per_s, t_cc_s, restore_s_per_byte, theta):
+    """(omega, hidden) of zgr_dtc_omega: argument marshalling only."""
+    w, ok = C.c_double(0), C.c_int32(0)
+    check(lib().zgr_dtc_omega(float(data_bytes), float(bandwidth_bytes_per_s), float(t_cc_s), float(restore_s_per_byte), float(theta),
+                              C.byref(w), C.byref(ok)))
+    return w.value, bool(ok.value)
+
+
+def dtc_memory_factor(n_layers, omega, theta):
+    f = C.c_double(0)
+    check(lib().zgr_dtc_memory_factor(int(n_layers), float(omega), float(theta), C.byref(f)))
+    return f.value
+

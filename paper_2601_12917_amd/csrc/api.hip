@@ -715,6 +715,29 @@ zgr_status zgr_set_basis_host(zgr_ctx* c, int32_t idx, const void* U_host, int32
   return ZGR_OK;
 }
 
+zgr_status zgr_dtc_omega(double data_bytes, double bandwidth_bytes_per_s, double t_cc_s, double restore_s_per_byte, double theta,
+                         double* omega, int32_t* hidden) {
+  if (!omega || !hidden) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  if (!(data_bytes > 0) || !(bandwidth_bytes_per_s > 0) || !(t_cc_s >= 0) || !(restore_s_per_byte >= 0) || !(theta > 0 && theta < 1))
+    return fail(nullptr, ZGR_ERR_CONFIG, "sizes and bandwidth must be positive, times non-negative, theta in (0, 1)");
+  // transfer(w) - client(w) = (D/B - T) - w D ((1 - theta)/B + tau): linear and decreasing in w
+  const double gap0 = data_bytes / bandwidth_bytes_per_s - t_cc_s;
+  const double slope = data_bytes * ((1.0 - theta) / bandwidth_bytes_per_s + restore_s_per_byte);
+  if (gap0 <= 0.0) { *omega = 0.0; *hidden = 1; return ZGR_OK; }
+  const double w = gap0 / slope;
+  if (w > 1.0) { *omega = 1.0; *hidden = 0; return ZGR_OK; }
+  *omega = w; *hidden = 1;
+  return ZGR_OK;
+}
+
+zgr_status zgr_dtc_memory_factor(int32_t n_layers, double omega, double theta, double* factor) {
+  if (!factor) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  if (n_layers < 1 || !(omega >= 0 && omega <= 1) || !(theta > 0 && theta < 1))
+    return fail(nullptr, ZGR_ERR_CONFIG, "n_layers >= 1, omega in [0, 1], theta in (0, 1)");
+  *factor = 1.0 + 2.0 / n_layers - omega * (1.0 - theta) / n_layers;
+  return ZGR_OK;
+}
+
 zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t ldu, uint8_t* Uq, int32_t ldq, float* minmax_dev,
                               float* lambda_out, float* delta_out, void* hip_stream) {
   if (!U || !Uq || !minmax_dev || !lambda_out || !delta_out) return fail(nullptr, ZGR_ERR_NULL, "a pointer is NULL");

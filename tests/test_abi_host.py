@@ -104,3 +104,30 @@ def test_workspace_bytes_and_null_context_calls(lib):
     assert lib.zgr_debug_gauss(1, 0, 1, 0, 24, 0, 4, 0x1000, None) == B.ZGR_ERR_CONFIG
     assert lib.zgr_debug_gauss(1, 0, 1, 0, 32, 0, 4, None, None) == B.ZGR_ERR_NULL
     lib.zgr_destroy(None)
+
+
+def test_compression_share_matches_the_oracle(lib):
+    """zgr_dtc_omega / zgr_dtc_memory_factor are host arithmetic: checked here against the oracle's search."""
+    import numpy as np
+    from oracle import dtc as D
+    rng = np.random.default_rng(5)
+    seen = set()
+    for _ in range(300):
+        D0 = 10 ** rng.uniform(4, 9)
+        B0 = 10 ** rng.uniform(5, 11)
+        Tcc = 10 ** rng.uniform(-5, -1)
+        tau = 0.0 if rng.random() < 0.5 else 10 ** rng.uniform(-13, -9)
+        theta = rng.uniform(0.05, 0.9)
+        w, ok = B.dtc_omega(D0, B0, Tcc, tau, theta)
+        w_o, ok_o = D.choose_omega(D0, B0, Tcc, tau, theta)
+        assert ok == ok_o and abs(w - w_o) <= 1e-9, (D0, B0, Tcc, tau, theta, w, w_o)
+        seen.add((w == 0.0, w == 1.0, ok))
+        L = int(rng.integers(1, 97))
+        assert B.dtc_memory_factor(L, w, theta) == pytest.approx(D.memory_factor(L, w, theta), rel=1e-14)
+    assert len(seen) == 3                      # already hidden, partly compressed, not reachable: all three occurred
+    for bad in [(0, 1e9, 1e-3, 0, 0.125), (1e6, 0, 1e-3, 0, 0.125), (1e6, 1e9, -1, 0, 0.125), (1e6, 1e9, 1e-3, 0, 1.0), (1e6, 1e9, 1e-3, 0, 0.0)]:
+        with pytest.raises(B.ZgrError):
+            B.dtc_omega(*bad)
+    with pytest.raises(B.ZgrError):
+        B.dtc_memory_factor(0, 0.5, 0.125)
+
