@@ -26,7 +26,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
 # vector instructions per Philox call of 4 elements on the main path of the bf16 / 32-bit-mode kernels (counted in the ISA)
-VALU_PER_CALL = {"perturb_flat": 202, "perturb_tile": 212}
+VALU_PER_CALL = {"perturb_flat": 183, "perturb_tile": 195}
 ALU_PEAK_TINSTR = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
