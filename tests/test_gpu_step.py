@@ -211,6 +211,34 @@ def test_batched_update_matches_oracle(cfg, n, bits):
     sess.close()
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_multi_query_client_round(name):
+    """The n-query client of Algorithm 1 (local steps t = 1..n before one aggregation): n client blocks with
+    different step indices, each leaving the parameters restored, then one batched update with weights 1/n.
+    Losses and g of every query against the oracle; the update is decoupled (both sides apply the oracle's g)."""
+    cfg = I.CONFIGS[name]
+    n = 3
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays))
+    sess = make_session(cfg, specs, values, bases)
+    batch = session_batch(sess, cfg, arrays)
+    for rnd in range(2):
+        steps = [rnd * n + q for q in range(n)]
+        ogs = []
+        for st in steps:
+            lp, lm, g = sess.step(st, batch)
+            olp, olm, og = o.step(st)
+            assert abs(lp - olp) <= LOSS_RTOL[cfg.dtype] * abs(olp) and abs(lm - olm) <= LOSS_RTOL[cfg.dtype] * abs(olm)
+            assert abs(g - og) <= 2e-6 * abs(olp) / (2 * cfg.eps) + 1e-4 * abs(og)
+            ogs.append(float(og) / n)
+        sess.apply_updates(steps, ogs, cfg.lr)
+        o.apply_updates(steps, ogs, cfg.lr)
+        for i, t in enumerate(o.tensors):
+            assert _close_params(sess.get_theta(i), t.theta, cfg.dtype), (rnd, t.name)
+    sess.close()
+
+
 def test_batched_update_rejects_bad_arguments():
     cfg = I.CONFIGS["cfg1"]
     specs, values, bases = inputs_of(cfg)
