@@ -111,6 +111,55 @@ def cpu_baseline(cfg, specs, budget_note=True):
                        f"{nb} sequences of {T} tokens, scaled to {cfg.n_layer} blocks x {cfg.batch} sequences x 2 forwards")}
 
 
+def gemm_shapes(args, torch, I, B):
+    """Every projection shape of the config's forward pass through zgr_debug_gemm, one at a time: [M, K] x [N, K]^T with the
+    epilogue the forward uses (0 bias + store, 1 bias + GELU, 2 bias + residual add into fp32).  The fused cross-entropy
+    product has no debug entry; it is timed inside the step only."""
+    import ctypes as C
+    cfg = I.CONFIGS[args.config]
+    if cfg.dtype != "bf16" or cfg.arch == I.ARCH_LINEAR_LSQ:
+        print("bench.py --gemm-shapes: needs a bf16 transformer config", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2601_12917_amd.build import build
+        build()
+    lib = B.lib()
+    dev = torch.device("cuda:0")
+    M, d, ff = cfg.batch * cfg.seq, cfg.d_model, cfg.d_ff
+    shapes = [("qkv", M, 3 * d, d, 0), ("attention output", M, d, d, 2), ("fc1 + gelu", M, ff, d, 1), ("fc2", M, d, ff, 2)]
+    g = torch.Generator(device="cpu").manual_seed(0)
+    st = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for name, m, n, k, epi in shapes:
+        A = (torch.randn(m, k, generator=g) * 0.5).bfloat16().to(dev)
+        W = (torch.randn(n, k, generator=g) * 0.05).bfloat16().to(dev)
+        bias = (torch.randn(n, generator=g) * 0.1).bfloat16().to(dev)
+        out = torch.zeros(m, n, device=dev, dtype=torch.float32 if epi == 2 else torch.bfloat16)
+        def run():
+            B.check(lib.zgr_debug_gemm(1, A.data_ptr(), W.data_ptr(), bias.data_ptr(), out.data_ptr(), epi, m, n, k, st))
+        def timed(fn, reps=max(args.steps, 20)):
+            for _ in range(max(args.warmup, 3)):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+        us = timed(run)
+        row = {"shape": name, "M": m, "N": n, "K": k, "epilogue": epi, "us": us, "tflops": 2.0 * m * n * k / us / 1e6, "launches_per_forward": cfg.n_layer}
+        if args.with_library:
+            lus = timed(lambda: torch.matmul(A, W.t()))
+            row["library_us"] = lus
+            row["library_tflops"] = 2.0 * m * n * k / lus / 1e6
+        rows.append(row)
+    tot_us = sum(r["us"] * r["launches_per_forward"] for r in rows)
+    tot_fl = sum(2.0 * r["M"] * r["N"] * r["K"] * r["launches_per_forward"] for r in rows)
+    print(json.dumps({"metric": "forward GEMM shapes", "config": {"workload": cfg.name}, "dtype": "bf16", "data": "synthetic (random operands)",
+                      "shapes": rows, "weighted_tflops": tot_fl / tot_us / 1e6, "peak_tflops": MFMA_PEAK_TFLOPS["bf16"]}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +182,9 @@ def main():
     ap.add_argument("--profile-every", type=int, default=5,
                     help="HIP events bracket every kernel launch on one timed step in this many (two event records per "
                          "launch cost about 8 %% of a step, so they are sampled inside the timed region rather than kept on)")
+    ap.add_argument("--gemm-shapes", action="store_true",
+                    help="instead of the step: time each forward GEMM shape of the config on its own (random bf16 operands, HIP events) and print one JSON line")
+    ap.add_argument("--with-library", action="store_true", help="with --gemm-shapes: also time torch.matmul (the vendor library) on the same operands, as context")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
@@ -142,6 +194,8 @@ def main():
     import zgr_inputs as I
     from paper_2601_12917_amd import binding as B
     from tests.util import inputs_of, make_batch_arrays, make_session, session_batch
+    if args.gemm_shapes:
+        return gemm_shapes(args, torch, I, B)
     if not os.path.exists(B.LIB_PATH):
         from paper_2601_12917_amd.build import build
         build()
