@@ -320,6 +320,37 @@ __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const Pertur
           acc[g * P + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[i], rrow[g * GC + j], acc[g * P + j], 0, 0, 0);
     }
   }
+  if (FULL && !WRITE_Z) {
+    // Whole tile: the lane's eight vectors of theta are requested one generator call ahead.  The wait before a
+    // vector is used is a full one (loads and stores share one counter, and with both kinds in flight it cannot
+    // be a partial wait), so whatever was requested last sets its length: with the request a whole call old it
+    // has landed, with the request placed a third of a call earlier, as the scheduler does by itself, it has not.
+    Vec<T, P> xn = load_global<Vec<T, P>>(th + ebase);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int v = t >> 1, g = t & 1;
+      const int64_t e0 = ebase + (int64_t)v * d.cols + g * GC;
+      const Vec<T, P> xc = xn;
+      if (t + 1 < 8) {
+        xn = load_global<Vec<T, P>>(th + ebase + (int64_t)((t + 1) >> 1) * d.cols + ((t + 1) & 1) * GC);
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+      }
+      float G[P];
+      draw<P, BATCH>((uint64_t)e0 / P, d.id, a, tab, G);
+      Vec<T, P> xv = xc;
+      float f[P];
+#pragma unroll
+      for (int j = 0; j < P; ++j) {
+        const float z = __builtin_fmaf(d.a, G[j], acc[g * P + j][v]);
+        f[j] = __builtin_fmaf(c, z, to_f32(xv.v[j]));
+      }
+      round_into<P>(xv, f);
+      store_global(th + e0, xv);
+    }
+    return;
+  }
 #pragma unroll
   for (int v = 0; v < 4; ++v)
 #pragma unroll
