@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 # vector instructions per Philox call of 4 elements on the main path of the bf16 / 32-bit-mode kernels (counted in the ISA)
 VALU_PER_CALL = {"perturb_flat": 183, "perturb_tile": 195}
-ALU_PEAK_TINSTR = 256 * 4 * 16 * 2.4e9 / 1e12
+ALU_PEAK_TINSTR = 256 * 4 * 32 * 2.4e9 / 1e12     # one simple wave64 instruction per 2 cycles and SIMD (157.3 TFLOP/s fp32 at 2 flops per FMA)
 
 
 def load_traffic():
@@ -304,9 +304,9 @@ def main():
             out["roofline_perturb_flat"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                                             "traffic": kernel_traffic(traffic, "perturb_flat"), "kernel": "perturb_flat_kernel"}
         # What really bounds the perturbation passes: vector-ALU issue.  One Philox call (4 Gaussians, 32-bit mode) costs
-        # VALU_PER_CALL wave64 vector instructions (static count of the kernels' main paths); a SIMD issues one per 4
-        # cycles (16 lanes), i.e. 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instructions/s (the 157.3 TFLOP/s
-        # fp32 vector figure counts packed FMAs as 4 flops per lane-instruction; packed fp32 is not used here).
+        # VALU_PER_CALL wave64 vector instructions (static count of the kernels' main paths).  The peak is the vector unit's
+        # rate for simple instructions, 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-instructions/s; the mix also holds
+        # multiply-adds (4-5 cycles), conversions, v_rsq (8) and, in the tile kernel, fp32 MFMAs, so the fraction stays near 0.5.
         if args.gauss_bits == 32 and cfg.dtype == "bf16":
             for name, elems, key in (("perturb_tile", guided_elems, "roofline_perturb"), ("perturb_flat", flat_elems, "roofline_perturb_flat")):
                 if name in kern and key in out and elems:
