@@ -328,7 +328,7 @@ def main():
                            "perturb_flat": out.get("roofline_perturb_flat")}.get(dom) or out.get("roofline_gemm") or out.get("roofline_perturb")
         out["dominant_kernel_class"] = dom
     if prof and "perturb_tile" in out.get("kernel_ms", {}) and cfg.arch != I.ARCH_LINEAR_LSQ and u_bytes:
-        # Sec. 4.4: the share of a layer's basis that would have to travel as 4-bit codes for the transfer to hide
+        # Sec. 3.4: the share of a layer's basis that would have to travel as 4-bit codes for the transfer to hide
         # under that layer's part of a perturbation pass, for a few link speeds (the restore is fused into the
         # pass and costs nothing measurable: a pass over 4-bit bases takes the same time).
         layer_bytes = sum(s.rows * cfg.k * 4 for s in specs if s.guided) / I.CONFIGS[args.config].n_layer   # uncompressed fp32 basis

@@ -3,12 +3,12 @@
  * gradient rectification) for one AMD MI355X (gfx950) GPU.
  *
  * The calls follow the paper's statement of the problem:
- *   - objective and two-point estimator: Sec. 4.2, Eq. (9);
+ *   - objective and two-point estimator: Sec. 3.2, Eq. (9);
  *   - hybrid perturbation z_h = sqrt(alpha/n) z + sqrt((1-alpha)/m) V z_g: Eq. (10);
  *   - rectified estimator: Eq. (11);
  *   - client procedure (perturb, two forward passes, send one scalar) and
  *     edge-server procedure (regenerate z_h from the seed, update): Algorithm 1;
- *   - in-place application of the perturbation to the local model: Sec. 4.1,
+ *   - in-place application of the perturbation to the local model: Sec. 3.1,
  *     workflow step 5.
  *
  * Conventions
@@ -71,7 +71,7 @@ typedef enum {
   ZGR_ROLE_COUNT = 23
 } zgr_role;
 
-/* One parameter tensor of the model W in R^d (Sec. 4.2). */
+/* One parameter tensor of the model W in R^d (Sec. 3.2). */
 typedef struct {
   void*        theta;      /* DEVICE, 16-byte aligned, rows*cols elements, row-major, MUTATED IN PLACE */
   int64_t      rows, cols; /* 1-D tensors: rows = 1                                            */
@@ -79,7 +79,8 @@ typedef struct {
   uint32_t     tensor_id;  /* < 2^31, unique; enters the Philox counter                        */
   const float* U;          /* DEVICE, rows x ldu fp32, orthonormal columns; NULL => isotropic  */
   int32_t      k, ldu;     /* first k columns of U are used (k <= ldu, k <= rows, k <= 64);
-                              a guided tensor needs cols % 4 == 0 (cols % 8 with gauss_bits 16) */
+                              a guided tensor needs cols % 4 == 0 (cols % 8 with gauss_bits 16);
+                              ranks >= 16 and < 16 may be mixed in one table (two kernels serve them) */
   int32_t      role;       /* zgr_role                                                         */
   int32_t      layer;      /* block index, -1 for tensors outside the blocks                   */
 } zgr_tensor;
@@ -153,7 +154,7 @@ zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* ten
 zgr_status zgr_set_basis(zgr_ctx* ctx, int32_t tensor_index, const float* U, int32_t k, int32_t ldu);
 
 /* Guided round with the basis sent compressed (Data Transmission Controller,
- * Sec. 4.4, first equation): Uq holds 4-bit codes, rows x ldq BYTES, element l
+ * Sec. 3.4, first equation): Uq holds 4-bit codes, rows x ldq BYTES, element l
  * of a row in byte l/2 (low nibble for even l); the kernels restore
  * U[r][l] = lambda * (code - delta) in fp32 while loading the operand, so no
  * fp32 copy of the basis is ever stored.  Uq is DEVICE memory owned by the
@@ -163,7 +164,7 @@ zgr_status zgr_set_basis(zgr_ctx* ctx, int32_t tensor_index, const float* U, int
 zgr_status zgr_set_basis_q4(zgr_ctx* ctx, int32_t tensor_index, const uint8_t* Uq, int32_t k, int32_t ldq,
                             float lambda, float delta);
 
-/* System-level Pipeline Controller (Sec. 4.3), client side: the basis of this
+/* System-level Pipeline Controller (Sec. 3.3), client side: the basis of this
  * tensor stays in HOST memory (where the link from the cloud delivers it) and
  * is brought to the device layer by layer during every perturbation pass.
  * Tensors with the same `layer` travel together, and consecutive layers are
@@ -199,7 +200,7 @@ zgr_status zgr_set_basis_host(zgr_ctx* ctx, int32_t tensor_index, const void* U_
 zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t ldu, uint8_t* Uq, int32_t ldq,
                               float* minmax_dev, float* lambda_out, float* delta_out, void* hip_stream);
 
-/* Sec. 4.4, the latency relations that close the section (host arithmetic only,
+/* Sec. 3.4, the latency relations that close the section (host arithmetic only,
  * no device work): the smallest share omega in [0, 1] of a layer's guided data
  * of data_bytes bytes that has to travel compressed (to theta of its size,
  * 0 < theta < 1) over a link of bandwidth_bytes_per_s so that the transfer
@@ -228,7 +229,9 @@ zgr_status zgr_dtc_memory_factor(int32_t n_layers, double omega, double theta, d
  * (both products in fp32: c = fl(eps - fl(lr g))), which leaves the parameters
  * updated as restore + zgr_apply_update(step, g, lr) would, with one rounding
  * of the storage type fewer; zgr_apply_update must then not be called for this
- * step.  A non-finite loss still restores (adds eps Z) and updates nothing.     */
+ * step.  A non-finite loss still restores (adds eps Z) and updates nothing.
+ * ZGR_ERR_DEVICE (a launch or copy failed part-way) is the one status after
+ * which the parameters are undefined: some tensors may hold a perturbed value. */
 zgr_status zgr_step(zgr_ctx* ctx, uint64_t step, const zgr_batch* batch, zgr_result* out);
 
 /* Edge-server block of Algorithm 1 for one client with weight 1:
@@ -243,7 +246,11 @@ zgr_status zgr_apply_update(zgr_ctx* ctx, uint64_t step, float g, float lr);
  * in ONE read-modify-write pass over the parameters per group of ZGR_MAX_BATCH
  * perturbations (n may exceed it; n = 0 is a no-op): every Z(seed, steps[q]) is
  * regenerated from the seed, the sum is accumulated in fp32 in list order and
- * the result is rounded to the storage type once per pass.  steps, g: HOST
+ * the result is rounded to the storage type once per pass.  For n > ZGR_MAX_BATCH
+ * the call is DEFINED as successive passes over the groups q = 0..7, 8..15, ...
+ * in list order, each group one exact-sum-then-round update of the parameters the
+ * previous group left (so it equals the same call made group by group, not one
+ * rounding of the whole sum).  steps, g: HOST
  * arrays of n entries, steps[q] < 2^32; each product lr*g[q] is formed in fp32.
  * The bases must be those of the steps named (one guidance interval).
  * Asynchronous.  n = 1 equals zgr_apply_update.                                */
@@ -288,6 +295,8 @@ zgr_status zgr_debug_set_stage_tiles(zgr_ctx* ctx, int64_t min_tiles);
 /* Per-example losses of the last forward (DEVICE -> HOST copy, synchronises):
  * LM: [batch*(seq-1)] token losses; CLS: [batch]; LSQ: [batch].  n must match. */
 zgr_status zgr_debug_last_row_losses(zgr_ctx* ctx, float* out /* HOST */, int64_t n);
+/* The same for either forward of the last zgr_step: which = 0 the rows of L+, 1 the rows of L-. */
+zgr_status zgr_debug_step_row_losses(zgr_ctx* ctx, int32_t which, float* out /* HOST */, int64_t n);
 /* Radius sqrt(-2 ln u) for all 2^23 (bits=32) or 2^16 (bits=16) values of the radius uniform, and
  * (cos, sin)(2 pi v) for all 2^24 / 2^16 angle uniforms, as the fused kernel evaluates them. */
 zgr_status zgr_debug_radius_table(int32_t gauss_bits, float* out /* DEVICE */, void* hip_stream);

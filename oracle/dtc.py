@@ -1,7 +1,7 @@
 """TEST INFRASTRUCTURE ONLY: CPU oracle, never imported by the product path.
 
 b-bit affine quantisation of the guided basis for transmission (Data Transmission
-Controller, Sec. 4.4, the quantise / restore pair of its first equation):
+Controller, Sec. 3.4, the quantise / restore pair of its first equation):
 
     x_q = round(x / lambda + delta),      x_hat = lambda * (x_q - delta),
     lambda = (max - min) / (2^b - 1)
@@ -61,7 +61,7 @@ def unpack_nibbles(b, k):
 
 
 # ----------------------------------------------------------------------------------------------------
-# How much to compress (Data Transmission Controller, Sec. 4.4, the three latency relations and the
+# How much to compress (Data Transmission Controller, Sec. 3.4, the three latency relations and the
 # memory relation that close the section).  A layer's guided data of D0 bytes crosses a link of B0
 # bytes/s; a share omega of it travels compressed to theta of its size and costs the client T(D0 omega)
 # of restoring on top of its computation T_cc; the transfer hides when T_t <= T_cc + T(D0 omega).

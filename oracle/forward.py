@@ -1,7 +1,7 @@
 """TEST INFRASTRUCTURE ONLY: CPU oracle, never imported by the product path.
 
 The loss L(W; x) that the two forward passes of the ZGR step evaluate
-(Sec. 4.2, Eq. (9) and Eq. (11); workflow step 6 of Sec. 4.1).  The paper uses
+(Sec. 3.2, Eq. (9) and Eq. (11); workflow step 6 of Sec. 3.1).  The paper uses
 off-the-shelf transformer checkpoints; here the model is the plain textbook
 one: pre-LayerNorm blocks, multi-head softmax attention scaled by
 1/sqrt(d_head), erf-GELU feed-forward, learned positions, final LayerNorm, and

@@ -1,6 +1,6 @@
 """TEST INFRASTRUCTURE ONLY: CPU oracle, never imported by the product path.
 
-Seeded hybrid perturbation of one parameter tensor (Sec. 4.2, Eq. (10) and
+Seeded hybrid perturbation of one parameter tensor (Sec. 3.2, Eq. (10) and
 Algorithm 1, client block):
 
     z_h = sqrt(alpha/n) z + sqrt((1-alpha)/m) V z_g,

@@ -4,7 +4,7 @@ Philox4x32-10 counter-based generator (Salmon, Moraes, Dror, Shaw, "Parallel
 random numbers: as easy as 1, 2, 3", SC'11, Sec. 3.2: the Philox S-box built
 from a 32x32->64 multiply, the Feistel-like word permutation, and the Weyl key
 schedule).  The paper only says that clients and the edge server draw the
-local perturbation from a shared random seed (Sec. 4.1 workflow step 5,
+local perturbation from a shared random seed (Sec. 3.1 workflow step 5,
 Algorithm 1 "shared random seed s" and the edge server's "regenerate identical
 z_h via seed s"); a counter-based generator is what makes that regeneration
 a pure function of (seed, step, tensor, element).

@@ -8,11 +8,11 @@ Algorithm 1 (client block, edge-server block) with the estimator of Eq. (11):
     W <- W - eta g_hat
 
 The parameters are perturbed in place and restored, as the workflow of
-Sec. 4.1 (step 5) describes, in three passes W += eps Z, W -= 2 eps Z,
+Sec. 3.1 (step 5) describes, in three passes W += eps Z, W -= 2 eps Z,
 W += eps Z, each pass regenerating Z from (seed, step).  Storage types:
 'f32' (one fp32 fused multiply-add per element and pass) or 'bf16' (the same,
 followed by round-to-nearest-even; no fp32 master copy, since the method's
-memory claim rests on holding only the model itself, Sec. 4.3).
+memory claim rests on holding only the model itself, Sec. 3.3).
 """
 import numpy as np
 
@@ -35,8 +35,11 @@ class Tensor:
 
 class ZgrOracle:
     def __init__(self, tensors, loss_fn, seed, eps, alpha, dtype="f32", scale_mode=SCALE_UNIT,
-                 gauss_bits=32):
-        """loss_fn(dict name -> fp64 array) -> python float."""
+                 gauss_bits=32, keep_z=False):
+        """loss_fn(dict name -> fp64 array) -> python float.  keep_z: remember every Z(seed, step) of
+        every tensor once computed (Z is a pure function of them, so the passes of a step, which all
+        regenerate it, get the same array; only worth the memory on large models)."""
+        self.z_kept = {} if keep_z else None
         self.tensors = list(tensors)
         self.loss_fn = loss_fn
         self.seed, self.eps, self.alpha = int(seed), np.float32(eps), float(alpha)
@@ -44,8 +47,13 @@ class ZgrOracle:
 
     # -- building blocks -----------------------------------------------------
     def z_of(self, t: Tensor, step: int):
-        return hybrid_z(self.seed, step, t.tensor_id, t.rows, t.cols, t.U, t.k, self.alpha,
-                        self.scale_mode, self.bits)
+        if self.z_kept is not None and (t.tensor_id, step) in self.z_kept:
+            return self.z_kept[(t.tensor_id, step)]
+        z = hybrid_z(self.seed, step, t.tensor_id, t.rows, t.cols, t.U, t.k, self.alpha,
+                     self.scale_mode, self.bits)
+        if self.z_kept is not None:
+            self.z_kept[(t.tensor_id, step)] = z
+        return z
 
     def axpy_all(self, step: int, c):
         """theta <- rnd(theta + c Z(seed, step)) for every tensor."""

@@ -73,6 +73,7 @@ SYMBOLS = {
     "zgr_debug_fill_z": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p]),
     "zgr_debug_set_stage_tiles": (C.c_int, [C.c_void_p, C.c_int64]),
     "zgr_debug_last_row_losses": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64]),
+    "zgr_debug_step_row_losses": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]),
     "zgr_debug_radius_table": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p]),
     "zgr_debug_cossin_table": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "zgr_debug_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -33,6 +34,7 @@ struct Carve {                 // workspace layout (byte offsets)
   size_t descs = 0, flat = 0, tiles = 0, dbg = 0;
   size_t cap_flat = 0, cap_tiles = 0, cap_dbg = 0;   // capacities in items
   size_t x = 0, h = 0, qkv = 0, ctx = 0, ff = 0, logits = 0, row_loss = 0, targets = 0, loss = 0;
+  size_t row_loss_stride = 0;                  // floats between the row losses of L+ (slot 0) and L- (slot 1)
   size_t spc[kSpcSlots] = {}, spc_bytes = 0;   // staging slots for the bases of one layer each (streamed bases)
   size_t total = 0;
 };
@@ -57,12 +59,14 @@ struct zgr_ctx {
   // Bases that stay in HOST memory and are streamed layer by layer during a pass (t[i].U NULL, t[i].k the rank)
   struct HostBasis { const void* host = nullptr; const unsigned char* dev = nullptr; int bits = 0; float lambda = 0.f, delta = 0.f; size_t slot_off = 0; };
   std::vector<HostBasis> hb;
-  struct Group { int layer = 0; std::vector<int> tensors; size_t tile_begin = 0, tile_end = 0; int max_k = 0, min_k = 0;
+  // A run of the tile list served by one kernel: class 0 = ranks >= kMfmaMinK (matrix-core kernel), class 1 = smaller
+  // ranks (vector kernel).  A context may mix both; each class gets its own launch.
+  struct TileRange { size_t begin = 0, end = 0; int max_k = 0, min_k = kMaxK + 1; };
+  struct Group { int layer = 0; std::vector<int> tensors; TileRange cls[2];
                  std::vector<StageCopy> copies; };   // host -> staging-slot pieces, contiguous runs merged
   std::vector<Group> groups;   // streamed groups in pass order; their tiles follow the resident ones in `tiles`
-  size_t resident_tiles = 0;
+  TileRange res[2];            // tiles of the resident guided tensors, by class
   size_t min_stage_tiles = kMinStageTiles;   // consecutive layers share a stage until it holds this many tiles
-  int res_max_k = 0, res_min_k = 0;
   std::vector<TensorDesc> descs;
   std::vector<WorkItem> flat, tiles;
   bool lists_dirty = true;
@@ -79,6 +83,8 @@ struct zgr_ctx {
   std::string err;
   Prof prof;
   int64_t last_rows = 0;       // rows of the last forward's row_loss
+  int last_slot = 0;           // which of the two row-loss buffers the last forward wrote
+  int64_t slot_rows[2] = {0, 0};
   double host_loss[2] = {0, 0};
 };
 
@@ -147,7 +153,7 @@ bool is_streamed(const zgr_ctx* c, size_t i) { return i < c->hb.size() && c->hb[
 void build_lists(zgr_ctx* c) {
   const int P = group_size(c->cfg.gauss_bits);
   c->flat.clear(); c->tiles.clear(); c->descs.resize(c->t.size()); c->groups.clear();
-  c->max_k = 0; c->min_k = kMaxK + 1; c->res_max_k = 0; c->res_min_k = kMaxK + 1;
+  c->max_k = 0; c->min_k = kMaxK + 1;
   // Streamed tensors: layers in order of first appearance; consecutive layers are packed into one stage until the
   // stage holds min_stage_tiles tiles, as long as its bases fit a staging slot and its pieces one launch's list.
   struct LayerSet { int layer; std::vector<int> tensors; size_t bytes = 0, tiles = 0, pieces = 0; };
@@ -175,7 +181,7 @@ void build_lists(zgr_ctx* c) {
     for (const LayerSet& l : layers) {
       const bool open = !c->groups.empty() && tiles > 0;
       if (!open || tiles >= c->min_stage_tiles || bytes + l.bytes > c->cv.spc_bytes || pieces + l.pieces > (size_t)kMaxStage) {
-        c->groups.push_back({}); c->groups.back().layer = l.layer; c->groups.back().min_k = kMaxK + 1;
+        c->groups.push_back({}); c->groups.back().layer = l.layer;
         bytes = tiles = pieces = 0;
       }
       for (int i : l.tensors) c->groups.back().tensors.push_back(i);
@@ -220,21 +226,35 @@ void build_lists(zgr_ctx* c) {
       else { d.U = reinterpret_cast<const float*>(slot); d.Uq = nullptr; d.ldu = t.k; }
     }
     mix_coefficients(c->cfg, t, guided, &d.a, &d.b);
-    append_items(t, (int)i, guided, P, c->flat, c->tiles);
     if (guided && t.k > c->max_k) c->max_k = t.k;
     if (guided && t.k < c->min_k) c->min_k = t.k;
   };
+  // the tiles of a set of tensors, matrix-core class first, then the vector class
+  auto tile_ranges = [&](const std::vector<int>& members, zgr_ctx::TileRange* cls) {
+    for (int k_class = 0; k_class < 2; ++k_class) {
+      cls[k_class] = zgr_ctx::TileRange{};
+      cls[k_class].begin = c->tiles.size();
+      for (int i : members) {
+        if (!is_guided(c, (size_t)i) || (c->t[i].k >= kMfmaMinK ? 0 : 1) != k_class) continue;
+        append_items(c->t[i], i, true, P, c->flat, c->tiles);
+        cls[k_class].max_k = std::max(cls[k_class].max_k, c->t[i].k);
+        cls[k_class].min_k = std::min(cls[k_class].min_k, c->t[i].k);
+      }
+      cls[k_class].end = c->tiles.size();
+    }
+  };
+  std::vector<int> resident;
   for (size_t i = 0; i < c->t.size(); ++i) {
     if (is_streamed(c, i)) continue;
     describe(i, 0);
-    if (is_guided(c, i)) { c->res_max_k = std::max(c->res_max_k, c->t[i].k); c->res_min_k = std::min(c->res_min_k, c->t[i].k); }
+    if (is_guided(c, i)) resident.push_back((int)i);
+    else append_items(c->t[i], (int)i, false, P, c->flat, c->tiles);
   }
-  c->resident_tiles = c->tiles.size();
+  tile_ranges(resident, c->res);
   for (size_t gi = 0; gi < c->groups.size(); ++gi) {
     zgr_ctx::Group& g = c->groups[gi];
-    g.tile_begin = c->tiles.size();
-    for (int i : g.tensors) { describe((size_t)i, (int)gi); g.max_k = std::max(g.max_k, c->t[i].k); g.min_k = std::min(g.min_k, c->t[i].k); }
-    g.tile_end = c->tiles.size();
+    for (int i : g.tensors) describe((size_t)i, (int)gi);
+    tile_ranges(g.tensors, g.cls);
   }
   c->lists_dirty = true;
 }
@@ -331,13 +351,15 @@ Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int
     // and token) and the target logits of the fused cross-entropy
     const size_t lm_logits = dtype == ZGR_BF16 ? M * ((size_t)2 * ce_partials_per_row(m.vocab) + 1) * 4 : M * (size_t)m.vocab * 4;
     cv.logits = take(m.arch == ZGR_ARCH_DECODER_LM ? lm_logits : (size_t)max_batch * m.n_class * 4);
-    cv.row_loss = take(M * 4);
+    cv.row_loss_stride = align_up(M * 4) / 4;
+    cv.row_loss = take(2 * cv.row_loss_stride * 4);
     cv.targets = take(M * 4);
   } else if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
     size_t out = 0;
     for (int i = 0; i < n_t; ++i) if (t[i].role == ZGR_ROLE_LSQ_W) out = (size_t)t[i].rows;
     cv.logits = take((size_t)max_batch * out * 4);
-    cv.row_loss = take((size_t)max_batch * 4);
+    cv.row_loss_stride = align_up((size_t)max_batch * 4) / 4;
+    cv.row_loss = take(2 * cv.row_loss_stride * 4);
   }
   cv.total = off;
   return cv;
@@ -407,30 +429,42 @@ PerturbArgs with_stage(const zgr_ctx* c, PerturbArgs a, size_t gi) {
 }
 
 // One pass over all parameters with the arguments `a` (single or batched) and coefficient coef: isotropic tensors
-// and resident guided tensors in one launch each, then the streamed groups layer by layer (Sec. 4.3): the launch of
+// and resident guided tensors in one launch each, then the streamed groups layer by layer (Sec. 3.3): the launch of
 // layer l also pulls the bases of layer l + 1 out of host memory into the other staging slot, so the transfer runs
 // under the arithmetic of layer l and needs no second stream; the first launch of the pass pulls layer 0.
 zgr_status run_pass(zgr_ctx* c, PerturbArgs a, float coef) {
   const WorkItem* tiles = a.tiles;
-  a.n_tiles = (int32_t)c->resident_tiles; a.max_k = c->res_max_k; a.min_k = c->res_min_k;
   bool staged0 = c->groups.empty();
   if (a.n_flat > 0) {
+    PerturbArgs af = staged0 ? a : with_stage(c, a, 0);
+    af.n_tiles = 0;
     ProfScope ps(c, ZGR_K_PERTURB_FLAT);
-    HIP_TRY(c, launch_perturb_flat(staged0 ? a : with_stage(c, a, 0), coef, nullptr, c->stream, c->n_cu));
+    HIP_TRY(c, launch_perturb_flat(af, coef, nullptr, c->stream, c->n_cu));
     staged0 = true;
   }
-  if (a.n_tiles > 0) {
-    ProfScope ps(c, ZGR_K_PERTURB_TILE);
-    HIP_TRY(c, launch_perturb_tile(staged0 ? a : with_stage(c, a, 0), coef, nullptr, c->stream, c->n_cu));
-    staged0 = true;
-  }
-  if (!staged0) HIP_TRY(c, launch_stage_only(with_stage(c, a, 0), c->stream));
+  // one tile launch per rank class present; `first` carries the staging copies of streamed group `next`
+  auto launch_ranges = [&](const zgr_ctx::TileRange* cls, bool& pending, size_t next) -> zgr_status {
+    for (int k_class = 0; k_class < 2; ++k_class) {
+      const zgr_ctx::TileRange& r = cls[k_class];
+      if (r.end == r.begin) continue;
+      PerturbArgs at = pending ? with_stage(c, a, next) : a;
+      at.n_stage = pending ? at.n_stage : 0;
+      at.tiles = tiles + r.begin; at.n_tiles = (int32_t)(r.end - r.begin); at.n_flat = 0; at.max_k = r.max_k; at.min_k = r.min_k;
+      ProfScope ps(c, ZGR_K_PERTURB_TILE);
+      HIP_TRY(c, launch_perturb_tile(at, coef, nullptr, c->stream, c->n_cu));
+      pending = false;
+    }
+    return ZGR_OK;
+  };
+  bool pending = !staged0;
+  zgr_status st = launch_ranges(c->res, pending, 0);
+  if (st != ZGR_OK) return st;
+  if (pending) HIP_TRY(c, launch_stage_only(with_stage(c, a, 0), c->stream));
   for (size_t gi = 0; gi < c->groups.size(); ++gi) {
-    const zgr_ctx::Group& g = c->groups[gi];
-    PerturbArgs ag = with_stage(c, a, gi + 1);
-    ag.tiles = tiles + g.tile_begin; ag.n_tiles = (int32_t)(g.tile_end - g.tile_begin); ag.n_flat = 0; ag.max_k = g.max_k; ag.min_k = g.min_k;
-    ProfScope ps(c, ZGR_K_PERTURB_TILE);
-    HIP_TRY(c, launch_perturb_tile(ag, coef, nullptr, c->stream, c->n_cu));
+    pending = gi + 1 < c->groups.size();
+    const bool had = pending;
+    if ((st = launch_ranges(c->groups[gi].cls, pending, gi + 1)) != ZGR_OK) return st;
+    if (had && pending) HIP_TRY(c, launch_stage_only(with_stage(c, a, gi + 1), c->stream));   // a group without tiles still has to pull for its successor
   }
   return ZGR_OK;
 }
@@ -460,7 +494,7 @@ zgr_status forward_loss(zgr_ctx* c, const zgr_batch* b, int slot) {
   hipStream_t s = c->stream;
   unsigned char* ws = c->ws;
   double* loss_dev = reinterpret_cast<double*>(ws + c->cv.loss) + slot;
-  float* row_loss = reinterpret_cast<float*>(ws + c->cv.row_loss);
+  float* row_loss = reinterpret_cast<float*>(ws + c->cv.row_loss) + (size_t)slot * c->cv.row_loss_stride;
   float* logits = reinterpret_cast<float*>(ws + c->cv.logits);
   const int dt = c->dtype;
   if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
@@ -469,7 +503,7 @@ zgr_status forward_loss(zgr_ctx* c, const zgr_batch* b, int slot) {
     { ProfScope ps(c, ZGR_K_LOSS);
       HIP_TRY(c, launch_lsq_rows(logits, reinterpret_cast<const float*>(b->y), row_loss, b->batch, (int)w.rows, s));
       HIP_TRY(c, launch_mean_f64(row_loss, b->batch, 1.0 / b->batch, loss_dev, s)); }
-    c->last_rows = b->batch;
+    c->last_rows = c->slot_rows[slot] = b->batch; c->last_slot = slot;
     return ZGR_OK;
   }
   const int M = b->batch * b->seq, d = m.d_model, ff = m.d_ff;
@@ -504,13 +538,13 @@ zgr_status forward_loss(zgr_ctx* c, const zgr_batch* b, int slot) {
     }
     { ProfScope ps(c, ZGR_K_LOSS);
       HIP_TRY(c, launch_mean_f64(row_loss, M, 1.0 / ((double)b->batch * (b->seq - 1)), loss_dev, s)); }
-    c->last_rows = M;
+    c->last_rows = c->slot_rows[slot] = M; c->last_slot = slot;
   } else {
     { ProfScope ps(c, ZGR_K_LOSS);
       HIP_TRY(c, launch_cls_head(dt, h, T(c, c->cls_w), T(c, c->cls_b), logits, b->batch, b->seq, d, m.n_class, s));
       HIP_TRY(c, launch_ce_rows(logits, reinterpret_cast<const int32_t*>(b->y), row_loss, b->batch, m.n_class, s));
       HIP_TRY(c, launch_mean_f64(row_loss, b->batch, 1.0 / b->batch, loss_dev, s)); }
-    c->last_rows = b->batch;
+    c->last_rows = c->slot_rows[slot] = b->batch; c->last_slot = slot;
   }
   return ZGR_OK;
 }
@@ -631,7 +665,7 @@ zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* ten
   }
   c->n_cu = n_cu;
   const RadiusEntry* tab = nullptr;
-  if (ensure_radius_table(&tab) != hipSuccess) { delete c; return fail(nullptr, ZGR_ERR_DEVICE, "could not set up the device tables"); }
+  if (ensure_radius_table(&tab, c->stream) != hipSuccess) { delete c; return fail(nullptr, ZGR_ERR_DEVICE, "could not set up the device tables"); }
   build_lists(c);
   *out = c;
   return ZGR_OK;
@@ -934,7 +968,17 @@ zgr_status zgr_debug_last_row_losses(zgr_ctx* c, float* out, int64_t n) {
   if (!c) return ZGR_ERR_NULL;
   if (!out) return fail(c, ZGR_ERR_NULL, "out is NULL");
   if (c->model.arch == ZGR_ARCH_NONE || n != c->last_rows) return fail(c, ZGR_ERR_SHAPE, "n = %lld, the last forward produced %lld rows", (long long)n, (long long)c->last_rows);
-  HIP_TRY(c, hipMemcpyAsync(out, c->ws + c->cv.row_loss, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(out, c->ws + c->cv.row_loss + sizeof(float) * (size_t)c->last_slot * c->cv.row_loss_stride, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_step_row_losses(zgr_ctx* c, int32_t which, float* out, int64_t n) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!out) return fail(c, ZGR_ERR_NULL, "out is NULL");
+  if (which != 0 && which != 1) return fail(c, ZGR_ERR_CONFIG, "which must be 0 (L+) or 1 (L-)");
+  if (c->model.arch == ZGR_ARCH_NONE || n != c->slot_rows[which]) return fail(c, ZGR_ERR_SHAPE, "n = %lld, that forward produced %lld rows", (long long)n, (long long)c->slot_rows[which]);
+  HIP_TRY(c, hipMemcpyAsync(out, c->ws + c->cv.row_loss + sizeof(float) * (size_t)which * c->cv.row_loss_stride, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return ZGR_OK;
 }

@@ -1,5 +1,5 @@
-// Forward pass L(W; x) for the two loss evaluations of the ZGR step (Sec. 4.2,
-// Eq. (11); Sec. 4.1 workflow step 6): pre-LayerNorm transformer blocks with
+// Forward pass L(W; x) for the two loss evaluations of the ZGR step (Sec. 3.2,
+// Eq. (11); Sec. 3.1 workflow step 6): pre-LayerNorm transformer blocks with
 // softmax attention and erf-GELU feed-forward, next-token cross-entropy through
 // the tied embedding (decoder) or a classification head on the first token
 // (encoder), and the least-squares loss of a single linear layer.

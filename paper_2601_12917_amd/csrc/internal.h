@@ -33,6 +33,7 @@ struct WorkItem {
 constexpr int kFlatGroupsPerItem = 2048;   // Philox calls per flat work item (8 per thread)
 constexpr int kTileRowsPerIter   = 128;    // rows one block covers per iteration (4 waves x 32)
 constexpr int kMaxK              = 64;
+constexpr int kMfmaMinK          = 16;     // from this rank on the U R contraction of a tile runs on the matrix cores
 constexpr int kMaxBatch          = 8;      // perturbations summed in one pass (zgr_apply_updates)
 constexpr int kMaxStage          = 16;     // tensors whose bases one launch may pull in for the next one
 constexpr int kPullBlocks        = 32;     // blocks of such a launch that do the pulling
@@ -70,8 +71,9 @@ struct PerturbArgs {
 hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu);
 hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipStream_t s, int n_cu);
 
-// radius table upload (once per process and device) and access
-hipError_t ensure_radius_table(const RadiusEntry** dev_ptr);
+// The radius table of the current device: filled once per process and device (thread-safe), by a copy on stream s
+// that has completed when the call returns.
+hipError_t ensure_radius_table(const RadiusEntry** dev_ptr, hipStream_t s);
 
 hipError_t launch_debug_philox(const uint32_t* ctr, uint32_t k0, uint32_t k1, uint32_t* out, int64_t n, hipStream_t s);
 hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t id_stream, int bits, int64_t first, int64_t n,

@@ -1,6 +1,6 @@
 // In-place perturbation pass theta <- rnd(theta + c Z), Z = a G + b U R (Eq. (10)),
 // with G and R regenerated from the shared seed in registers / LDS and never
-// stored (Sec. 4.1 step 5; Algorithm 1, client and edge-server blocks).  One
+// stored (Sec. 3.1 step 5; Algorithm 1, client and edge-server blocks).  One
 // pass reads and writes every parameter exactly once.
 //
 // Two persistent kernels per pass, each looping over a work list:
@@ -10,6 +10,8 @@
 //         generates its slice of R once into LDS, stages U row blocks in LDS,
 //         contracts U R in registers and fuses G, the mix and the axpy.
 #include "internal.h"
+
+#include <mutex>
 
 namespace zgr {
 
@@ -72,7 +74,7 @@ template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const Radiu
 template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
 
 // Element [row][l] of the basis: fp32 as stored, or restored from its 4-bit code as lambda (code - delta)
-// (Sec. 4.4, first equation): the restore is fused into the operand load, the fp32 basis never exists in memory.
+// (Sec. 3.4, first equation): the restore is fused into the operand load, the fp32 basis never exists in memory.
 __device__ __forceinline__ float basis_at(const TensorDesc& d, int64_t row, int l) {
   if (d.Uq) {
     const uint32_t byte = d.Uq[row * d.ldu + (l >> 1)];
@@ -82,7 +84,7 @@ __device__ __forceinline__ float basis_at(const TensorDesc& d, int64_t row, int 
   return load_global<float>(d.U + row * d.ldu + l);
 }
 
-// Layer pipeline (Sec. 4.3): a launch also fetches the basis data its successor will need, straight from pinned
+// Layer pipeline (Sec. 3.3): a launch also fetches the basis data its successor will need, straight from pinned
 // host memory into the staging slot the successor reads.  The last a.pull_blocks blocks of the grid do nothing
 // else (a block that waited for the host link before computing would delay its share of the tiles by that long);
 // the other blocks share the work list among themselves.  The kernel boundary makes the data visible.
@@ -163,7 +165,6 @@ __global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const 
 
 // ------------------------------------------------------------------ tile
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-constexpr int kMfmaMinK = 16;      // from this rank on the U R contraction runs on the matrix cores
 
 // One lane's P consecutive elements starting at flat index e0: G from the seed, Z = a G + (b U R), axpy.
 template <typename T, int P, bool WRITE_Z, bool BATCH>
@@ -426,7 +427,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   }
 }
 
-// ------------------------------------------------------------------ affine quantiser of a basis (cloud side of Sec. 4.4)
+// ------------------------------------------------------------------ affine quantiser of a basis (cloud side of Sec. 3.4)
 // min / max as order-preserving integers, so that integer atomics reduce them
 __device__ __forceinline__ int32_t float_order(float x) { const int32_t b = __float_as_int(x); return b >= 0 ? b : (int32_t)(0x80000000u - (uint32_t)b); }
 __device__ __forceinline__ float order_float(int32_t o) { return __int_as_float(o >= 0 ? o : (int32_t)(0x80000000u - (uint32_t)o)); }
@@ -532,28 +533,37 @@ __device__ RadiusEntry g_radius_table[kRadiusTabEntries];
 
 }  // namespace
 
-hipError_t ensure_radius_table(const RadiusEntry** dev_ptr) {
+hipError_t ensure_radius_table(const RadiusEntry** dev_ptr, hipStream_t s) {
+  static std::mutex mu;
   static const RadiusEntry* cached[64] = {};
+  static RadiusEntry host[kRadiusTabEntries];
+  static bool host_ready = false;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
   if (!cached[dev]) {
-    static RadiusEntry host[kRadiusTabEntries];
-    for (int E = 0; E < 24; ++E)
-      for (int j = 0; j < 64; ++j) {
-        const double cj = __builtin_rint(128.0 / (1.0 + (j + 0.5) / 64.0)) / 128.0;
-        double hl = 2.0 * __builtin_log(cj) + 2.0 * (24.0 - E) * 0.69314718055994530942;
-        if (E == 23 && j == 63) hl = 0.0;        // c = 1/2, N c 2^-23 -> exactly -2 log1p(z)
-        RadiusEntry& r = host[E * 64 + j];
-        r.H = (float)hl;
-        r.L = (float)(hl - (double)r.H);
-        r.C = (float)__builtin_ldexp(cj, -E);
-      }
+    if (!host_ready) {
+      for (int E = 0; E < 24; ++E)
+        for (int j = 0; j < 64; ++j) {
+          const double cj = __builtin_rint(128.0 / (1.0 + (j + 0.5) / 64.0)) / 128.0;
+          double hl = 2.0 * __builtin_log(cj) + 2.0 * (24.0 - E) * 0.69314718055994530942;
+          if (E == 23 && j == 63) hl = 0.0;        // c = 1/2, N c 2^-23 -> exactly -2 log1p(z)
+          RadiusEntry& r = host[E * 64 + j];
+          r.H = (float)hl;
+          r.L = (float)(hl - (double)r.H);
+          r.C = (float)__builtin_ldexp(cj, -E);
+        }
+      host_ready = true;
+    }
     void* p = nullptr;
     e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_radius_table));
     if (e != hipSuccess) return e;
-    e = hipMemcpy(p, host, sizeof(host), hipMemcpyHostToDevice);
+    // ordered with the caller's work: on its stream, complete before anything that follows this call is enqueued
+    e = hipMemcpyAsync(p, host, sizeof(host), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return e;
+    e = hipStreamSynchronize(s);
     if (e != hipSuccess) return e;
     cached[dev] = reinterpret_cast<const RadiusEntry*>(p);
   }
@@ -640,7 +650,7 @@ hipError_t launch_perturb_flat(const PerturbArgs& a, float c, float* zout, hipSt
   if (a.n_q < 0 || a.n_q > kMaxBatch || (a.n_q > 0 && zout)) return hipErrorInvalidValue;
   if (a.n_stage < 0 || a.n_stage > kMaxStage) return hipErrorInvalidValue;
   const RadiusEntry* tab = nullptr;
-  hipError_t e = ensure_radius_table(&tab);
+  hipError_t e = ensure_radius_table(&tab, s);
   if (e != hipSuccess) return e;
   if (a.dtype == 0) return a.bits == 32 ? launch_flat_t<float, 4>(a, c, zout, s, n_cu, tab) : launch_flat_t<float, 8>(a, c, zout, s, n_cu, tab);
   return a.bits == 32 ? launch_flat_t<bf16_t, 4>(a, c, zout, s, n_cu, tab) : launch_flat_t<bf16_t, 8>(a, c, zout, s, n_cu, tab);
@@ -653,7 +663,7 @@ hipError_t launch_perturb_tile(const PerturbArgs& a, float c, float* zout, hipSt
   if (a.n_stage < 0 || a.n_stage > kMaxStage) return hipErrorInvalidValue;
   if (a.n_stage < 0 || a.n_stage > kMaxStage) return hipErrorInvalidValue;
   const RadiusEntry* tab = nullptr;
-  hipError_t e = ensure_radius_table(&tab);
+  hipError_t e = ensure_radius_table(&tab, s);
   if (e != hipSuccess) return e;
   if (a.dtype == 0) return a.bits == 32 ? launch_tile_t<float, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<float, 8>(a, c, zout, s, n_cu, tab);
   return a.bits == 32 ? launch_tile_t<bf16_t, 4>(a, c, zout, s, n_cu, tab) : launch_tile_t<bf16_t, 8>(a, c, zout, s, n_cu, tab);
@@ -699,7 +709,7 @@ hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t 
                               float* out, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   const RadiusEntry* tab = nullptr;
-  hipError_t e = ensure_radius_table(&tab);
+  hipError_t e = ensure_radius_table(&tab, s);
   if (e != hipSuccess) return e;
   const int P = bits == 32 ? 4 : 8;
   int64_t blocks = (n / P + 256) / 256;
@@ -711,7 +721,7 @@ hipError_t launch_debug_gauss(uint32_t k0, uint32_t k1, uint32_t step, uint32_t 
 
 hipError_t launch_debug_radius_table(int bits, float* out, hipStream_t s) {
   const RadiusEntry* tab = nullptr;
-  hipError_t e = ensure_radius_table(&tab);
+  hipError_t e = ensure_radius_table(&tab, s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(debug_radius_kernel, dim3(bits == 32 ? 2048 : 64), dim3(256), 0, s, bits, tab, out);
   return hipGetLastError();

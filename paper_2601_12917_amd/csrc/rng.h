@@ -1,7 +1,7 @@
 // Device-side random stream of the ZGR perturbation: Philox4x32-10 counters
 // (Salmon et al., SC'11) -> Box-Muller Gaussians, all in fp32 registers.
 //
-// The paper (Sec. 4.1 step 5, Algorithm 1) only requires that client and edge
+// The paper (Sec. 3.1 step 5, Algorithm 1) only requires that client and edge
 // server regenerate the same perturbation from the shared seed; a counter-based
 // generator makes every element a pure function of
 // (seed, step, tensor id, stream, flat element index).

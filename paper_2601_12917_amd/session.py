@@ -205,6 +205,12 @@ class Session:
         B.check(self.lib.zgr_debug_last_row_losses(self.ctx, out.ctypes.data, n), self.ctx)
         return out
 
+    def step_row_losses(self, which, n):
+        """Row losses of the last step's forward at W + eps Z (which = 0) or W - eps Z (which = 1)."""
+        out = np.empty(n, dtype=np.float32)
+        B.check(self.lib.zgr_debug_step_row_losses(self.ctx, which, out.ctypes.data, n), self.ctx)
+        return out
+
     def profile_enable(self, on=True):
         B.check(self.lib.zgr_profile_enable(self.ctx, 1 if on else 0), self.ctx)
 

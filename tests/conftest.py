@@ -25,3 +25,12 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture
+def say(capsys):
+    """Prints a progress line past pytest's capture: a test that works for minutes stays visibly alive."""
+    def _say(msg):
+        with capsys.disabled():
+            print("  [" + msg + "]", flush=True)
+    return _say

@@ -1,4 +1,4 @@
-"""HIP path vs CPU oracle for the compressed basis (Sec. 4.4, first equation): the device quantiser's
+"""HIP path vs CPU oracle for the compressed basis (Sec. 3.4, first equation): the device quantiser's
 4-bit codes, lambda and delta bit for bit, and Z = a G + b U_hat R with U_hat restored from the codes
 inside the kernels, in the VALU (k < 16) and the matrix-core (k >= 16) tile kernels."""
 import numpy as np

@@ -51,6 +51,9 @@ SHAPES = [
     (100, 72, 5, 5),        # ragged in both directions, odd k
     (300, 136, 16, 16),     # two row blocks of a tile, ragged tail
     (130, 256, 64, 64),     # maximum k
+    (300, 136, 20, 20),     # matrix-core kernel with a rank that is no multiple of 8: the padded contraction steps are masked
+    (200, 264, 36, 40),     # the same with a truncated basis (36 of 40 columns) and ragged tiles in both directions
+    (70, 128, 17, 17),      # one step past the smallest matrix-core rank
     (64, 128, 8, 24),       # truncated basis: first 8 of 24 columns
     (1, 1000, 0, 0),        # 1-D, isotropic
     (1, 7, 0, 0),           # shorter than two Philox calls
@@ -123,4 +126,46 @@ def test_alpha_one_and_identity_basis_special_cases():
     cfg1 = I.shrink(cfg, alpha=1.0, k=4, k_full=4)
     sess = make_session(cfg1, [spec], [W], [_basis(rows, 4)], arch=-1)
     assert np.all(np.abs(sess.fill_z(0, 0) - G) <= 2 * np.spacing(np.abs(G)))  # alpha = 1: plain ZO-SGD direction
+    sess.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("ranks", [(8, 16), (16, 4), (20, 5, 64)])
+def test_mixed_ranks_in_one_context(ranks, dtype):
+    """Tensors with ranks on both sides of 16 in one table: each rank class is served by its own kernel (matrix
+    cores from 16 on, vector FMAs below), and every tensor's Z and in-place pass match the oracle."""
+    from paper_2601_12917_amd.session import ParamSpec, Session
+    rng = np.random.default_rng(sum(ranks))
+    shapes = [(192, 256), (150, 136), (256, 128)][:len(ranks)]
+    params, Ws, Us = [], [], []
+    for j, ((rows, cols), k) in enumerate(zip(shapes, ranks)):
+        W = (rng.standard_normal((rows, cols)) * PARAM_SCALE).astype(np.float32)
+        if dtype == "bf16":
+            W = P.bf16_round(W)
+        U = _basis(rows, k, seed=40 + j)
+        params.append(ParamSpec(f"W{j}", I.ROLE_LSQ_W, -1, 10 + j, W, U, k))
+        Ws.append(W); Us.append(U)
+    # plus an isotropic tensor, so the flat kernel runs in the same pass
+    b = (rng.standard_normal((1, 300)) * PARAM_SCALE).astype(np.float32)
+    if dtype == "bf16":
+        b = P.bf16_round(b)
+    params.append(ParamSpec("b", I.ROLE_B1, 0, 20, b))
+    cfg = _single_tensor_cfg(1, 1, 1, dtype)
+    sess = Session(-1, dtype, params, cfg.seed, cfg.eps, cfg.alpha, P.SCALE_UNIT, 32)
+    step, c = 6, np.float32(1e-3)
+    for j, ((rows, cols), k) in enumerate(zip(shapes, ranks)):
+        G, R, Z = P.hybrid_z(cfg.seed, step, 10 + j, rows, cols, Us[j], k, cfg.alpha, P.SCALE_UNIT, 32, parts=True)
+        got = sess.fill_z(j, step)
+        assert np.all(np.abs(got.astype(np.float64) - Z) <= _z_bound(cfg, G, R, Us[j], k, rows, cols, P.SCALE_UNIT)), (j, k)
+    sess.perturb(step, float(c))
+    for j, ((rows, cols), k) in enumerate(zip(shapes, ranks)):
+        Z = P.hybrid_z(cfg.seed, step, 10 + j, rows, cols, Us[j], k, cfg.alpha, P.SCALE_UNIT, 32)
+        want = P.axpy_inplace_value(Ws[j], c, Z, dtype)
+        got = sess.get_theta(j)
+        if dtype == "f32":
+            assert np.all(np.abs(got - want) <= F32_RTOL * (np.abs(want) + PARAM_SCALE)), (j, k)
+        else:
+            assert np.all(np.abs(got - want) <= BF16_RTOL * np.abs(want) + 1e-30) and np.mean(got == want) > 0.98, (j, k)
+    want_b = P.axpy_inplace_value(b, c, P.gauss_field(cfg.seed, step, 20, 0, 1, 300), dtype)
+    assert np.all(np.abs(sess.get_theta(len(ranks)) - want_b) <= (F32_RTOL if dtype == "f32" else BF16_RTOL) * (np.abs(want_b) + PARAM_SCALE))
     sess.close()

@@ -1,13 +1,16 @@
-"""Bases streamed from host memory layer by layer (Sec. 4.3): the result of every pass is bit-identical
-to the resident-basis path (same kernels, same operands), for fp32 bases and for 4-bit codes, over several
-passes so that both staging slots are reused; the resident path itself is checked against the oracle
-elsewhere."""
+"""Bases streamed from host memory layer by layer (Sec. 3.3): every step of a session whose bases are
+streamed is compared with the CPU oracle (losses, restored and updated parameters, Z of a streamed tensor),
+for fp32 bases and for 4-bit codes, over several passes so that both staging slots are reused; as an extra,
+the result of every pass is bit-identical to the resident-basis path (same kernels, same operands)."""
 import numpy as np
 import pytest
 
 import zgr_inputs as I
 from oracle import dtc as D
-from tests.util import inputs_of, make_batch_arrays, make_session, session_batch
+from oracle import perturbation as P
+from tests.test_gpu_perturb import _z_bound
+from tests.test_gpu_step import LOSS_RTOL, _close_params
+from tests.util import inputs_of, make_batch_arrays, make_oracle, make_session, oracle_loss_fn, session_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -59,6 +62,54 @@ def test_streamed_bases_give_identical_steps(cfg, mode, stage_tiles):
     i = g[len(g) // 2]
     assert np.array_equal(res.fill_z(i, 3), spc.fill_z(i, 3))
     res.close(); spc.close()
+
+
+@pytest.mark.parametrize("cfg", [DEEP_F32, DEEP_BF16], ids=lambda c: c.name)
+@pytest.mark.parametrize("mode,stage_tiles", [("f32", 1), ("q4", 1), ("mixed", 20)])
+def test_streamed_session_matches_oracle(cfg, mode, stage_tiles):
+    """The streamed path against the oracle itself: the oracle is given the basis each tensor really uses (the
+    first k columns as sent, or what the 4-bit codes restore to) and runs the same steps; losses within the
+    per-pass tolerance, parameters after the restoring pass and after the update (both sides apply the oracle's
+    g) within the parameter tolerance, and Z of a streamed tensor within the Gaussian / dot-product bound."""
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    spc = make_session(cfg, specs, values, bases)
+    spc.set_stage_tiles(stage_tiles)
+    used = list(bases)                     # per tensor: the basis the kernels end up contracting with
+    for i in _guided(specs, bases):
+        k = cfg.k
+        if mode == "q4" or (mode == "mixed" and specs[i].layer % 2 == 1):
+            lam, delta = D.affine_params(bases[i][:, :k], 4)
+            codes = D.quantize(bases[i][:, :k], lam, delta, 4)
+            spc.set_basis_host(i, None, k, codes=D.pack_nibbles(codes), lam=lam, delta=delta)
+            used[i] = D.dequantize(codes, lam, delta)
+        else:
+            spc.set_basis_host(i, bases[i], k)
+    o = make_oracle(cfg, specs, values, used, oracle_loss_fn(cfg, arrays))
+    batch = session_batch(spc, cfg, arrays)
+    lr = cfg.lr if cfg.dtype == "f32" else 1e-4
+    for step in range(3):
+        lp, lm, g = spc.step(step, batch)
+        olp, olm, og = o.step(step)
+        assert abs(lp - olp) <= LOSS_RTOL[cfg.dtype] * abs(olp), (step, lp, olp)
+        assert abs(lm - olm) <= LOSS_RTOL[cfg.dtype] * abs(olm), (step, lm, olm)
+        eps_z = [np.float32(cfg.eps) * np.abs(o.z_of(t, step)) for t in o.tensors]
+        for i, t in enumerate(o.tensors):
+            assert _close_params(spc.get_theta(i), t.theta, cfg.dtype, eps_z[i]), (step, t.name)
+        spc.apply_update(step, float(og), lr)
+        o.apply_update(step, og, lr)
+        for i, t in enumerate(o.tensors):
+            got = spc.get_theta(i)
+            assert _close_params(got, t.theta, cfg.dtype, eps_z[i]), (step, t.name)
+            t.theta = got.copy()           # same trajectory on both sides (bf16 roundings may differ by an ulp)
+    g_idx = _guided(specs, bases)
+    assert len({specs[i].layer for i in g_idx}) >= 4
+    for i in (g_idx[0], g_idx[len(g_idx) // 2], g_idx[-1]):
+        s_ = specs[i]
+        G, R, Z = P.hybrid_z(cfg.seed, 9, s_.tensor_id, s_.rows, s_.cols, used[i], cfg.k, cfg.alpha, cfg.scale_mode, 32, parts=True)
+        got = spc.fill_z(i, 9)
+        assert np.all(np.abs(got.astype(np.float64) - Z) <= _z_bound(cfg, G, R, used[i], cfg.k, s_.rows, s_.cols, cfg.scale_mode)), s_.name
+    spc.close()
 
 
 @pytest.mark.parametrize("codes", [False, True])

@@ -291,3 +291,64 @@ def test_seed_replay_by_a_context_without_model():
     with pytest.raises(Exception):
         server.loss(batch)
     client.close(); server.close()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_non_finite_loss_is_reported_and_parameters_are_restored_lsq(fused):
+    """A NaN in the batch makes both losses NaN: zgr_step must say so (ZGR_ERR_NONFINITE), leave the parameters
+    restored within the restore bound, and, with the fused last pass, apply no update."""
+    from paper_2601_12917_amd import binding as B
+    cfg = I.CONFIGS["cfg1"]
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    bad = {k: (None if v is None else v.copy()) for k, v in arrays.items()}
+    bad["x"][3, 17] = np.nan
+    sess = make_session(cfg, specs, values, bases, fuse_lr=cfg.lr if fused else None)
+    batch_bad = session_batch(sess, cfg, bad)
+    with pytest.raises(B.ZgrError) as ei:
+        sess.step(0, batch_bad)
+    assert ei.value.status == B.ZGR_ERR_NONFINITE
+    got = sess.get_theta(0)
+    # three fp32 passes +eps Z, -2 eps Z, +eps Z: back to within a few ulp of the magnitude reached in between
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays))
+    z = np.abs(o.z_of(o.tensors[0], 0))
+    bound = 4 * np.spacing((np.abs(values[0]) + np.float32(cfg.eps) * z).astype(np.float32))
+    assert np.all(np.isfinite(got)) and np.all(np.abs(got - values[0]) <= bound)
+    # the context is still usable: a clean batch gives the oracle's losses, from the restored parameters
+    good = session_batch(sess, cfg, arrays)
+    lp, lm, g = sess.step(1, good)
+    olp, olm, og = o.step(1, fuse_lr=cfg.lr if fused else None)
+    assert abs(lp - olp) <= LOSS_RTOL["f32"] * abs(olp) and abs(lm - olm) <= LOSS_RTOL["f32"] * abs(olm)
+    sess.close()
+
+
+@pytest.mark.parametrize("cfg", [TINY_LM, SMALL_BF16_LM], ids=lambda c: c.name)
+@pytest.mark.parametrize("fused", [False, True])
+def test_non_finite_loss_is_reported_and_parameters_are_restored_lm(cfg, fused):
+    """A loss out of range: a final LayerNorm gain of 3e38 overflows the hidden state, so the cross-entropy is not
+    finite.  ZGR_ERR_NONFINITE, every parameter back within the restore bound, no update in fused mode."""
+    from paper_2601_12917_amd import binding as B
+    specs, values, bases = inputs_of(cfg)
+    arrays = make_batch_arrays(cfg)
+    values = [v.copy() for v in values]
+    gi = [s.name for s in specs].index("lnf_g")
+    values[gi][...] = np.float32(3e38) if cfg.dtype == "f32" else P.bf16_round(np.array([3e38], np.float32))[0]
+    lr = cfg.lr if cfg.dtype == "f32" else 1e-4
+    sess = make_session(cfg, specs, values, bases, fuse_lr=lr if fused else None)
+    batch = session_batch(sess, cfg, arrays)
+    with pytest.raises(B.ZgrError) as ei:
+        sess.step(0, batch)
+    assert ei.value.status == B.ZGR_ERR_NONFINITE
+    o = make_oracle(cfg, specs, values, bases, oracle_loss_fn(cfg, arrays))
+    eps = np.float32(cfg.eps)
+    for c in (eps, np.float32(-2.0) * eps, eps):      # the three passes of the client block, and nothing else
+        o.axpy_all(0, c)
+    for i, t in enumerate(o.tensors):
+        got = sess.get_theta(i)
+        eps_z = eps * np.abs(o.z_of(t, 0))
+        assert np.all(np.isfinite(got)), t.name
+        if cfg.dtype == "f32":
+            assert np.all(np.abs(got - values[i]) <= 4 * np.spacing((np.abs(values[i]) + eps_z).astype(np.float32))), t.name
+        # bf16 storage does not return to the starting values exactly (three roundings): the oracle's three passes do the same
+        assert _close_params(got, t.theta, cfg.dtype, eps_z), t.name
+    sess.close()

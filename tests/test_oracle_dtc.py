@@ -1,4 +1,4 @@
-"""Pins of the affine quantiser (Sec. 4.4, first equation) against closed forms."""
+"""Pins of the affine quantiser (Sec. 3.4, first equation) against closed forms."""
 import numpy as np
 import pytest
 
@@ -76,7 +76,7 @@ def test_quantised_basis_keeps_the_guided_term_in_its_span():
     assert np.abs(resid).max() <= 1e-5 * np.abs(guided).max()
 
 
-# ------------------------------------------------------------------ how much to compress (Sec. 4.4)
+# ------------------------------------------------------------------ how much to compress (Sec. 3.4)
 
 def test_omega_zero_when_plain_transfer_already_hides():
     # 1 MB over 1 GB/s = 1 ms <= T_cc = 2 ms

@@ -13,11 +13,11 @@ def inputs_of(cfg, data_seed=0):
     return specs, values, bases
 
 
-def make_oracle(cfg, specs, values, bases, loss_fn, bits=32, scale_mode=None, dtype=None):
+def make_oracle(cfg, specs, values, bases, loss_fn, bits=32, scale_mode=None, dtype=None, keep_z=False):
     from oracle.zgr import Tensor, ZgrOracle
     tens = [Tensor(s.name, v, s.tensor_id, u, cfg.k if u is not None else 0) for s, v, u in zip(specs, values, bases)]
     return ZgrOracle(tens, loss_fn, cfg.seed, cfg.eps, cfg.alpha, dtype or cfg.dtype,
-                     cfg.scale_mode if scale_mode is None else scale_mode, bits)
+                     cfg.scale_mode if scale_mode is None else scale_mode, bits, keep_z=keep_z)
 
 
 def oracle_loss_fn(cfg, batch):

@@ -9,7 +9,7 @@ one child stream per array, so every array is reproducible from
 (config name, data seed, array name) alone.
 
 The paper evaluates on SST-2, AGNews, 20News and LongAlign with pretrained
-checkpoints (Sec. 5, "Models and Datasets"); those are not available, so the
+checkpoints (Sec. 4, "Models and Datasets"); those are not available, so the
 workloads here are stand-ins of the same shape: random-init weights,
 uniform or Zipf(1.1) token ids (the rank-frequency law of natural text) and,
 for the classifier, padding lengths uniform in [32, 256].
