@@ -264,6 +264,19 @@ zgr_status zgr_perturb(zgr_ctx* ctx, uint64_t step, float c);
 /* One loss evaluation at the current parameters (synchronises the stream). */
 zgr_status zgr_loss(zgr_ctx* ctx, const zgr_batch* batch, double* loss_out /* HOST */);
 
+/* zgr_loss of the least-squares model for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no context, no workspace;
+ * the predictions X W^T and the per-example losses live in a static device array of the library (1 MiB + 16 KiB
+ * per GPU, held until the process ends).  W [n_out, n_in], X [batch, n_in], Y [batch, n_out]: DEVICE fp32, row-major;
+ * loss_out: DEVICE, one double, = ||X W^T - Y||_F^2 / (2 batch) exactly as zgr_loss computes it (same kernels, same
+ * order).  Limits: batch <= 4096 and batch * n_out <= 262144; larger sizes return ZGR_ERR_WORKSPACE and launch
+ * nothing.  Asynchronous on hip_stream: no synchronisation, no copy to the host, no allocation of any kind.  All
+ * calls on one GPU share the one array: calls that overlap on a GPU (different streams or threads) race; calls
+ * on one stream are ordered.  Nothing in the array has to be cleared between calls: each call writes every word
+ * it later reads.                                                                                             */
+zgr_status zgr_lsq_loss_static(const float* W, const float* X, const float* Y, int32_t batch, int32_t n_out, int32_t n_in,
+                               double* loss_out /* DEVICE */, void* hip_stream);
+
 void        zgr_destroy(zgr_ctx* ctx);
 const char* zgr_last_error(const zgr_ctx* ctx); /* ctx may be NULL: last error of a failed zgr_init */
 

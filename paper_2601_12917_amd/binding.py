@@ -63,6 +63,7 @@ SYMBOLS = {
     "zgr_apply_updates": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.c_float]),
     "zgr_perturb": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float]),
     "zgr_loss": (C.c_int, [C.c_void_p, C.POINTER(zgr_batch), C.POINTER(C.c_double)]),
+    "zgr_lsq_loss_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "zgr_destroy": (None, [C.c_void_p]),
     "zgr_last_error": (C.c_char_p, [C.c_void_p]),
     "zgr_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),

@@ -16,6 +16,14 @@
 
 using namespace zgr;
 
+// Scratch of zgr_lsq_loss_static: the predictions X W^T (fp32, up to kStaticPredFloats of them) followed by the
+// per-example losses (up to kStaticMaxBatch).  One copy per device, held until the process ends.  Host code never
+// uses this name as an address: it asks the runtime for the device address (scratch_of_current_device below).
+constexpr size_t kStaticPredFloats = (size_t)1 << 18;     // 1 MiB of predictions
+constexpr size_t kStaticMaxBatch   = 4096;
+constexpr size_t kStaticScratchBytes = (kStaticPredFloats + kStaticMaxBatch) * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 std::string g_init_error;   // message of the last failed zgr_init / context-free call
@@ -808,6 +816,47 @@ zgr_status zgr_loss(zgr_ctx* c, const zgr_batch* b, double* loss_out) {
   if (c->prof.on) prof_harvest(c);
   *loss_out = c->host_loss[0];
   return std::isfinite(*loss_out) ? ZGR_OK : fail(c, ZGR_ERR_NONFINITE, "loss is not finite");
+}
+
+namespace {
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t scratch_of_current_device(unsigned char** out) {
+  static std::mutex mu;
+  static unsigned char* ptr_of[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    unsigned char* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    ptr_of[dev] = ptr;
+  }
+  *out = ptr_of[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+zgr_status zgr_lsq_loss_static(const float* W, const float* X, const float* Y, int32_t batch, int32_t n_out, int32_t n_in,
+                               double* loss_out, void* hip_stream) {
+  if (!W || !X || !Y || !loss_out) return fail(nullptr, ZGR_ERR_NULL, "a pointer is NULL");
+  if (batch < 1 || n_out < 1 || n_in < 1) return fail(nullptr, ZGR_ERR_SHAPE, "batch, n_out and n_in must be positive");
+  if ((size_t)batch > kStaticMaxBatch || (size_t)batch * (size_t)n_out > kStaticPredFloats)
+    return fail(nullptr, ZGR_ERR_WORKSPACE, "batch = %d, n_out = %d exceed the static scratch (batch <= %zu, batch * n_out <= %zu): use zgr_loss with a workspace",
+                batch, n_out, kStaticMaxBatch, kStaticPredFloats);
+  unsigned char* ptr = nullptr;
+  HIP_TRY(nullptr, scratch_of_current_device(&ptr));
+  float* pred = reinterpret_cast<float*>(ptr);
+  float* row_loss = pred + kStaticPredFloats;
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  // the three launches of zgr_loss for this model; every word of scratch they read they have written in this call
+  HIP_TRY(nullptr, launch_gemm(0, X, W, nullptr, pred, EPI_F32, batch, n_out, n_in, s));
+  HIP_TRY(nullptr, launch_lsq_rows(pred, Y, row_loss, batch, n_out, s));
+  HIP_TRY(nullptr, launch_mean_f64(row_loss, batch, 1.0 / batch, loss_out, s));
+  return ZGR_OK;
 }
 
 zgr_status zgr_step(zgr_ctx* c, uint64_t step, const zgr_batch* b, zgr_result* out) {
