@@ -25,13 +25,12 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-# vector instructions per Philox call of 4 elements on the main path of the bf16 / 32-bit-mode kernels (counted in the ISA)
-VALU_PER_CALL = {"perturb_flat": 183, "perturb_tile": 195}
-ALU_PEAK_TINSTR = 256 * 4 * 32 * 2.4e9 / 1e12     # one simple wave64 instruction per 2 cycles and SIMD (157.3 TFLOP/s fp32 at 2 flops per FMA)
+ALU_PEAK_DATASHEET = 256 * 4 * 32 * 2.4e9 / 1e12   # T lane-instr/s: 32 lanes per SIMD at 2.4 GHz (157.3 TFLOP/s fp32 at 2 flops per FMA)
 
 
 def load_traffic():
-    """HBM bytes per launch from the committed counter runs, or {} when the kernels changed since."""
+    """Per-launch counter figures of the committed counter runs (HBM bytes fetched / written, vector instructions),
+    or {} when the kernel sources changed since they were taken."""
     try:
         from paper_2601_12917_amd.build import source_digest
         rec = json.load(open(TRAFFIC_FILE))
@@ -40,11 +39,30 @@ def load_traffic():
         return {}
 
 
+def kernel_valu(traffic, prefix):
+    """SQ_INSTS_VALU (wave instructions) per launch of the kernels whose name starts with prefix, or None."""
+    sel = [v for k, v in traffic.items() if k.startswith(prefix) and "valu_insts" in v]
+    n = sum(v["launches"] for v in sel)
+    return sum(v["valu_insts"] * v["launches"] for v in sel) / n if n else None
+
+
+def measured_ceilings(torch, B, dtype_code):
+    """Live on this machine: wave64 issue rate of a simple vector instruction (v_fma_f32, 8 waves per SIMD) and the
+    bare in-place read-modify-write stream over 1 GiB of the storage type."""
+    from paper_2601_12917_amd import ceilings as Cl
+    lib = B.lib()
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    cpi, ghz, rate = Cl.issue_rate(lib, B, torch, 0, 1, 8, n_cu=n_cu)
+    gbs, _ = Cl.stream_rate(lib, B, torch, 1 << 30, dtype_code, 0, n_cu * 8)
+    return {"simple_issue_T_lane_instr_per_s": rate * 64 / 1e12, "simple_issue_cycles_per_instruction": cpi, "shader_ghz": ghz, "rmw_stream_GBs": gbs}
+
+
 def forward_gemm_flops(cfg):
     """Algorithmic FLOPs of the GEMM launches of one forward pass (linear layers + vocabulary projection)."""
     M, d, ff = cfg.batch * cfg.seq, cfg.d_model, cfg.d_ff
     per_layer = 2.0 * M * (4 * d * d + 2 * d * ff)
-    return cfg.n_layer * per_layer + 2.0 * M * d * cfg.vocab
+    head = 2.0 * M * d * cfg.vocab if cfg.arch == 1 else 0.0      # the classifier's head is a reduction kernel, not a GEMM launch
+    return cfg.n_layer * per_layer + head
 
 
 def kernel_traffic(traffic, prefix):
@@ -93,21 +111,27 @@ def cpu_baseline(cfg, specs, budget_note=True):
     for n in [f"l{i}.ln1_g" for i in range(nl)] + [f"l{i}.ln2_g" for i in range(nl)] + ["lnf_g"]:
         Pd[n] = Pd[n] + 1.0
     tok = rng.integers(0, V, size=(nb, T))
+    lm = cfg.arch == I.ARCH_DECODER_LM
+    lengths = None if lm else rng.integers(32, T + 1, size=(nb,))
     t0 = time.perf_counter()
     x = Pd["tok_emb"][tok] + Pd["pos_emb"][:T][None]
     for i in range(nl):
-        x = F.block(x, Pd, i, cfg.n_head, True, None, cfg.ln_eps)
+        x = F.block(x, Pd, i, cfg.n_head, lm, lengths, cfg.ln_eps)
     t_layers = time.perf_counter() - t0
     t0 = time.perf_counter()
     h = F.layer_norm(x, Pd["lnf_g"], Pd["lnf_b"], cfg.ln_eps)
-    logp = F.log_softmax(h[:, :-1] @ Pd["tok_emb"].T)
-    float(-np.take_along_axis(logp, tok[:, 1:, None], axis=-1).mean())
+    if lm:
+        logp = F.log_softmax(h[:, :-1] @ Pd["tok_emb"].T)
+        float(-np.take_along_axis(logp, tok[:, 1:, None], axis=-1).mean())
+    else:
+        logp = F.log_softmax(h[:, 0] @ Pd["cls_w"].T + Pd["cls_b"].reshape(-1))
+        float(-logp[:, 0].mean())
     t_head = time.perf_counter() - t0
     fwd = (cfg.batch / nb) * (cfg.n_layer / nl * t_layers + t_head)
     step_s = 4.0 * t_pass * total_params / sampled + 2.0 * fwd
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
             "sample": (f"one perturbation pass over the {len(layer0)} guided matrices of one block ({sampled} parameters, {t_pass:.2f} s) scaled to "
-                       f"{total_params} parameters x 4 passes; {nl} blocks ({t_layers:.2f} s) and the vocabulary projection + loss ({t_head:.2f} s) on "
+                       f"{total_params} parameters x 4 passes; {nl} blocks ({t_layers:.2f} s) and the final projection + loss ({t_head:.2f} s) on "
                        f"{nb} sequences of {T} tokens, scaled to {cfg.n_layer} blocks x {cfg.batch} sequences x 2 forwards")}
 
 
@@ -193,7 +217,7 @@ def main():
     import torch
     import zgr_inputs as I
     from paper_2601_12917_amd import binding as B
-    from tests.util import inputs_of, make_batch_arrays, make_session, session_batch
+    from paper_2601_12917_amd.workloads import inputs_of, make_batch_arrays, make_session, session_batch
     if args.gemm_shapes:
         return gemm_shapes(args, torch, I, B)
     if not os.path.exists(B.LIB_PATH):
@@ -276,7 +300,7 @@ def main():
         "metric": "ZGR steps/sec", "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {I.CONFIGS[args.config].n_layer}-layer d={cfg.d_model} decoder, batch {cfg.batch} x seq {cfg.seq}, "
+        "config": {"workload": f"{cfg.name}: {I.CONFIGS[args.config].n_layer}-layer d={cfg.d_model} {'decoder' if cfg.arch == I.ARCH_DECODER_LM else 'encoder classifier'}, batch {cfg.batch} x seq {cfg.seq}, "
                                f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns{', 4-bit codes' if args.q4_basis else ''}{', streamed from host memory per layer' if args.stream_bases else ''}), gauss_bits={args.gauss_bits}"
                    if cfg.arch != I.ARCH_LINEAR_LSQ else f"{cfg.name}: linear least squares {cfg.lsq_out}x{cfg.lsq_in}",
                    "params": int(guided_elems + flat_elems), "tokens_per_step": int(cfg.batch * max(cfg.seq, 1))},
@@ -303,17 +327,22 @@ def main():
             gbs = 2.0 * flat_elems * es / (k1["ms_avg"] * 1e-3) / 1e9
             out["roofline_perturb_flat"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                                             "traffic": kernel_traffic(traffic, "perturb_flat"), "kernel": "perturb_flat_kernel"}
-        # What really bounds the perturbation passes: vector-ALU issue.  One Philox call (4 Gaussians, 32-bit mode) costs
-        # VALU_PER_CALL wave64 vector instructions (static count of the kernels' main paths).  The peak is the vector unit's
-        # rate for simple instructions, 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-instructions/s; the mix also holds
-        # multiply-adds (4-5 cycles), conversions, v_rsq (8) and, in the tile kernel, fp32 MFMAs, so the fraction stays near 0.5.
-        if args.gauss_bits == 32 and cfg.dtype == "bf16":
-            for name, elems, key in (("perturb_tile", guided_elems, "roofline_perturb"), ("perturb_flat", flat_elems, "roofline_perturb_flat")):
-                if name in kern and key in out and elems:
-                    lane_instr = VALU_PER_CALL[name] * elems / 4.0
-                    ach = lane_instr / (kern[name]["ms_avg"] * 1e-3) / 1e12
-                    out[key]["alu"] = {"bound": "alu", "achieved": ach, "peak": ALU_PEAK_TINSTR, "unit": "T lane-instr/s", "frac": ach / ALU_PEAK_TINSTR,
-                                       "valu_instructions_per_philox_call": VALU_PER_CALL[name]}
+        # What really bounds the perturbation passes: vector-ALU issue.  Achieved = vector instructions executed (the
+        # SQ_INSTS_VALU counter of the committed counter run, valid while the kernel sources are unchanged) over the
+        # measured launch time; peak = the issue rate of a simple wave64 instruction measured on this machine just now
+        # (the data-sheet figure, 32 lanes per SIMD at 2.4 GHz, beside it).  The mix also holds half-rate multiplies and
+        # conversions and quarter-rate transcendentals, so 1.0 is not reachable; profiles/mi355x_ceilings.md has the rates.
+        ceil = measured_ceilings(torch, B, 0 if cfg.dtype == "f32" else 1)
+        out["ceilings"] = ceil
+        for name, elems, key in (("perturb_tile", guided_elems, "roofline_perturb"), ("perturb_flat", flat_elems, "roofline_perturb_flat")):
+            if name in kern and key in out and elems:
+                out[key]["frac_of_rmw_stream"] = out[key]["achieved"] / ceil["rmw_stream_GBs"]
+                valu = kernel_valu(traffic, name)
+                if valu:
+                    ach = valu * 64 / (kern[name]["ms_avg"] * 1e-3) / 1e12
+                    out[key]["alu"] = {"bound": "alu", "achieved": ach, "peak": ceil["simple_issue_T_lane_instr_per_s"], "unit": "T lane-instr/s",
+                                       "frac": ach / ceil["simple_issue_T_lane_instr_per_s"], "peak_datasheet": ALU_PEAK_DATASHEET,
+                                       "valu_instructions_per_philox_call": valu * 64 / (elems / (4.0 if args.gauss_bits == 32 else 8.0))}
         if "gemm" in kern and cfg.arch != I.ARCH_LINEAR_LSQ:
             gm = kern["gemm"]
             flops_per_launch = 2.0 * profiled_steps * forward_gemm_flops(cfg) / gm["launches"]
@@ -376,7 +405,7 @@ def main():
         fs.close()
         del fs, fb
     del values
-    if not args.no_cpu_baseline and cfg.arch == I.ARCH_DECODER_LM:
+    if not args.no_cpu_baseline and cfg.arch != I.ARCH_LINEAR_LSQ:
         out["cpu_baseline"] = cpu_baseline(cfg, specs)
     print(json.dumps(out))
 

@@ -325,6 +325,24 @@ zgr_status zgr_debug_gemm(int32_t dtype, const void* A, const void* W, const voi
  * reference that hardware traffic counters are calibrated against.                                      */
 zgr_status zgr_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* ---- machine ceilings the perturbation pass is rated against (measurement only) ---- */
+/* The bare in-place stream buf[i] <- rnd(buf[i] + c) over `bytes` bytes of dtype data in 16-byte vectors, with a
+ * grid of `blocks` blocks of 256 threads striding over the buffer: mode 0 read-modify-write, 1 read only, 2 write
+ * only.  sink16: 16 bytes of DEVICE memory (written only if the data xor to one particular value).            */
+zgr_status zgr_debug_rmw(void* buf, size_t bytes, int32_t dtype, float c, int32_t mode, int32_t blocks, void* sink16, void* hip_stream);
+/* Issue rate of one kind of vector instruction: `blocks` blocks of 4 waves each run iters x 64 instructions of
+ * kind op (0 v_fma_f32, 1 v_xor_b32, 2 v_bitop3_b32, 3 v_mad_u64_u32, 4 v_mul_hi_u32, 5 v_mul_lo_u32, 6 v_cvt_f32_u32,
+ * 7 v_rsq_f32, 8 v_add_u32, 9 v_lshrrev_b32, 10 v_cndmask_b32, 11 v_mul_f32, 12 v_add_f32, 13 v_log_f32,
+ * 14 v_cvt_pk_bf16_f32, 15 v_sqrt_f32, 16 v_mov_b32) in ilp (1, 2 or 4) independent dependent-chains.  out: DEVICE,
+ * 4 uint64 per wave (4 * blocks waves): shader cycles of the wave's own run, the 100 MHz real-time counter at its
+ * start and at its end, a checksum.  The waves of a SIMD do not advance in step: rates come from the span over all
+ * waves (first start to last end).                                                                            */
+zgr_status zgr_debug_issue_rate(int32_t op, int32_t ilp, int32_t blocks, int32_t iters, uint64_t* out, void* hip_stream);
+/* The same for the Gaussian generator's own parts, with nothing else in the kernel: part 0 one Philox4x32-10 call,
+ * 1 two radii sqrt(-2 ln u), 2 two (cos, sin) pairs, 3 two Box-Muller pairs, 4 the whole generator of four
+ * Gaussians (one Philox call + two pairs), 5 the two table look-ups alone; iters calls per lane.  out as above. */
+zgr_status zgr_debug_generator_rate(int32_t part, int32_t blocks, int32_t iters, uint64_t* out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

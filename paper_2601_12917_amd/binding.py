@@ -78,6 +78,9 @@ SYMBOLS = {
     "zgr_debug_radius_table": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p]),
     "zgr_debug_cossin_table": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "zgr_debug_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "zgr_debug_rmw": (C.c_int, [C.c_void_p, C.c_size_t, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "zgr_debug_issue_rate": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "zgr_debug_generator_rate": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "zgr_debug_gemm": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
 }
 

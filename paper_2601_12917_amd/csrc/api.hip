@@ -126,9 +126,9 @@ void mix_coefficients(const zgr_config& cfg, const zgr_tensor& t, bool guided, f
 
 int group_size(int bits) { return bits == 32 ? 4 : 8; }
 
-size_t flat_items_of(int64_t numel, int P) {
-  const int64_t groups = (numel + P - 1) / P;
-  return (size_t)((groups + kFlatGroupsPerItem - 1) / kFlatGroupsPerItem);
+size_t flat_items_of(int64_t numel, int P, int dtype) {
+  const int64_t groups = (numel + P - 1) / P, per = flat_groups_per_item((int)elem_size(dtype), P);
+  return (size_t)((groups + per - 1) / per);
 }
 // Row tiles of 128 rows: fine enough that a launch over one layer's matrices (a stage of the layer pipeline) still
 // gives every block several tiles; the slice of R is shared by the consecutive row tiles of a strip, so small tiles cost nothing.
@@ -140,9 +140,9 @@ size_t tile_items_of(int64_t rows, int64_t cols, int P) {
 
 void append_items(const zgr_tensor& t, int index, bool guided, int P, std::vector<WorkItem>& flat, std::vector<WorkItem>& tiles) {
   if (!guided) {
-    const int64_t groups = (t.rows * t.cols + P - 1) / P;
-    for (int64_t g0 = 0; g0 < groups; g0 += kFlatGroupsPerItem)
-      flat.push_back({index, (int32_t)std::min<int64_t>(kFlatGroupsPerItem, groups - g0), g0});
+    const int64_t groups = (t.rows * t.cols + P - 1) / P, per = flat_groups_per_item((int)elem_size(t.dtype), P);
+    for (int64_t g0 = 0; g0 < groups; g0 += per)
+      flat.push_back({index, (int32_t)std::min<int64_t>(per, groups - g0), g0});
   } else {
     const int64_t tr = tile_rows_of(t.rows), tc = 32 * P;
     // column strips outermost: the kernels keep a strip's slice of R in LDS across its consecutive row tiles
@@ -313,7 +313,7 @@ Carve carve(const zgr_model& m, const zgr_tensor* t, int n_t, int max_batch, int
   size_t nf = 0, nt = 0, nd = 0;
   int dtype = n_t > 0 ? t[0].dtype : 0;
   for (int i = 0; i < n_t; ++i) {
-    const size_t f = flat_items_of(t[i].rows * t[i].cols, P);
+    const size_t f = flat_items_of(t[i].rows * t[i].cols, P, t[i].dtype);
     const size_t tl = (t[i].cols % P == 0) ? tile_items_of(t[i].rows, t[i].cols, P) : 0;
     nf += f; nt += tl;
     nd = std::max(nd, std::max(f, tl));
@@ -1052,6 +1052,29 @@ zgr_status zgr_debug_gemm(int32_t dtype, const void* A, const void* W, const voi
   if ((dtype != ZGR_F32 && dtype != ZGR_BF16) || epilogue < 0 || epilogue > 3) return fail(nullptr, ZGR_ERR_CONFIG, "bad dtype or epilogue");
   if (M < 1 || N < 1 || K < 1 || (dtype == ZGR_BF16 && K % 64)) return fail(nullptr, ZGR_ERR_SHAPE, "bad GEMM shape");
   HIP_TRY(nullptr, launch_gemm(dtype, A, W, bias, out, epilogue, M, N, K, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_rmw(void* buf, size_t bytes, int32_t dtype, float c, int32_t mode, int32_t blocks, void* sink16, void* hip_stream) {
+  if (!buf || !sink16) return fail(nullptr, ZGR_ERR_NULL, "NULL argument");
+  if (bytes % 16 || ((uintptr_t)buf & 15) || ((uintptr_t)sink16 & 15)) return fail(nullptr, ZGR_ERR_SHAPE, "size and pointers must be multiples of 16 bytes");
+  if ((dtype != ZGR_F32 && dtype != ZGR_BF16) || mode < 0 || mode > 2 || blocks < 1 || blocks > (1 << 24)) return fail(nullptr, ZGR_ERR_CONFIG, "bad dtype, mode or grid");
+  HIP_TRY(nullptr, launch_debug_rmw(buf, bytes, dtype, c, mode, blocks, sink16, reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_issue_rate(int32_t op, int32_t ilp, int32_t blocks, int32_t iters, uint64_t* out, void* hip_stream) {
+  if (!out) return fail(nullptr, ZGR_ERR_NULL, "out is NULL");
+  if (op < 0 || op > 16 || (ilp != 1 && ilp != 2 && ilp != 4) || blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20))
+    return fail(nullptr, ZGR_ERR_CONFIG, "bad instruction kind, chain count, grid or iteration count");
+  HIP_TRY(nullptr, launch_debug_issue(op, ilp, blocks, iters, reinterpret_cast<unsigned long long*>(out), reinterpret_cast<hipStream_t>(hip_stream)));
+  return ZGR_OK;
+}
+
+zgr_status zgr_debug_generator_rate(int32_t part, int32_t blocks, int32_t iters, uint64_t* out, void* hip_stream) {
+  if (!out) return fail(nullptr, ZGR_ERR_NULL, "out is NULL");
+  if (part < 0 || part > 5 || blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20)) return fail(nullptr, ZGR_ERR_CONFIG, "bad part, grid or iteration count");
+  HIP_TRY(nullptr, launch_debug_generator(part, blocks, iters, reinterpret_cast<unsigned long long*>(out), reinterpret_cast<hipStream_t>(hip_stream)));
   return ZGR_OK;
 }
 

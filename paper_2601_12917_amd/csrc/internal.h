@@ -30,7 +30,10 @@ struct WorkItem {
   int64_t first;
 };
 
-constexpr int kFlatGroupsPerItem = 2048;   // Philox calls per flat work item (8 per thread)
+// Philox calls of a flat work item: 256 threads x as many vectors per thread as make 64 bytes per lane (what a lane
+// keeps in flight while it works on the previous item): 8 for bf16 with 4 elements per call, down to 2 for fp32 with 8.
+constexpr int flat_slots(int elem_bytes, int P) { return 64 / (elem_bytes * P) < 1 ? 1 : 64 / (elem_bytes * P); }
+constexpr int flat_groups_per_item(int elem_bytes, int P) { return 256 * flat_slots(elem_bytes, P); }
 constexpr int kTileRowsPerIter   = 128;    // rows one block covers per iteration (4 waves x 32)
 constexpr int kMaxK              = 64;
 constexpr int kMfmaMinK          = 16;     // from this rank on the U R contraction of a tile runs on the matrix cores
@@ -86,5 +89,9 @@ hipError_t launch_stage_only(const PerturbArgs& a, hipStream_t s);
 hipError_t launch_basis_minmax(const float* U, int64_t rows, int k, int ldu, float* minmax, hipStream_t s);
 hipError_t launch_basis_quantize(const float* U, int64_t rows, int k, int ldu, float lambda, float delta, uint8_t* Uq, int ldq, hipStream_t s);
 hipError_t launch_debug_cossin_table(int bits, float* c, float* sn, hipStream_t s);
+// machine ceilings (ceilings.hip): bare in-place stream, vector-instruction issue rate
+hipError_t launch_debug_rmw(void* p, size_t bytes, int dtype, float c, int mode, int blocks, void* sink, hipStream_t s);
+hipError_t launch_debug_issue(int op, int ilp, int blocks, int iters, unsigned long long* out, hipStream_t s);
+hipError_t launch_debug_generator(int part, int blocks, int iters, unsigned long long* out, hipStream_t s);
 
 }  // namespace zgr

@@ -69,6 +69,35 @@ template <typename V> __device__ __forceinline__ void store_global(void* p, cons
   *reinterpret_cast<GR*>(reinterpret_cast<uintptr_t>(p)) = r;
 }
 
+__device__ __forceinline__ float load_global_elem(const float* p) { return load_global<float>(p); }
+__device__ __forceinline__ bf16_t load_global_elem(const bf16_t* p) {
+  typedef const uint16_t __attribute__((address_space(1))) GH;
+  bf16_t r; r.bits = *reinterpret_cast<GH*>(reinterpret_cast<uintptr_t>(p)); return r;
+}
+__device__ __forceinline__ void store_global_elem(float* p, float v) {
+  typedef float __attribute__((address_space(1))) GF;
+  *reinterpret_cast<GF*>(reinterpret_cast<uintptr_t>(p)) = v;
+}
+__device__ __forceinline__ void store_global_elem(bf16_t* p, bf16_t v) {
+  typedef uint16_t __attribute__((address_space(1))) GH;
+  *reinterpret_cast<GH*>(reinterpret_cast<uintptr_t>(p)) = v.bits;
+}
+
+// A descriptor or work-list entry read through the constant address space: these tables are never written by a
+// kernel, and only a load the compiler knows to be invariant may use the scalar unit however many stores to theta
+// surround it (as a vector load it would have to be waited for behind the stores issued just before it).
+template <typename S> __device__ __forceinline__ S load_const(const S* p) {
+  static_assert(sizeof(S) % 4 == 0, "whole words");
+  typedef const uint32_t __attribute__((address_space(4))) CW;
+  CW* w = reinterpret_cast<CW*>(reinterpret_cast<uintptr_t>(p));
+  uint32_t buf[sizeof(S) / 4];
+#pragma unroll
+  for (size_t i = 0; i < sizeof(S) / 4; ++i) buf[i] = w[i];
+  S s;
+  __builtin_memcpy(&s, buf, sizeof(S));
+  return s;
+}
+
 template <int P> __device__ __forceinline__ void gaussP(const u32x4 w, const RadiusEntry* tab, float* g);
 template <> __device__ __forceinline__ void gaussP<4>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss4(w, tab, g); }
 template <> __device__ __forceinline__ void gaussP<8>(const u32x4 w, const RadiusEntry* tab, float* g) { gauss8(w, tab, g); }
@@ -127,39 +156,114 @@ __device__ __forceinline__ void draw(uint64_t q, uint32_t id_stream, const Pertu
 // with scalar loads.  Fetched through the struct they become vector loads behind an s_waitcnt vmcnt(0), which
 // drains every outstanding load and store of the wave once per work item.
 // ------------------------------------------------------------------ flat
-template <typename T, int P, bool WRITE_Z, bool BATCH>
-__global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
-                                                           float c, const RadiusEntry* __restrict__ gtab, float* __restrict__ zout) {
+// Materialiser of Z for the isotropic tensors (test boundary only): one thread per Philox call.
+template <typename T, int P>
+__global__ void __launch_bounds__(256) fill_flat_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
+                                                        const RadiusEntry* __restrict__ gtab, float* __restrict__ zout) {
   __shared__ RadiusEntry tab[kRadiusTabEntries];
+  load_radius_table(tab, gtab);
+  __syncthreads();
+  for (int w = blockIdx.x; w < a.n_flat; w += gridDim.x) {
+    const WorkItem it = items[w];
+    const TensorDesc d = descs[it.tensor];
+    const int64_t n = d.rows * d.cols;
+    for (int g = threadIdx.x; g < it.count; g += 256) {
+      const int64_t q = it.first + g;
+      float G[P];
+      draw<P, false>((uint64_t)q, d.id, a, tab, G);
+      for (int j = 0; j < P; ++j) if (q * P + j < n) zout[q * P + j] = G[j];
+    }
+  }
+}
+
+// The registers of v as inputs of an empty statement: whatever they are waiting for (a load issued long ago) is
+// waited for HERE.  The compiler places the wait for an outstanding load in front of the first use of its
+// registers, and that wait also covers every store issued before it; anchoring it in front of a store, at a point
+// where the load is a whole work item old, keeps the write it would otherwise have to sit out behind it.
+template <typename V> __device__ __forceinline__ void wait_here_for(const V& v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef uint32_t R __attribute__((ext_vector_type(sizeof(V) / 4 > 4 ? 4 : sizeof(V) / 4)));
+  R r[sizeof(V) / sizeof(R)];
+  __builtin_memcpy(r, &v, sizeof(V));
+#pragma unroll
+  for (size_t i = 0; i < sizeof(V) / sizeof(R); ++i) asm volatile("" ::"v"(r[i]));
+#endif
+}
+
+// In-place pass over the isotropic tensors.  A work item is flat_groups_per_item Philox calls of one tensor; a
+// thread owns the calls tid, tid + 256, ... of it (flat_slots of them, 64 bytes per lane).  The parameters of the NEXT item of the
+// block are requested before the generator runs for the current one, so kFlatSlots vectors per lane are in
+// flight under a whole item's arithmetic: the pass needs about 20 KB of reads in flight per compute unit to
+// keep HBM busy, and one 8-byte request per lane at a time, waited for after one call, supplies less than that.
+template <typename T, int P, bool BATCH>
+__global__ void __launch_bounds__(256) perturb_flat_kernel(PerturbArgs a, const TensorDesc* __restrict__ descs, const WorkItem* __restrict__ items,
+                                                           float c, const RadiusEntry* __restrict__ gtab) {
+  __shared__ RadiusEntry tab[kRadiusTabEntries];
+  constexpr int kFlatSlots = flat_slots((int)sizeof(T), P);
   const int nblk = (int)gridDim.x - a.pull_blocks;               // computing blocks
   if ((int)blockIdx.x >= nblk) { pull_next_stage(a, (int)blockIdx.x - nblk, a.pull_blocks); return; }
   load_radius_table(tab, gtab);
   __syncthreads();
+  const int tid = threadIdx.x;
+  // Requests the vectors of item w (the last item again once the list is exhausted).  A slot past the end of the
+  // item or of the tensor re-reads the tensor's last whole vector, and a tensor shorter than one vector reads the
+  // descriptor table instead: always in bounds, never used, and so the requests carry no condition at all (a
+  // conditional request would make the compiler merge old and new registers behind it, with a wait).
+  auto request = [&](int w, Vec<T, P>* buf) {
+    const WorkItem it = load_const(items + (w < a.n_flat ? w : a.n_flat - 1));
+    const TensorDesc d = load_const(descs + it.tensor);
+    const int64_t n = d.rows * d.cols;
+    const int64_t last = n >= P ? (n - P) / P * P : 0;
+    const T* th = n >= P ? reinterpret_cast<const T*>(d.theta) : reinterpret_cast<const T*>(descs);
+#pragma unroll
+    for (int j = 0; j < kFlatSlots; ++j) {
+      int64_t e0 = (it.first + tid + 256 * j) * P;
+      e0 = e0 < last ? e0 : last;
+      buf[j] = load_global<Vec<T, P>>(th + e0);
+    }
+  };
+  Vec<T, P> cur[kFlatSlots], nxt[kFlatSlots];
+  request(blockIdx.x, cur);
+#pragma unroll
+  for (int j = 0; j < kFlatSlots; ++j) wait_here_for(cur[j]);      // nothing outstanding on entry to the loop
   for (int w = blockIdx.x; w < a.n_flat; w += nblk) {
-    const WorkItem it = items[w];
-    const TensorDesc d = descs[it.tensor];
+    request(w + nblk, nxt);
+    const WorkItem it = load_const(items + w);
+    const TensorDesc d = load_const(descs + it.tensor);
     const int64_t n = d.rows * d.cols;
     T* __restrict__ th = reinterpret_cast<T*>(d.theta);
-    for (int g = threadIdx.x; g < it.count; g += 256) {
-      const int64_t q = it.first + g;
-      const int64_t e0 = q * P;
-      // the load goes out ahead of the generator's arithmetic, which then covers its latency
-      const bool whole = !WRITE_Z && e0 + P <= n;
-      Vec<T, P> x;
-      if (whole) x = load_global<Vec<T, P>>(th + e0);
-      float G[P];
-      draw<P, BATCH>((uint64_t)q, d.id, a, tab, G);
-      if (WRITE_Z) {
-        for (int j = 0; j < P; ++j) if (e0 + j < n) zout[e0 + j] = G[j];
-      } else if (whole) {
 #pragma unroll
-        for (int j = 0; j < P; ++j) from_f32(__builtin_fmaf(c, G[j], to_f32(x.v[j])), x.v[j]);
-        store_global(th + e0, x);
-      } else {
-        for (int j = 0; j < P; ++j)
-          if (e0 + j < n) { T x = th[e0 + j]; from_f32(__builtin_fmaf(c, G[j], to_f32(x)), x); th[e0 + j] = x; }
+    for (int j = 0; j < kFlatSlots; ++j) {
+      const int g = tid + 256 * j;
+      if (j == kFlatSlots - 1) {
+        // the next item's vectors were requested a whole item ago and the youngest store is one call old: nothing to sit out
+#pragma unroll
+        for (int i = 0; i < kFlatSlots; ++i) wait_here_for(nxt[i]);
+      }
+      if (g < it.count) {
+        const int64_t q = it.first + g, e0 = q * P;
+        float G[P];
+        draw<P, BATCH>((uint64_t)q, d.id, a, tab, G);
+        if (e0 + P <= n) {
+          Vec<T, P> x = cur[j];
+          float f[P];
+#pragma unroll
+          for (int i = 0; i < P; ++i) f[i] = __builtin_fmaf(c, G[i], to_f32(x.v[i]));
+          round_into<P>(x, f);
+          store_global(th + e0, x);
+        } else {
+          // ragged end of a tensor: element by element
+          for (int i = 0; i < P; ++i)
+            if (e0 + i < n) {
+              T x = load_global_elem(th + e0 + i);
+              from_f32(__builtin_fmaf(c, G[i], to_f32(x)), x);
+              store_global_elem(th + e0 + i, x);
+            }
+        }
       }
     }
+#pragma unroll
+    for (int j = 0; j < kFlatSlots; ++j) cur[j] = nxt[j];
   }
 }
 
@@ -610,12 +714,17 @@ int split_grid(PerturbArgs& a, int items, int capacity) {
 template <typename T, int P>
 hipError_t launch_flat_t(const PerturbArgs& a_in, float c, float* zout, hipStream_t s, int n_cu, const RadiusEntry* tab) {
   PerturbArgs a = a_in;
-  auto kern = zout ? perturb_flat_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_flat_kernel<T, P, false, true> : perturb_flat_kernel<T, P, false, false>);
-  static int per[3] = {0, 0, 0};
-  int& nb = per[zout ? 1 : (a.n_q > 0 ? 2 : 0)];
+  if (zout) {
+    const int grid = a.n_flat < n_cu * 8 ? a.n_flat : n_cu * 8;
+    hipLaunchKernelGGL((fill_flat_kernel<T, P>), dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, tab, zout);
+    return hipGetLastError();
+  }
+  auto kern = a.n_q > 0 ? perturb_flat_kernel<T, P, true> : perturb_flat_kernel<T, P, false>;
+  static int per[2] = {0, 0};
+  int& nb = per[a.n_q > 0 ? 1 : 0];
   if (nb == 0) nb = resident_blocks_per_cu(kern, 0, 8);
   const int grid = split_grid(a, a.n_flat, n_cu * nb);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, c, tab, zout);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, c, tab);
   return hipGetLastError();
 }
 template <typename T, int P>

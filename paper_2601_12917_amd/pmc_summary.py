@@ -2,7 +2,10 @@
 traffic per launch of each kernel, scaled by what the same counters read for the plain copy kernel of
 known size that `bench.py --calibrate-copy` runs.  Writes the JSON that bench.py reads for `traffic`.
 
-    python -m paper_2601_12917_amd.pmc_summary FETCH_counter_collection.csv WRITE_counter_collection.csv COPY_BYTES out.json
+    python -m paper_2601_12917_amd.pmc_summary FETCH_counter_collection.csv WRITE_counter_collection.csv COPY_BYTES out.json [VALU_counter_collection.csv]
+
+The optional fifth argument is a run with SQ_INSTS_VALU among its counters: the vector instructions (wave64) per
+launch of each kernel go into the same JSON, from which bench.py derives the instructions per Philox call.
 """
 import collections
 import csv
@@ -33,6 +36,10 @@ def main(argv):
     for k in f:
         if k in w:
             kernels[k] = {"launches": f[k][1], "fetch_bytes": f[k][0] * 1024.0 * f_scale, "write_bytes": w[k][0] * 1024.0 * w_scale}
+    if len(argv) > 5:
+        for k, (val, _) in per_kernel(argv[5], "SQ_INSTS_VALU").items():
+            if k in kernels:
+                kernels[k]["valu_insts"] = val
     json.dump({"source_digest": source_digest(), "fetch_scale": f_scale, "write_scale": w_scale, "copy_bytes": copy_bytes,
                "kernels": kernels}, open(out, "w"), indent=1)
     for k, v in sorted(kernels.items(), key=lambda kv: -kv[1]["fetch_bytes"] * kv[1]["launches"]):
