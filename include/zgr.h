@@ -220,6 +220,27 @@ zgr_status zgr_dtc_omega(double data_bytes, double bandwidth_bytes_per_s, double
  * when a share omega travels and is held compressed.  HOST arithmetic.        */
 zgr_status zgr_dtc_memory_factor(int32_t n_layers, double omega, double theta, double* factor);
 
+/* ---- cloud block of Algorithm 1 ("perform BP on D_p; collect gradients to build basis V_r"; Sec. 3.2, "Guided
+ * Perturbation Sampling on Cloud") ---- */
+/* The basis U [rows, k] (row stride ldu >= k, DEVICE, orthonormal columns) of one weight matrix from n_snap stored
+ * gradient snapshots of it (snapshots: HOST array of n_snap DEVICE pointers, each fp32 [rows, cols] row-major): the
+ * k-dimensional subspace of R^rows that captures the most of them, i.e. the span of the k leading left singular
+ * vectors of [G_1 | ... | G_s] (the paper asks for "the orthonormal basis of the subspace of gradients" and does
+ * not say how a rank is chosen; this is the reading for a basis that acts on every column of the matrix).  Reached by
+ * n_iter sweeps of block subspace iteration Q <- orth(sum_t G_t G_t^T Q) from Q = orth(sum_t G_t omega), omega
+ * [cols, k] DEVICE fp32 being the caller's seeded standard-normal start; the subspace converges like
+ * (sigma_{k+1} / sigma_k)^(2 n_iter).  Only the subspace is defined: compare projectors U U^T.  A column the
+ * snapshots do not span (rank below k) comes out as zeros; *dependent_out (HOST, may be NULL; reading it
+ * synchronises the stream) counts them.  workspace: DEVICE, 256-byte aligned, zgr_cloud_basis_workspace bytes.   */
+size_t     zgr_cloud_basis_workspace(int64_t rows, int64_t cols, int32_t k);
+zgr_status zgr_cloud_basis(const float* const* snapshots, int32_t n_snap, int64_t rows, int64_t cols, int32_t k, const float* omega, int32_t n_iter,
+                           float* U, int32_t ldu, int32_t* dependent_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* The cloud's gradient for the least-squares model: G [n_out, n_in] = (X W^T - Y)^T X / batch, all DEVICE fp32 row-major;
+ * workspace: DEVICE, batch * n_out floats.  Asynchronous.  (The transformer models' backward pass is not part of this
+ * library: their snapshots come from the caller.)                                                                    */
+zgr_status zgr_cloud_lsq_gradient(const float* W, const float* X, const float* Y, int32_t batch, int32_t n_out, int32_t n_in, float* G,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Client block of Algorithm 1 for round/step `step` (< 2^32): perturb all
  * tensors in place by +eps Z, evaluate L+, by -2 eps Z, evaluate L-, restore by
  * +eps Z, Z regenerated from (seed, step) in each pass.  Fills *out.  On

@@ -58,6 +58,10 @@ SYMBOLS = {
                                      C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p]),
     "zgr_dtc_omega": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
     "zgr_dtc_memory_factor": (C.c_int, [C.c_int32, C.c_double, C.c_double, C.POINTER(C.c_double)]),
+    "zgr_cloud_basis_workspace": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int32]),
+    "zgr_cloud_basis": (C.c_int, [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                  C.POINTER(C.c_int32), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "zgr_cloud_lsq_gradient": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "zgr_step": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(zgr_batch), C.POINTER(zgr_result)]),
     "zgr_apply_update": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float, C.c_float]),
     "zgr_apply_updates": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.c_float]),

@@ -799,6 +799,59 @@ zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t l
   return ZGR_OK;
 }
 
+size_t zgr_cloud_basis_workspace(int64_t rows, int64_t cols, int32_t k) {
+  if (rows < 1 || cols < 1 || k < 1 || k > kMaxK) return 0;
+  return 2 * align_up((size_t)rows * k * 4) + align_up((size_t)cols * k * 4) + 256;
+}
+
+zgr_status zgr_cloud_basis(const float* const* snapshots, int32_t n_snap, int64_t rows, int64_t cols, int32_t k, const float* omega, int32_t n_iter,
+                           float* U, int32_t ldu, int32_t* dependent_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!snapshots || !omega || !U || !workspace) return fail(nullptr, ZGR_ERR_NULL, "a pointer is NULL");
+  if (n_snap < 1 || rows < 1 || cols < 1 || k < 1 || k > kMaxK || k > rows || ldu < k || n_iter < 0) return fail(nullptr, ZGR_ERR_SHAPE, "bad shape (1 <= k <= min(rows, 64), ldu >= k, n_iter >= 0)");
+  for (int t = 0; t < n_snap; ++t) if (!snapshots[t]) return fail(nullptr, ZGR_ERR_NULL, "snapshot %d is NULL", t);
+  if (workspace_bytes < zgr_cloud_basis_workspace(rows, cols, k) || ((uintptr_t)workspace & 255)) return fail(nullptr, ZGR_ERR_WORKSPACE, "workspace too small or not 256-byte aligned");
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  const size_t yb = align_up((size_t)rows * k * 4);
+  float* Q = reinterpret_cast<float*>(ws);               // the current orthonormal block
+  float* Y = reinterpret_cast<float*>(ws + yb);          // the block being built by a sweep
+  float* T = reinterpret_cast<float*>(ws + 2 * yb);      // G_t^T Q of one snapshot
+  int* dep = reinterpret_cast<int*>(ws + 2 * yb + align_up((size_t)cols * k * 4));
+  // Q = orth(sum_t G_t Omega)
+  for (int t = 0; t < n_snap; ++t) HIP_TRY(nullptr, launch_cloud_g_t(snapshots[t], rows, cols, omega, k, Q, t > 0, s));
+  HIP_TRY(nullptr, launch_cloud_orth(Q, rows, k, dep, s));
+  // sweeps Q <- orth(sum_t G_t (G_t^T Q))
+  for (int it = 0; it < n_iter; ++it) {
+    for (int t = 0; t < n_snap; ++t) {
+      HIP_TRY(nullptr, launch_cloud_gt_q(snapshots[t], rows, cols, cols, Q, k, k, T, k, 1.0f, 0, s));
+      HIP_TRY(nullptr, launch_cloud_g_t(snapshots[t], rows, cols, T, k, Y, t > 0, s));
+    }
+    float* tmp = Q; Q = Y; Y = tmp;
+    HIP_TRY(nullptr, launch_cloud_orth(Q, rows, k, dep, s));
+  }
+  HIP_TRY(nullptr, launch_cloud_copy_basis(Q, rows, k, U, ldu, s));
+  if (dependent_out) {
+    int h = 0;
+    HIP_TRY(nullptr, hipMemcpyAsync(&h, dep, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(nullptr, hipStreamSynchronize(s));
+    *dependent_out = h;
+  }
+  return ZGR_OK;
+}
+
+zgr_status zgr_cloud_lsq_gradient(const float* W, const float* X, const float* Y, int32_t batch, int32_t n_out, int32_t n_in, float* G,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!W || !X || !Y || !G || !workspace) return fail(nullptr, ZGR_ERR_NULL, "a pointer is NULL");
+  if (batch < 1 || n_out < 1 || n_in < 1) return fail(nullptr, ZGR_ERR_SHAPE, "batch, n_out and n_in must be positive");
+  if (workspace_bytes < (size_t)batch * n_out * 4) return fail(nullptr, ZGR_ERR_WORKSPACE, "workspace must hold batch * n_out floats");
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  float* R = reinterpret_cast<float*>(workspace);
+  HIP_TRY(nullptr, launch_gemm(0, X, W, nullptr, R, EPI_F32, batch, n_out, n_in, s));                     // X W^T
+  HIP_TRY(nullptr, launch_cloud_residual(R, Y, (int64_t)batch * n_out, s));                                // - Y
+  HIP_TRY(nullptr, launch_cloud_gt_q(R, batch, n_out, n_out, X, n_in, n_in, G, n_in, 1.0f / (float)batch, 0, s));   // R^T X / B
+  return ZGR_OK;
+}
+
 zgr_status zgr_perturb(zgr_ctx* c, uint64_t step, float coef) {
   if (!c) return ZGR_ERR_NULL;
   return perturb_pass(c, step, coef);

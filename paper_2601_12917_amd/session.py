@@ -274,3 +274,33 @@ def debug_cossin_table(bits, device="cuda:0"):
     B.check(lib.zgr_debug_cossin_table(bits, c.data_ptr(), s.data_ptr(), torch.cuda.current_stream().cuda_stream))
     torch.cuda.synchronize()
     return c.cpu().numpy(), s.cpu().numpy()
+
+
+# ---- cloud block of Algorithm 1 (context-free) ----------------------------------
+def cloud_basis(snapshots, k, omega, n_iter, ldu=None, device="cuda:0"):
+    """U [rows, ldu] and the number of dependent columns: zgr_cloud_basis on host arrays (marshalling only)."""
+    lib = B.lib()
+    snaps = [torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to(device) for g in snapshots]
+    rows, cols = snaps[0].shape
+    ldu = ldu or k
+    om = torch.from_numpy(np.ascontiguousarray(omega, dtype=np.float32)).to(device)
+    U = torch.zeros(rows, ldu, dtype=torch.float32, device=device)
+    nbytes = lib.zgr_cloud_basis_workspace(rows, cols, k)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    ptrs = (C.c_void_p * len(snaps))(*[t.data_ptr() for t in snaps])
+    dep = C.c_int32(-1)
+    B.check(lib.zgr_cloud_basis(ptrs, len(snaps), rows, cols, k, om.data_ptr(), n_iter, U.data_ptr(), ldu, C.byref(dep), ws.data_ptr(), nbytes,
+                                torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    return U.cpu().numpy(), dep.value
+
+
+def cloud_lsq_gradient(W, X, Y, device="cuda:0"):
+    lib = B.lib()
+    w, x, y = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device) for a in (W, X, Y))
+    G = torch.zeros_like(w)
+    ws = torch.empty(x.shape[0] * w.shape[0] * 4, dtype=torch.uint8, device=device)
+    B.check(lib.zgr_cloud_lsq_gradient(w.data_ptr(), x.data_ptr(), y.data_ptr(), x.shape[0], w.shape[0], w.shape[1], G.data_ptr(), ws.data_ptr(), ws.numel(),
+                                       torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    return G.cpu().numpy()

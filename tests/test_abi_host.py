@@ -131,3 +131,23 @@ def test_compression_share_matches_the_oracle(lib):
     with pytest.raises(B.ZgrError):
         B.dtc_memory_factor(0, 0.5, 0.125)
 
+
+
+def test_cloud_entry_points_validate_their_arguments_without_a_gpu():
+    import ctypes as C
+    from paper_2601_12917_amd import binding as B
+    lib = B.lib()
+    assert lib.zgr_cloud_basis_workspace(256, 512, 4) >= (2 * 256 * 4 + 512 * 4) * 4
+    assert lib.zgr_cloud_basis_workspace(256, 512, 65) == 0 and lib.zgr_cloud_basis_workspace(0, 512, 4) == 0
+    one = (C.c_void_p * 1)(0x1000)
+    dep = C.c_int32(0)
+    # NULL pieces, rank above the rows / above 64, row stride below the rank, workspace too small or misaligned
+    assert lib.zgr_cloud_basis(None, 1, 8, 8, 2, 0x1000, 1, 0x1000, 2, C.byref(dep), 0x1000, 1 << 20, None) == B.ZGR_ERR_NULL
+    assert lib.zgr_cloud_basis((C.c_void_p * 1)(None), 1, 8, 8, 2, 0x1000, 1, 0x1000, 2, C.byref(dep), 0x1000, 1 << 20, None) == B.ZGR_ERR_NULL
+    assert lib.zgr_cloud_basis(one, 1, 8, 8, 9, 0x1000, 1, 0x1000, 9, C.byref(dep), 0x1000, 1 << 20, None) == B.ZGR_ERR_SHAPE
+    assert lib.zgr_cloud_basis(one, 1, 100, 8, 65, 0x1000, 1, 0x1000, 65, C.byref(dep), 0x1000, 1 << 20, None) == B.ZGR_ERR_SHAPE
+    assert lib.zgr_cloud_basis(one, 1, 8, 8, 4, 0x1000, 1, 0x1000, 3, C.byref(dep), 0x1000, 1 << 20, None) == B.ZGR_ERR_SHAPE
+    assert lib.zgr_cloud_basis(one, 1, 8, 8, 4, 0x1000, 1, 0x1000, 4, C.byref(dep), 0x1000, 16, None) == B.ZGR_ERR_WORKSPACE
+    assert lib.zgr_cloud_basis(one, 1, 8, 8, 4, 0x1000, 1, 0x1000, 4, C.byref(dep), 0x1010, 1 << 20, None) == B.ZGR_ERR_WORKSPACE
+    assert lib.zgr_cloud_lsq_gradient(None, 0x1000, 0x1000, 1, 1, 1, 0x1000, 0x1000, 64, None) == B.ZGR_ERR_NULL
+    assert lib.zgr_cloud_lsq_gradient(0x1000, 0x1000, 0x1000, 4, 4, 4, 0x1000, 0x1000, 8, None) == B.ZGR_ERR_WORKSPACE
