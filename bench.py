@@ -47,14 +47,17 @@ def kernel_valu(traffic, prefix):
 
 
 def measured_ceilings(torch, B, dtype_code):
-    """Live on this machine: wave64 issue rate of a simple vector instruction (v_fma_f32, 8 waves per SIMD) and the
-    bare in-place read-modify-write stream over 1 GiB of the storage type."""
+    """Live on this machine: wave64 issue rate of a simple vector instruction (v_fma_f32, 8 waves per SIMD), the
+    bare in-place read-modify-write stream over 1 GiB of the storage type, and the matrix core alone (bf16 32x32x16
+    on register operands, 4 accumulators, one wave per SIMD) with the clock the chip holds under it."""
     from paper_2601_12917_amd import ceilings as Cl
     lib = B.lib()
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     cpi, ghz, rate = Cl.issue_rate(lib, B, torch, 0, 1, 8, n_cu=n_cu)
     gbs, _ = Cl.stream_rate(lib, B, torch, 1 << 30, dtype_code, 0, n_cu * 8)
-    return {"simple_issue_T_lane_instr_per_s": rate * 64 / 1e12, "simple_issue_cycles_per_instruction": cpi, "shader_ghz": ghz, "rmw_stream_GBs": gbs}
+    _, mghz, mrate = Cl.issue_rate(lib, B, torch, len(Cl.OPS) - 1, 4, 1, iters=4096, n_cu=n_cu)
+    return {"simple_issue_T_lane_instr_per_s": rate * 64 / 1e12, "simple_issue_cycles_per_instruction": cpi, "shader_ghz": ghz, "rmw_stream_GBs": gbs,
+            "mfma_bf16_alone_TFLOPs": mrate * Cl.MFMA_FLOPS / 1e12, "mfma_bf16_alone_ghz": mghz}
 
 
 def forward_gemm_flops(cfg):
@@ -350,6 +353,8 @@ def main():
             peak = MFMA_PEAK_TFLOPS[cfg.dtype]
             gemm_roof = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak, "traffic": kernel_traffic(traffic, "gemm_"),
                          "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel", "flops_per_launch": flops_per_launch}
+            if cfg.dtype == "bf16":
+                gemm_roof["frac_of_mfma_alone"] = tf / ceil["mfma_bf16_alone_TFLOPs"]
             out["roofline_gemm"] = gemm_roof
         # the dominant kernel of the step carries the headline roofline
         dom = max(kern, key=lambda n: kern[n]["ms_total"])

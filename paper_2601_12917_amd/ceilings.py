@@ -13,7 +13,8 @@ import sys
 import numpy as np
 
 OPS = ["v_fma_f32", "v_xor_b32", "v_bitop3_b32", "v_mad_u64_u32", "v_mul_hi_u32", "v_mul_lo_u32", "v_cvt_f32_u32", "v_rsq_f32",
-       "v_add_u32", "v_lshrrev_b32", "v_cndmask_b32", "v_mul_f32", "v_add_f32", "v_log_f32", "v_cvt_pk_bf16_f32", "v_sqrt_f32", "v_mov_b32"]
+       "v_add_u32", "v_lshrrev_b32", "v_cndmask_b32", "v_mul_f32", "v_add_f32", "v_log_f32", "v_cvt_pk_bf16_f32", "v_sqrt_f32", "v_mov_b32", "v_mfma_f32_32x32x16_bf16"]
+MFMA_FLOPS = 2.0 * 32 * 32 * 16
 
 
 def issue_rate(lib, B, torch, op, ilp, waves_per_simd, iters=512, n_cu=None):
@@ -97,13 +98,20 @@ def main():
                     print(f"| {dname} | {nbytes} | {mname} | {blocks} | {ms:.3f} | {gbs:.0f} |")
     print("\n## Vector-instruction issue rate (cycles per wave64 instruction and SIMD; shader cycle counter s_memtime, clock from the 100 MHz s_memrealtime)\n")
     print("| instruction | chains per wave | waves per SIMD | cycles / instruction | shader clock GHz | T wave-instr/s (chip) |\n|---|---:|---:|---:|---:|---:|")
-    for op, name in enumerate(OPS):
+    for op, name in enumerate(OPS[:-1]):
         for ilp, wps in ((1, 1), (4, 1), (1, 4), (4, 4), (1, 8), (4, 8)):
             if name not in ("v_fma_f32", "v_xor_b32", "v_mad_u64_u32") and (ilp, wps) not in ((1, 1), (4, 8), (1, 8)):
                 continue
             cpi, ghz, rate = issue_rate(lib, B, torch, op, ilp, wps, n_cu=n_cu)
             res["issue"].append({"op": name, "ilp": ilp, "waves_per_simd": wps, "cycles_per_instruction": cpi, "shader_ghz": ghz, "wave_instr_per_s": rate})
             print(f"| {name} | {ilp} | {wps} | {cpi:.2f} | {ghz:.2f} | {rate / 1e12:.3f} |")
+    print("\n## The matrix core alone (v_mfma_f32_32x32x16_bf16 on register operands of random bf16; dense peak quoted at 2.4 GHz: 2500 TFLOP/s)\n")
+    print("| accumulators per wave | waves per SIMD | cycles / instruction | shader clock GHz | TFLOP/s (chip) |\n|---:|---:|---:|---:|---:|")
+    res["mfma"] = []
+    for ilp, wps in ((1, 1), (4, 1), (2, 2), (4, 2)):
+        cpi, ghz, rate = issue_rate(lib, B, torch, len(OPS) - 1, ilp, wps, iters=4096, n_cu=n_cu)
+        res["mfma"].append({"ilp": ilp, "waves_per_simd": wps, "cycles_per_instruction": cpi, "shader_ghz": ghz, "tflops": rate * MFMA_FLOPS / 1e12})
+        print(f"| {ilp} | {wps} | {cpi:.2f} | {ghz:.2f} | {rate * MFMA_FLOPS / 1e12:.0f} |")
     print("\n## The Gaussian generator's parts alone (cycles per call and SIMD; a call is one lane's work for 4 Gaussians, 64 lanes per wave)\n")
     print("| part | waves per SIMD | cycles / call | shader clock GHz |\n|---|---:|---:|---:|")
     res["generator"] = []

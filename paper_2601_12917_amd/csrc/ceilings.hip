@@ -100,6 +100,53 @@ __global__ void __launch_bounds__(256) issue_kernel(int iters, unsigned long lon
 #endif
 }
 
+// The matrix core alone: every wave runs iters x 64 v_mfma_f32_32x32x16_bf16 (32768 flops each) on register
+// operands, in ILP independent accumulators, and nothing else.  The operands are pseudo-random bf16 in (-2, 2): what
+// the unit draws, and with it the clock the chip holds, depends on how many bits toggle.  out as for issue_kernel.
+typedef __bf16 cbf16x8 __attribute__((ext_vector_type(8)));
+typedef float cf32x16 __attribute__((ext_vector_type(16)));
+
+template <int ILP>
+__global__ void __launch_bounds__(256) mfma_kernel(int iters, unsigned long long* __restrict__ out) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  union { uint32_t u[4]; cbf16x8 v; } a[ILP], b[ILP];
+  cf32x16 acc[ILP];
+  uint32_t h = (blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int i = 0; i < ILP; ++i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // two bf16 per word: random sign and mantissa, exponent of 1.0 or 0.5
+      h = h * 1664525u + 1013904223u;  a[i].u[j] = (h & 0x80ff80ffu) | 0x3f003f00u;
+      h = h * 1664525u + 1013904223u;  b[i].u[j] = (h & 0x80ff80ffu) | 0x3f003f00u;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  }
+  __builtin_amdgcn_s_barrier();
+  const unsigned long long c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 64 / ILP; ++r)
+#pragma unroll
+      for (int i = 0; i < ILP; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[i].v, acc[i], 0, 0, 0);
+  }
+  const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  float f = 0.f;
+#pragma unroll
+  for (int i = 0; i < ILP; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) f += acc[i][j];
+  if ((threadIdx.x & 63) == 0) {
+    const size_t w = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    out[4 * w] = c1 - c0;
+    out[4 * w + 1] = r0;
+    out[4 * w + 2] = r1;
+    out[4 * w + 3] = __float_as_uint(f);
+  }
+#endif
+}
+
 // The generator's own parts at full occupancy of the vector unit and nothing else: part 0 one Philox4x32-10 call,
 // 1 two radii, 2 two (cos, sin) pairs, 3 two Box-Muller pairs (on cheap pseudo-random integers), 4 the whole
 // generator of four Gaussians (Philox call + two Box-Muller pairs), 5 its two table look-ups alone.
@@ -182,6 +229,13 @@ hipError_t launch_debug_generator(int part, int blocks, int iters, unsigned long
 }
 
 hipError_t launch_debug_issue(int op, int ilp, int blocks, int iters, unsigned long long* out, hipStream_t s) {
+  if (op == 17) {
+    if (ilp == 1) hipLaunchKernelGGL(mfma_kernel<1>, dim3(blocks), dim3(256), 0, s, iters, out);
+    else if (ilp == 2) hipLaunchKernelGGL(mfma_kernel<2>, dim3(blocks), dim3(256), 0, s, iters, out);
+    else if (ilp == 4) hipLaunchKernelGGL(mfma_kernel<4>, dim3(blocks), dim3(256), 0, s, iters, out);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
   switch (op) {
 #define ZGR_ISSUE_CASE(N) case N: return launch_issue_ilp<N>(ilp, blocks, iters, out, s);
     ZGR_ISSUE_CASE(0) ZGR_ISSUE_CASE(1) ZGR_ISSUE_CASE(2) ZGR_ISSUE_CASE(3) ZGR_ISSUE_CASE(4) ZGR_ISSUE_CASE(5)
