@@ -236,10 +236,23 @@ size_t     zgr_cloud_basis_workspace(int64_t rows, int64_t cols, int32_t k);
 zgr_status zgr_cloud_basis(const float* const* snapshots, int32_t n_snap, int64_t rows, int64_t cols, int32_t k, const float* omega, int32_t n_iter,
                            float* U, int32_t ldu, int32_t* dependent_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 /* The cloud's gradient for the least-squares model: G [n_out, n_in] = (X W^T - Y)^T X / batch, all DEVICE fp32 row-major;
- * workspace: DEVICE, batch * n_out floats.  Asynchronous.  (The transformer models' backward pass is not part of this
- * library: their snapshots come from the caller.)                                                                    */
+ * workspace: DEVICE, batch * n_out floats.  Asynchronous.                                                            */
 zgr_status zgr_cloud_lsq_gradient(const float* W, const float* X, const float* Y, int32_t batch, int32_t n_out, int32_t n_in, float* G,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+/* The cloud's backward pass over the context's model ("Perform BP on D_p with W^r; collect gradients", cloud block of
+ * Algorithm 1): *loss_out (HOST) = L(theta; batch) as zgr_loss defines it, and grads[i] (HOST array of n_grads = n_t
+ * DEVICE pointers, caller-owned, each rows_i * cols_i fp32 row-major, overwritten) = dL/dtheta_i for every tensor the
+ * context was created with, in fp32 whatever the storage type; theta itself is left untouched.  The forward half runs
+ * the client's own kernels (so a bf16 model's intermediate results are bf16-rounded exactly as in zgr_loss, except
+ * that GELU is evaluated from the fp32 pre-activation by its erf form) and keeps every layer's results in
+ * `workspace` (DEVICE, 256-byte aligned, zgr_cloud_backward_workspace(ctx, batch, seq) bytes: it grows with
+ * n_layer * batch * seq * (d_model + d_ff)); the backward half is deterministic (no atomics).  Runs on the context's
+ * stream and returns after it has finished.  seq <= 2048.  Errors: ZGR_ERR_NULL, ZGR_ERR_SHAPE (batch outside the
+ * context's limits, n_grads != n_t, seq too long), ZGR_ERR_WORKSPACE, ZGR_ERR_STATE (a context without a model),
+ * ZGR_ERR_NONFINITE (gradients are then undefined), ZGR_ERR_DEVICE.                                            */
+size_t     zgr_cloud_backward_workspace(const zgr_ctx* ctx, int32_t batch, int32_t seq);
+zgr_status zgr_cloud_backward(zgr_ctx* ctx, const zgr_batch* batch, float* const* grads, int32_t n_grads, double* loss_out,
+                              void* workspace, size_t workspace_bytes);
 
 /* Client block of Algorithm 1 for round/step `step` (< 2^32): perturb all
  * tensors in place by +eps Z, evaluate L+, by -2 eps Z, evaluate L-, restore by

@@ -61,6 +61,8 @@ SYMBOLS = {
     "zgr_cloud_basis_workspace": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int32]),
     "zgr_cloud_basis": (C.c_int, [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                   C.POINTER(C.c_int32), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "zgr_cloud_backward_workspace": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int32]),
+    "zgr_cloud_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.POINTER(C.c_double), C.c_void_p, C.c_size_t]),
     "zgr_cloud_lsq_gradient": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "zgr_step": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(zgr_batch), C.POINTER(zgr_result)]),
     "zgr_apply_update": (C.c_int, [C.c_void_p, C.c_uint64, C.c_float, C.c_float]),

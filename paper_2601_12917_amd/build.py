@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzgr.so")
-SOURCES = ["api.hip", "perturb.hip", "forward.hip", "ceilings.hip", "cloud.hip"]
+SOURCES = ["api.hip", "perturb.hip", "forward.hip", "ceilings.hip", "cloud.hip", "backward.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

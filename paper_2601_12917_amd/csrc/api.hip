@@ -3,6 +3,7 @@
 // profiling.  Follows Algorithm 1 (client block: zgr_step; edge-server block:
 // zgr_apply_update) with the estimator of Eq. (11).
 #include "../../include/zgr.h"
+#include "backward.h"
 #include "forward.h"
 #include "internal.h"
 
@@ -850,6 +851,185 @@ zgr_status zgr_cloud_lsq_gradient(const float* W, const float* X, const float* Y
   HIP_TRY(nullptr, launch_cloud_residual(R, Y, (int64_t)batch * n_out, s));                                // - Y
   HIP_TRY(nullptr, launch_cloud_gt_q(R, batch, n_out, n_out, X, n_in, n_in, G, n_in, 1.0f / (float)batch, 0, s));   // R^T X / B
   return ZGR_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Workspace of one backward pass over a batch of `batch` sequences of `seq` tokens (byte offsets).
+struct BwCarve {
+  struct PerLayer { size_t xin, h1, qkv, ctx, xmid, h2, u, f; };
+  std::vector<PerLayer> layer;
+  size_t xfin = 0, hf = 0, logits = 0, targets = 0, row_loss = 0, loss = 0;
+  size_t dx = 0, dt = 0, dff = 0, dqkv = 0, P = 0, dS = 0, stats = 0;
+  size_t total = 0;
+};
+
+BwCarve bw_carve(const zgr_ctx* c, int batch, int seq) {
+  BwCarve v;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+  const zgr_model& m = c->model;
+  if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
+    v.logits = take((size_t)batch * (size_t)c->t[c->lsq_w].rows * 4);
+    v.total = off;
+    return v;
+  }
+  const size_t M = (size_t)batch * seq, d = m.d_model, ff = m.d_ff, es = elem_size(c->dtype);
+  v.layer.resize(m.n_layer);
+  for (int l = 0; l < m.n_layer; ++l) {
+    BwCarve::PerLayer& L = v.layer[l];
+    L.xin = take(M * d * 4);  L.h1 = take(M * d * es);  L.qkv = take(M * 3 * d * es);  L.ctx = take(M * d * es);
+    L.xmid = take(M * d * 4); L.h2 = take(M * d * es);  L.u = take(M * ff * 4);        L.f = take(M * ff * es);
+  }
+  v.xfin = take(M * d * 4);
+  v.hf = take(M * d * es);
+  v.logits = take(m.arch == ZGR_ARCH_DECODER_LM ? M * (size_t)m.vocab * 4 : (size_t)batch * m.n_class * 4);
+  v.targets = take(M * 4);
+  v.row_loss = take(M * 4);
+  v.loss = take(sizeof(double));
+  v.dx = take(M * d * 4);
+  v.dt = take(M * d * 4);
+  v.dff = take(M * ff * 4);
+  v.dqkv = take(M * 3 * d * 4);
+  v.P = take((size_t)batch * m.n_head * seq * seq * 4);
+  v.dS = take((size_t)batch * m.n_head * seq * seq * 4);
+  v.stats = take(M * 2 * 4);
+  v.total = off;
+  return v;
+}
+
+// y = a W^T + bias with a [M, K] kept in the storage type and dy [M, N] known: dW [N, K] = dy^T a, dbias = column sums of dy
+zgr_status linear_param_grads(zgr_ctx* c, const float* dy, int64_t ldy, const void* a, int M, int N, int K, float* dW, float* dbias) {
+  HIP_TRY(c, launch_bw_gemm(c->dtype, dy, 1, ldy, a, K, 1, dW, K, N, K, M, 1.0f, 0, c->stream));
+  HIP_TRY(c, launch_bw_colsum(dy, M, N, ldy, dbias, c->stream));
+  return ZGR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t zgr_cloud_backward_workspace(const zgr_ctx* c, int32_t batch, int32_t seq) {
+  if (!c || c->model.arch == ZGR_ARCH_NONE || batch < 1 || (c->model.arch != ZGR_ARCH_LINEAR_LSQ && seq < 1)) return 0;
+  return bw_carve(c, batch, seq).total;
+}
+
+zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grads, int32_t n_grads, double* loss_out, void* workspace, size_t workspace_bytes) {
+  if (!c) return ZGR_ERR_NULL;
+  if (!grads || !loss_out || !workspace) return fail(c, ZGR_ERR_NULL, "grads, loss_out or workspace is NULL");
+  zgr_status st = check_batch(c, b);
+  if (st != ZGR_OK) return st;
+  if (n_grads != (int32_t)c->t.size()) return fail(c, ZGR_ERR_SHAPE, "grads must hold one pointer per tensor (%zu), got %d", c->t.size(), n_grads);
+  for (int32_t i = 0; i < n_grads; ++i) if (!grads[i]) return fail(c, ZGR_ERR_NULL, "grads[%d] is NULL", i);
+  if ((uintptr_t)workspace & 255) return fail(c, ZGR_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const zgr_model& m = c->model;
+  hipStream_t s = c->stream;
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  const int dt = c->dtype;
+  const BwCarve v = bw_carve(c, b->batch, m.arch == ZGR_ARCH_LINEAR_LSQ ? 1 : b->seq);
+  if (workspace_bytes < v.total) return fail(c, ZGR_ERR_WORKSPACE, "workspace holds %zu bytes, the pass needs %zu", workspace_bytes, v.total);
+  auto F = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  if (m.arch == ZGR_ARCH_LINEAR_LSQ) {
+    // L = mean_b ||x_b W^T - y_b||^2 / 2: dW = (X W^T - Y)^T X / B
+    const zgr_tensor& w = c->t[c->lsq_w];
+    if ((st = forward_loss(c, b, 0)) != ZGR_OK) return st;
+    float* R = F(v.logits);
+    const float* X = reinterpret_cast<const float*>(b->x);
+    HIP_TRY(c, launch_gemm(0, X, w.theta, nullptr, R, EPI_F32, b->batch, (int)w.rows, (int)w.cols, s));
+    HIP_TRY(c, launch_cloud_residual(R, reinterpret_cast<const float*>(b->y), (int64_t)b->batch * w.rows, s));
+    HIP_TRY(c, launch_cloud_gt_q(R, b->batch, w.rows, w.rows, X, (int)w.cols, w.cols, grads[c->lsq_w], w.cols, 1.0f / (float)b->batch, 0, s));
+    HIP_TRY(c, hipMemcpyAsync(c->host_loss, c->ws + c->cv.loss, sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    *loss_out = c->host_loss[0];
+    return std::isfinite(*loss_out) ? ZGR_OK : fail(c, ZGR_ERR_NONFINITE, "loss is not finite");
+  }
+  const int B = b->batch, Tn = b->seq, M = B * Tn, d = m.d_model, ff = m.d_ff, H = m.n_head;
+  if (Tn > kBackwardMaxSeq || (size_t)(2 * (d / H) + Tn) * 4 > 48 * 1024) return fail(c, ZGR_ERR_SHAPE, "seq = %d is beyond what the backward attention rule holds", Tn);
+  const bool lm = m.arch == ZGR_ARCH_DECODER_LM;
+  const int32_t* tok = reinterpret_cast<const int32_t*>(b->x);
+  const int32_t* lengths = lm ? nullptr : b->lengths;
+  const size_t xbytes = (size_t)M * d * 4;
+  // ---- forward, every layer's intermediate results kept
+  HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), F(v.layer.empty() ? v.xfin : v.layer[0].xin), M, Tn, d, m.vocab, s));
+  for (int l = 0; l < m.n_layer; ++l) {
+    const Layer& L = c->layers[l];
+    const BwCarve::PerLayer& W = v.layer[l];
+    float* xnext = F(l + 1 < m.n_layer ? v.layer[l + 1].xin : v.xfin);
+    HIP_TRY(c, launch_layernorm(dt, F(W.xin), T(c, L.ln1_g), T(c, L.ln1_b), ws + W.h1, M, d, m.ln_eps, s));
+    HIP_TRY(c, launch_gemm(dt, ws + W.h1, T(c, L.wq), T(c, L.bq), ws + W.qkv, EPI_STORE, M, 3 * d, d, s));
+    HIP_TRY(c, launch_attention(dt, ws + W.qkv, ws + W.ctx, lengths, B, Tn, d, H, lm ? 1 : 0, s));
+    HIP_TRY(c, hipMemcpyAsync(F(W.xmid), F(W.xin), xbytes, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, launch_gemm(dt, ws + W.ctx, T(c, L.wo), T(c, L.bo), F(W.xmid), EPI_RESID, M, d, d, s));
+    HIP_TRY(c, launch_layernorm(dt, F(W.xmid), T(c, L.ln2_g), T(c, L.ln2_b), ws + W.h2, M, d, m.ln_eps, s));
+    HIP_TRY(c, launch_gemm(dt, ws + W.h2, T(c, L.w1), T(c, L.b1), F(W.u), EPI_F32, M, ff, d, s));
+    HIP_TRY(c, launch_bw_gelu_forward(dt, F(W.u), ws + W.f, (int64_t)M * ff, s));
+    HIP_TRY(c, hipMemcpyAsync(xnext, F(W.xmid), xbytes, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(c, launch_gemm(dt, ws + W.f, T(c, L.w2), T(c, L.b2), xnext, EPI_RESID, M, d, ff, s));
+  }
+  HIP_TRY(c, launch_layernorm(dt, F(v.xfin), T(c, c->lnf_g), T(c, c->lnf_b), ws + v.hf, M, d, m.ln_eps, s));
+  // ---- the loss and its gradient with respect to the final hidden states (into dt), head parameters
+  float* logits = F(v.logits);
+  float* dx = F(v.dx);
+  float* dtb = F(v.dt);
+  double* loss_dev = reinterpret_cast<double*>(ws + v.loss);
+  if (lm) {
+    int32_t* tgt = reinterpret_cast<int32_t*>(ws + v.targets);
+    const double inv_n = 1.0 / ((double)B * (Tn - 1));
+    HIP_TRY(c, launch_lm_targets(tok, tgt, M, Tn, m.vocab, s));
+    HIP_TRY(c, launch_gemm(dt, ws + v.hf, T(c, c->tok_emb), nullptr, logits, EPI_F32, M, m.vocab, d, s));
+    HIP_TRY(c, launch_ce_rows(logits, tgt, F(v.row_loss), M, m.vocab, s));
+    HIP_TRY(c, launch_mean_f64(F(v.row_loss), M, inv_n, loss_dev, s));
+    HIP_TRY(c, launch_bw_cross_entropy(logits, tgt, M, m.vocab, (float)inv_n, s));
+    // tied head: logits = hf E^T, so dE = dlogits^T hf (the embedding rule adds its share below), dhf = dlogits E
+    HIP_TRY(c, launch_bw_gemm(dt, logits, 1, m.vocab, ws + v.hf, d, 1, grads[c->tok_emb], d, m.vocab, d, M, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_gemm(dt, logits, m.vocab, 1, T(c, c->tok_emb), d, 1, dtb, d, M, d, m.vocab, 1.0f, 0, s));
+  } else {
+    const int32_t* labels = reinterpret_cast<const int32_t*>(b->y);
+    const int C = m.n_class;
+    HIP_TRY(c, launch_cls_head(dt, ws + v.hf, T(c, c->cls_w), T(c, c->cls_b), logits, B, Tn, d, C, s));
+    HIP_TRY(c, launch_ce_rows(logits, labels, F(v.row_loss), B, C, s));
+    HIP_TRY(c, launch_mean_f64(F(v.row_loss), B, 1.0 / B, loss_dev, s));
+    HIP_TRY(c, launch_bw_cross_entropy(logits, labels, B, C, 1.0f / (float)B, s));
+    // the head reads the first token of each sequence: rows b T of hf
+    HIP_TRY(c, launch_bw_gemm(dt, logits, 1, C, ws + v.hf, (int64_t)Tn * d, 1, grads[c->cls_w], d, C, d, B, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_colsum(logits, B, C, C, grads[c->cls_b], s));
+    HIP_TRY(c, launch_bw_fill(dtb, (int64_t)M * d, 0.f, s));
+    HIP_TRY(c, launch_bw_gemm(dt, logits, C, 1, T(c, c->cls_w), d, 1, dtb, (int64_t)Tn * d, B, d, C, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_fill(grads[c->tok_emb], (int64_t)m.vocab * d, 0.f, s));
+  }
+  HIP_TRY(c, launch_bw_layernorm(dt, F(v.xfin), T(c, c->lnf_g), dtb, nullptr, dx, F(v.stats), grads[c->lnf_g], grads[c->lnf_b], M, d, m.ln_eps, s));
+  // ---- the blocks in reverse; dx holds dL/d(residual stream) at the block's output
+  for (int l = m.n_layer - 1; l >= 0; --l) {
+    const Layer& L = c->layers[l];
+    const BwCarve::PerLayer& W = v.layer[l];
+    float* dff = F(v.dff);
+    float* dqkv = F(v.dqkv);
+    // x_out = x_mid + f W2^T + b2
+    if ((st = linear_param_grads(c, dx, d, ws + W.f, M, d, ff, grads[L.w2], grads[L.b2])) != ZGR_OK) return st;
+    HIP_TRY(c, launch_bw_gemm(dt, dx, d, 1, T(c, L.w2), ff, 1, dff, ff, M, ff, d, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_gelu(F(W.u), dff, (int64_t)M * ff, s));
+    // u = h2 W1^T + b1
+    if ((st = linear_param_grads(c, dff, ff, ws + W.h2, M, ff, d, grads[L.w1], grads[L.b1])) != ZGR_OK) return st;
+    HIP_TRY(c, launch_bw_gemm(dt, dff, ff, 1, T(c, L.w1), d, 1, dtb, d, M, d, ff, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xmid), T(c, L.ln2_g), dtb, dx, dx, F(v.stats), grads[L.ln2_g], grads[L.ln2_b], M, d, m.ln_eps, s));
+    // x_mid = x_in + ctx Wo^T + bo
+    if ((st = linear_param_grads(c, dx, d, ws + W.ctx, M, d, d, grads[L.wo], grads[L.bo])) != ZGR_OK) return st;
+    HIP_TRY(c, launch_bw_gemm(dt, dx, d, 1, T(c, L.wo), d, 1, dtb, d, M, d, d, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_attention(dt, ws + W.qkv, dtb, lengths, B, Tn, d, H, lm ? 1 : 0, F(v.P), F(v.dS), dqkv, s));
+    // q, k, v = h1 W{q,k,v}^T + b{q,k,v}: three column blocks of dqkv; Wq, Wk, Wv are adjacent, one [3 d, d] matrix
+    const int wi[3] = {L.wq, L.wk, L.wv}, bi[3] = {L.bq, L.bk, L.bv};
+    for (int p = 0; p < 3; ++p)
+      if ((st = linear_param_grads(c, dqkv + (size_t)p * d, 3 * d, ws + W.h1, M, d, d, grads[wi[p]], grads[bi[p]])) != ZGR_OK) return st;
+    HIP_TRY(c, launch_bw_gemm(dt, dqkv, 3 * d, 1, T(c, L.wq), d, 1, dtb, d, M, d, 3 * d, 1.0f, 0, s));
+    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xin), T(c, L.ln1_g), dtb, dx, dx, F(v.stats), grads[L.ln1_g], grads[L.ln1_b], M, d, m.ln_eps, s));
+  }
+  HIP_TRY(c, launch_bw_embedding(tok, dx, M, Tn, d, m.vocab, grads[c->tok_emb], grads[c->pos_emb], m.max_pos, s));
+  HIP_TRY(c, hipMemcpyAsync(c->host_loss, loss_dev, sizeof(double), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  *loss_out = c->host_loss[0];
+  return std::isfinite(*loss_out) ? ZGR_OK : fail(c, ZGR_ERR_NONFINITE, "loss is not finite");
 }
 
 zgr_status zgr_perturb(zgr_ctx* c, uint64_t step, float coef) {

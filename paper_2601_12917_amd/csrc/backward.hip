@@ -1,0 +1,376 @@
+// Backward pass of the cloud block of Algorithm 1 ("Perform BP on D_p with W^r; collect gradients to build basis
+// V_r"; Sec. 3.2, "Guided Perturbation Sampling on Cloud"): dL/dtheta of the loss of forward.hip, by the chain rule
+// layer by layer, in fp32.  The forward pass that precedes it runs the client's own kernels and keeps every layer's
+// intermediate results; these kernels take them back in reverse order.
+//
+// This runs on the cloud once per stored gradient snapshot, not on the client's step: the kernels are plain
+// (LDS-tiled fp32 products with general strides, one workgroup per row for the row-wise rules), deterministic (no
+// atomics: every sum has a fixed order) and not tuned.
+#include "backward.h"
+
+namespace zgr {
+
+namespace {
+
+struct bf16_t { uint16_t bits; };
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
+__device__ __forceinline__ void from_f32(float x, float& o) { o = x; }
+__device__ __forceinline__ void from_f32(float x, bf16_t& o) {
+  const __bf16 h = static_cast<__bf16>(x);
+  o.bits = __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// block of 256 threads
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// ------------------------------------------------------------------ C (+)= alpha A B with general strides
+// C[i][j] = sum_k A[i ars + k acs] B[k brs + j bcs], i < M, j < N, k < K; A fp32 (a gradient), B fp32 or the storage
+// type (a weight or a kept activation).  64 x 64 tile, 16 deep, 4 x 4 outputs per thread.  The two uses:
+//   input gradient   dA [M, K'] = dY [M, N'] W [N', K']      : A = dY (ars = N', acs = 1), B = W  (brs = K', bcs = 1)
+//   weight gradient  dW [N', K'] = dY^T [N', M] A_in [M, K'] : A = dY (ars = 1, acs = N'), B = A_in (brs = K', bcs = 1)
+template <typename TB>
+__global__ void __launch_bounds__(256) gemm_strided_kernel(const float* __restrict__ A, int64_t ars, int64_t acs, const TB* __restrict__ B, int64_t brs, int64_t bcs,
+                                                           float* __restrict__ C, int64_t ldc, int M, int N, int K, float alpha, int accumulate) {
+  __shared__ float As[16][64 + 4], Bs[16][64 + 4];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const bool a_rows_contig = ars == 1, b_k_contig = brs == 1;       // which index consecutive threads should walk
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      const int ra = a_rows_contig ? (i & 63) : (i >> 4), ka = a_rows_contig ? (i >> 6) : (i & 15);
+      As[ka][ra] = (m0 + ra < M && k0 + ka < K) ? A[(int64_t)(m0 + ra) * ars + (int64_t)(k0 + ka) * acs] : 0.f;
+      const int cb = b_k_contig ? (i >> 4) : (i & 63), kb = b_k_contig ? (i & 15) : (i >> 6);
+      Bs[kb][cb] = (n0 + cb < N && k0 + kb < K) ? to_f32(B[(int64_t)(k0 + kb) * brs + (int64_t)(n0 + cb) * bcs]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) { float* c = C + (int64_t)m * ldc + n; *c = (accumulate ? *c : 0.f) + alpha * acc[i][j]; }
+    }
+}
+
+// out[n] = sum_m Y[m ld + n]  (bias gradients): 64 columns per block, 4 row groups, rows in increasing order per group
+__global__ void __launch_bounds__(256) colsum_kernel(const float* __restrict__ Y, int M, int N, int64_t ld, float* __restrict__ out) {
+  __shared__ float part[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
+  float s = 0.f;
+  if (c < N)
+    for (int m = g; m < M; m += 4) s += Y[(int64_t)m * ld + c];
+  part[g][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (g == 0 && c < N) out[c] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+}
+
+__global__ void __launch_bounds__(256) fill_kernel(float* __restrict__ p, int64_t n, float v) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = v;
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+// In place on a row of logits: d = (softmax - onehot(target)) * inv_count, or zeros for a row without a target.
+__global__ void __launch_bounds__(256) ce_backward_kernel(float* __restrict__ logits, const int32_t* __restrict__ targets, int n, float inv_count) {
+  __shared__ float red[4];
+  float* row = logits + (size_t)blockIdx.x * n;
+  const int tgt = targets[blockIdx.x];
+  if (tgt < 0 || tgt >= n) {                        // uniform over the block
+    for (int i = threadIdx.x; i < n; i += 256) row[i] = 0.f;
+    return;
+  }
+  float mx = -INFINITY;
+  for (int i = threadIdx.x; i < n; i += 256) mx = fmaxf(mx, row[i]);
+  mx = block_max(mx, red);
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += expf(row[i] - mx);
+  s = block_sum(s, red);
+  const float inv = 1.0f / s;
+  for (int i = threadIdx.x; i < n; i += 256) row[i] = (expf(row[i] - mx) * inv - (i == tgt ? 1.0f : 0.f)) * inv_count;
+}
+
+// ------------------------------------------------------------------ LayerNorm
+// y = xhat g + b, xhat = (x - mu) rstd.  Per row: dx = rstd (dy g - mean(dy g) - xhat mean(dy g xhat)), written as
+// dx_out = (add ? add : 0) + dx; the row's (mu, rstd) go to stats for the parameter gradients.
+template <typename T>
+__global__ void __launch_bounds__(256) ln_backward_kernel(const float* __restrict__ x, const T* __restrict__ g, const float* __restrict__ dy,
+                                                          const float* add, float* dx_out, float* __restrict__ stats, int d, float eps) {   // add may be dx_out
+  __shared__ float red[4];
+  const size_t o = (size_t)blockIdx.x * d;
+  const float* row = x + o;
+  const float* drow = dy + o;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) s += row[i];
+  const float mu = block_sum(s, red) / d;
+  float v = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) { const float t = row[i] - mu; v += t * t; }
+  const float rstd = 1.0f / sqrtf(block_sum(v, red) / d + eps);
+  float s1 = 0.f, s2 = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float dg = drow[i] * to_f32(g[i]);
+    s1 += dg;
+    s2 += dg * ((row[i] - mu) * rstd);
+  }
+  s1 = block_sum(s1, red) / d;
+  s2 = block_sum(s2, red) / d;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float xhat = (row[i] - mu) * rstd;
+    const float r = rstd * (drow[i] * to_f32(g[i]) - s1 - xhat * s2);
+    dx_out[o + i] = (add ? add[o + i] : 0.f) + r;
+  }
+  if (threadIdx.x == 0) { stats[2 * blockIdx.x] = mu; stats[2 * blockIdx.x + 1] = rstd; }
+}
+
+// dg[c] = sum_m dy[m][c] xhat[m][c], db[c] = sum_m dy[m][c]
+__global__ void __launch_bounds__(256) ln_param_grad_kernel(const float* __restrict__ x, const float* __restrict__ dy, const float* __restrict__ stats,
+                                                            int M, int d, float* __restrict__ dg, float* __restrict__ db) {
+  __shared__ float pg[4][64], pb[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
+  float sg = 0.f, sb = 0.f;
+  if (c < d)
+    for (int m = grp; m < M; m += 4) {
+      const float dyv = dy[(size_t)m * d + c];
+      sg += dyv * ((x[(size_t)m * d + c] - stats[2 * m]) * stats[2 * m + 1]);
+      sb += dyv;
+    }
+  pg[grp][threadIdx.x & 63] = sg; pb[grp][threadIdx.x & 63] = sb;
+  __syncthreads();
+  if (grp == 0 && c < d) {
+    dg[c] = (pg[0][threadIdx.x] + pg[1][threadIdx.x]) + (pg[2][threadIdx.x] + pg[3][threadIdx.x]);
+    db[c] = (pb[0][threadIdx.x] + pb[1][threadIdx.x]) + (pb[2][threadIdx.x] + pb[3][threadIdx.x]);
+  }
+}
+
+// ------------------------------------------------------------------ GELU (erf form)
+template <typename T>
+__global__ void __launch_bounds__(256) gelu_forward_kernel(const float* __restrict__ u, T* __restrict__ f, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float x = u[i];
+    from_f32(0.5f * x * (1.0f + erff(x * 0.70710678118654752f)), f[i]);
+  }
+}
+// du = df * (Phi(u) + u phi(u)), in place on df
+__global__ void __launch_bounds__(256) gelu_backward_kernel(const float* __restrict__ u, float* __restrict__ df, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float x = u[i];
+    const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+    const float pdf = 0.3989422804014327f * expf(-0.5f * x * x);
+    df[i] *= cdf + x * pdf;
+  }
+}
+
+// ------------------------------------------------------------------ attention
+// qkv [B T, 3 d]: query, key, value of head h at columns h dh, d + h dh, 2 d + h dh.  Key j takes part in query i's
+// softmax when j < length (the sequence's length, or T) and, under the causal mask, j <= i.
+//
+// Per query row (one block per (b, h, i)): p = softmax(q k^T / sqrt dh), dp_j = dctx_i . v_j, ds = p (dp - p . dp);
+// P and dS rows (zeros at masked keys) go to memory for the key-side kernel, dq_i = sum_j ds_j k_j / sqrt dh.
+template <typename T>
+__global__ void __launch_bounds__(256) attn_backward_query_kernel(const T* __restrict__ qkv, const float* __restrict__ dctx, const int32_t* __restrict__ lengths,
+                                                                  int seq, int d, int n_head, int dh, int causal, float* __restrict__ P, float* __restrict__ dS,
+                                                                  float* __restrict__ dqkv) {
+  extern __shared__ float sm[];          // q [dh], do [dh], ds [seq]
+  __shared__ float red[4];
+  float* qs = sm; float* dos = sm + dh; float* dss = sm + 2 * dh;
+  const int i = blockIdx.x % seq, h = (blockIdx.x / seq) % n_head, b = blockIdx.x / (seq * n_head);
+  const size_t ld = (size_t)3 * d;
+  const T* base = qkv + (size_t)b * seq * ld + (size_t)h * dh;
+  const float scale = 1.0f / sqrtf((float)dh);
+  int kend = lengths ? lengths[b] : seq;
+  kend = kend < seq ? kend : seq;
+  if (causal) kend = kend < i + 1 ? kend : i + 1;
+  for (int t = threadIdx.x; t < dh; t += 256) {
+    qs[t] = to_f32(base[(size_t)i * ld + t]);
+    dos[t] = dctx[((size_t)b * seq + i) * d + (size_t)h * dh + t];
+  }
+  __syncthreads();
+  // scores and dp for this thread's keys (seq <= 256 * 8)
+  constexpr int MAXJ = 8;
+  float sc[MAXJ], dp[MAXJ];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < MAXJ; ++u) {
+    const int j = threadIdx.x + 256 * u;
+    sc[u] = -INFINITY; dp[u] = 0.f;
+    if (j < kend) {
+      const T* kr = base + (size_t)j * ld + d;
+      const T* vr = base + (size_t)j * ld + 2 * d;
+      float s = 0.f, p = 0.f;
+      for (int t = 0; t < dh; ++t) { s = __builtin_fmaf(qs[t], to_f32(kr[t]), s); p = __builtin_fmaf(dos[t], to_f32(vr[t]), p); }
+      sc[u] = s * scale; dp[u] = p;
+      mx = fmaxf(mx, sc[u]);
+    }
+  }
+  mx = block_max(mx, red);
+  float den = 0.f;
+#pragma unroll
+  for (int u = 0; u < MAXJ; ++u) { sc[u] = (threadIdx.x + 256 * u < kend) ? expf(sc[u] - mx) : 0.f; den += sc[u]; }
+  den = block_sum(den, red);
+  const float inv = den > 0.f ? 1.0f / den : 0.f;
+  float dot = 0.f;
+#pragma unroll
+  for (int u = 0; u < MAXJ; ++u) { sc[u] *= inv; dot += sc[u] * dp[u]; }
+  dot = block_sum(dot, red);
+  float* prow = P + (((size_t)b * n_head + h) * seq + i) * seq;
+  float* srow = dS + (((size_t)b * n_head + h) * seq + i) * seq;
+#pragma unroll
+  for (int u = 0; u < MAXJ; ++u) {
+    const int j = threadIdx.x + 256 * u;
+    if (j < seq) {
+      const float ds = sc[u] * (dp[u] - dot);
+      prow[j] = sc[u]; srow[j] = ds; dss[j] = ds;
+    }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < dh; t += 256) {
+    float a = 0.f;
+    for (int j = 0; j < kend; ++j) a = __builtin_fmaf(dss[j], to_f32(base[(size_t)j * ld + d + t]), a);
+    dqkv[((size_t)b * seq + i) * ld + (size_t)h * dh + t] = a * scale;
+  }
+}
+
+// Per key row (one block per (b, h, j)): dk_j = sum_i dS[i][j] q_i / sqrt dh, dv_j = sum_i P[i][j] dctx_i.
+template <typename T>
+__global__ void __launch_bounds__(128) attn_backward_key_kernel(const T* __restrict__ qkv, const float* __restrict__ dctx, int seq, int d, int n_head, int dh,
+                                                                const float* __restrict__ P, const float* __restrict__ dS, float* __restrict__ dqkv) {
+  const int j = blockIdx.x % seq, h = (blockIdx.x / seq) % n_head, b = blockIdx.x / (seq * n_head);
+  const size_t ld = (size_t)3 * d;
+  const T* base = qkv + (size_t)b * seq * ld + (size_t)h * dh;
+  const float scale = 1.0f / sqrtf((float)dh);
+  const float* pcol = P + ((size_t)b * n_head + h) * seq * seq + j;
+  const float* scol = dS + ((size_t)b * n_head + h) * seq * seq + j;
+  for (int t = threadIdx.x; t < dh; t += 128) {
+    float dk = 0.f, dv = 0.f;
+    for (int i = 0; i < seq; ++i) {
+      dk = __builtin_fmaf(scol[(size_t)i * seq], to_f32(base[(size_t)i * ld + t]), dk);
+      dv = __builtin_fmaf(pcol[(size_t)i * seq], dctx[((size_t)b * seq + i) * d + (size_t)h * dh + t], dv);
+    }
+    dqkv[((size_t)b * seq + j) * ld + d + (size_t)h * dh + t] = dk * scale;
+    dqkv[((size_t)b * seq + j) * ld + 2 * d + (size_t)h * dh + t] = dv;
+  }
+}
+
+// ------------------------------------------------------------------ embeddings
+// x0[m] = E[tok[m]] + Pe[m mod seq]: one thread per column walks the rows in order (tokens repeat, so the adds into
+// one row of dE must be ordered to be reproducible); dE accumulates (the tied head has written it), dPe is overwritten.
+__global__ void __launch_bounds__(256) embed_backward_kernel(const int32_t* __restrict__ tok, const float* __restrict__ dx, int M, int seq, int d, int vocab,
+                                                             float* __restrict__ dE, float* __restrict__ dPe, int max_pos) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= d) return;
+  for (int p = 0; p < max_pos; ++p) dPe[(size_t)p * d + c] = 0.f;
+  for (int m = 0; m < M; ++m) {
+    int t = tok[m];
+    t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+    const float g = dx[(size_t)m * d + c];
+    dE[(size_t)t * d + c] += g;
+    dPe[(size_t)(m % seq) * d + c] += g;
+  }
+}
+
+}  // namespace
+
+static unsigned grid_1d(int64_t n) { const int64_t b = (n + 255) / 256; return (unsigned)(b < 1 ? 1 : (b > 4096 ? 4096 : b)); }
+
+hipError_t launch_bw_gemm(int b_dtype, const float* A, int64_t ars, int64_t acs, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
+                          int M, int N, int K, float alpha, int accumulate, hipStream_t s) {
+  if (M < 1 || N < 1) return hipSuccess;
+  const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
+  if (b_dtype == 1) hipLaunchKernelGGL(gemm_strided_kernel<bf16_t>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const bf16_t*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate);
+  else              hipLaunchKernelGGL(gemm_strided_kernel<float>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const float*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_colsum(const float* Y, int M, int N, int64_t ld, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, s, Y, M, N, ld, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_fill(float* p, int64_t n, float v, hipStream_t s) {
+  if (n < 1) return hipSuccess;
+  hipLaunchKernelGGL(fill_kernel, dim3(grid_1d(n)), dim3(256), 0, s, p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_cross_entropy(float* logits, const int32_t* targets, int rows, int n, float inv_count, hipStream_t s) {
+  hipLaunchKernelGGL(ce_backward_kernel, dim3((unsigned)rows), dim3(256), 0, s, logits, targets, n, inv_count);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_layernorm(int dtype, const float* x, const void* g, const float* dy, const float* add, float* dx_out, float* stats, float* dg, float* db,
+                               int M, int d, float eps, hipStream_t s) {
+  if (dtype == 1) hipLaunchKernelGGL(ln_backward_kernel<bf16_t>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const bf16_t*>(g), dy, add, dx_out, stats, d, eps);
+  else            hipLaunchKernelGGL(ln_backward_kernel<float>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const float*>(g), dy, add, dx_out, stats, d, eps);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(ln_param_grad_kernel, dim3((unsigned)((d + 63) / 64)), dim3(256), 0, s, x, dy, stats, M, d, dg, db);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_gelu_forward(int dtype, const float* u, void* f, int64_t n, hipStream_t s) {
+  if (dtype == 1) hipLaunchKernelGGL(gelu_forward_kernel<bf16_t>, dim3(grid_1d(n)), dim3(256), 0, s, u, reinterpret_cast<bf16_t*>(f), n);
+  else            hipLaunchKernelGGL(gelu_forward_kernel<float>, dim3(grid_1d(n)), dim3(256), 0, s, u, reinterpret_cast<float*>(f), n);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_gelu(const float* u, float* df, int64_t n, hipStream_t s) {
+  hipLaunchKernelGGL(gelu_backward_kernel, dim3(grid_1d(n)), dim3(256), 0, s, u, df, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_attention(int dtype, const void* qkv, const float* dctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal,
+                               float* P, float* dS, float* dqkv, hipStream_t s) {
+  if (seq > kBackwardMaxSeq || d % n_head != 0) return hipErrorInvalidValue;
+  const int dh = d / n_head;
+  const size_t lds = (size_t)(2 * dh + seq) * sizeof(float);
+  if (lds > 48 * 1024) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)batch * n_head * seq;
+  if (dtype == 1) {
+    hipLaunchKernelGGL(attn_backward_query_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const bf16_t*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
+    hipLaunchKernelGGL(attn_backward_key_kernel<bf16_t>, dim3(blocks), dim3(128), 0, s, reinterpret_cast<const bf16_t*>(qkv), dctx, seq, d, n_head, dh, P, dS, dqkv);
+  } else {
+    hipLaunchKernelGGL(attn_backward_query_kernel<float>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const float*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
+    hipLaunchKernelGGL(attn_backward_key_kernel<float>, dim3(blocks), dim3(128), 0, s, reinterpret_cast<const float*>(qkv), dctx, seq, d, n_head, dh, P, dS, dqkv);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_embedding(const int32_t* tok, const float* dx, int M, int seq, int d, int vocab, float* dE, float* dPe, int max_pos, hipStream_t s) {
+  hipLaunchKernelGGL(embed_backward_kernel, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s, tok, dx, M, seq, d, vocab, dE, dPe, max_pos);
+  return hipGetLastError();
+}
+
+}  // namespace zgr

@@ -115,6 +115,19 @@ class Session:
         B.check(self.lib.zgr_loss(self.ctx, C.byref(batch), C.byref(v)), self.ctx)
         return v.value
 
+    def cloud_backward(self, batch, seq=0):
+        """(loss, [dL/dtheta_i as a device fp32 tensor [rows, cols] per parameter]) by zgr_cloud_backward."""
+        n_b = int(batch.batch)
+        nbytes = self.lib.zgr_cloud_backward_workspace(self.ctx, n_b, int(batch.seq) if batch.seq else int(seq))
+        if nbytes == 0:
+            raise RuntimeError("zgr_cloud_backward_workspace returned 0 (a context without a model, or a bad batch)")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+        grads = [torch.empty(*p.values.shape, dtype=torch.float32, device=self.dev) for p in self.params]
+        ptrs = (C.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
+        v = C.c_double()
+        B.check(self.lib.zgr_cloud_backward(self.ctx, C.byref(batch), ptrs, len(grads), C.byref(v), ws.data_ptr(), nbytes), self.ctx)
+        return v.value, grads
+
     def set_basis(self, index, U: Optional[np.ndarray], k):
         if U is None:
             B.check(self.lib.zgr_set_basis(self.ctx, index, None, 0, 0), self.ctx)

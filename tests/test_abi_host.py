@@ -151,3 +151,7 @@ def test_cloud_entry_points_validate_their_arguments_without_a_gpu():
     assert lib.zgr_cloud_basis(one, 1, 8, 8, 4, 0x1000, 1, 0x1000, 4, C.byref(dep), 0x1010, 1 << 20, None) == B.ZGR_ERR_WORKSPACE
     assert lib.zgr_cloud_lsq_gradient(None, 0x1000, 0x1000, 1, 1, 1, 0x1000, 0x1000, 64, None) == B.ZGR_ERR_NULL
     assert lib.zgr_cloud_lsq_gradient(0x1000, 0x1000, 0x1000, 4, 4, 4, 0x1000, 0x1000, 8, None) == B.ZGR_ERR_WORKSPACE
+    # the backward pass needs a context: without one it reports that and sizes nothing
+    assert lib.zgr_cloud_backward_workspace(None, 4, 16) == 0
+    v = C.c_double()
+    assert lib.zgr_cloud_backward(None, None, None, 0, C.byref(v), None, 0) == B.ZGR_ERR_NULL
