@@ -494,12 +494,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   load_radius_table(tab, gtab);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, rg = lane >> 4;
-  // contiguous run of the list per block; R slice regenerated only when the column strip changes (see above)
+  // contiguous run of the list per block; R slice regenerated only when the column strip changes (see above).
+  // Consecutive block ids go round-robin to the 8 XCDs: run j goes to block (j % (nblk / 8)) * 8 + j / (nblk / 8), so
+  // that the blocks of one XCD hold neighbouring runs, i.e. neighbouring column strips of the same matrices, walk the
+  // same rows at about the same time and find each other's rows of U in their common L2.
+  const int per_xcd = nblk >> 3;
+  const int run = (nblk & 7) ? (int)blockIdx.x : ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
   const int per_block = (a.n_tiles + nblk - 1) / nblk;
-  const int w_end = min(a.n_tiles, ((int)blockIdx.x + 1) * per_block);
+  const int w_end = min(a.n_tiles, (run + 1) * per_block);
   int prev_tensor = -1;
   int64_t prev_col0 = -1;
-  for (int w = (int)blockIdx.x * per_block; w < w_end; ++w) {
+  for (int w = run * per_block; w < w_end; ++w) {
     const WorkItem it = items[w];
     const TensorDesc d = descs[it.tensor];
     const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
