@@ -396,6 +396,7 @@ __global__ void __launch_bounds__(256) perturb_tile_kernel(PerturbArgs a, const 
 // 2P x 4 accumulators.  The contraction index is l = rg * (kpt/4) + s: a lane reads kpt/4 consecutive floats
 // of its row of U from global memory and one row of the R slice from LDS per step.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kTilePasses = 3;      // runs of the tile list per block of the matrix-core kernel
 
 template <typename T, int P, bool WRITE_Z, bool BATCH, bool FULL>
 __device__ __forceinline__ void mfma_row_block(const TensorDesc& d, const PerturbArgs& a, float c, const RadiusEntry* tab, const float* Rs,
@@ -494,44 +495,49 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   load_radius_table(tab, gtab);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, rg = lane >> 4;
-  // contiguous run of the list per block; R slice regenerated only when the column strip changes (see above).
-  // Consecutive block ids go round-robin to the 8 XCDs: run j goes to block (j % (nblk / 8)) * 8 + j / (nblk / 8), so
-  // that the blocks of one XCD hold neighbouring runs, i.e. neighbouring column strips of the same matrices, walk the
-  // same rows at about the same time and find each other's rows of U in their common L2.
+  // Every block takes kTilePasses contiguous runs of the list; the R slice is regenerated only when the column strip
+  // changes (see above).  Consecutive block ids go round-robin to the 8 XCDs, so the list is cut into 8 chunks, one
+  // per XCD, and in pass i the blocks q = 0, 1, ... of an XCD take the neighbouring runs i n + q of its chunk: at any
+  // time the blocks of one XCD work on neighbouring column strips of the same few matrices, walk the same rows and
+  // find each other's rows of U in their common L2, and a block's next run lies in other matrices.
+  const bool by_xcd = (nblk & 7) == 0;
+  const int n_pass = by_xcd ? kTilePasses : 1;
   const int per_xcd = nblk >> 3;
-  const int run = (nblk & 7) ? (int)blockIdx.x : ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-  const int per_block = (a.n_tiles + nblk - 1) / nblk;
-  const int w_end = min(a.n_tiles, (run + 1) * per_block);
+  const int run_len = (a.n_tiles + nblk * n_pass - 1) / (nblk * n_pass);
   int prev_tensor = -1;
   int64_t prev_col0 = -1;
-  for (int w = run * per_block; w < w_end; ++w) {
-    const WorkItem it = items[w];
-    const TensorDesc d = descs[it.tensor];
-    const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
-    const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kq4 = kpt >> 2;
-    T* __restrict__ th = reinterpret_cast<T*>(d.theta);
-    const bool same_strip = it.tensor == prev_tensor && col0 == prev_col0;
-    prev_tensor = it.tensor; prev_col0 = col0;
-    if (!same_strip) __syncthreads();                // table loaded / previous strip's readers of Rs done
-    for (int idx = tid; idx < (same_strip ? 0 : kpt * 32); idx += 256) {
-      const int l = idx >> 5, g = idx & 31;
-      const int64_t col = col0 + (int64_t)g * P;
-      float r[P];
+  for (int pass = 0; pass < n_pass; ++pass) {
+    const int run = by_xcd ? (((int)blockIdx.x & 7) * n_pass + pass) * per_xcd + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+    const int w_end = min(a.n_tiles, (run + 1) * run_len);
+    for (int w = run * run_len; w < w_end; ++w) {
+      const WorkItem it = items[w];
+      const TensorDesc d = descs[it.tensor];
+      const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;
+      const int nrows = it.count, k = d.k, kpt = (k + 7) & ~7, kq4 = kpt >> 2;
+      T* __restrict__ th = reinterpret_cast<T*>(d.theta);
+      const bool same_strip = it.tensor == prev_tensor && col0 == prev_col0;
+      prev_tensor = it.tensor; prev_col0 = col0;
+      if (!same_strip) __syncthreads();                // table loaded / previous strip's readers of Rs done
+      for (int idx = tid; idx < (same_strip ? 0 : kpt * 32); idx += 256) {
+        const int l = idx >> 5, g = idx & 31;
+        const int64_t col = col0 + (int64_t)g * P;
+        float r[P];
 #pragma unroll
-      for (int j = 0; j < P; ++j) r[j] = 0.f;
-      if (l < k && col < d.cols) {
-        draw<P, BATCH>((uint64_t)((int64_t)l * d.cols + col) / P, d.id | 0x80000000u, a, tab, r);
+        for (int j = 0; j < P; ++j) r[j] = 0.f;
+        if (l < k && col < d.cols) {
+          draw<P, BATCH>((uint64_t)((int64_t)l * d.cols + col) / P, d.id | 0x80000000u, a, tab, r);
 #pragma unroll
-        for (int j = 0; j < P; ++j) r[j] *= d.b;
+          for (int j = 0; j < P; ++j) r[j] *= d.b;
+        }
+#pragma unroll
+        for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
       }
-#pragma unroll
-      for (int j = 0; j < P; ++j) Rs[l * TC + g * P + j] = r[j];
-    }
-    if (!same_strip) __syncthreads();
-    const bool full = (nrows % 64 == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
-    for (int r0 = 0; r0 < nrows; r0 += 64) {
-      if (full) mfma_row_block<T, P, WRITE_Z, BATCH, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
-      else      mfma_row_block<T, P, WRITE_Z, BATCH, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
+      if (!same_strip) __syncthreads();
+      const bool full = (nrows % 64 == 0) && row0 + nrows <= d.rows && col0 + TC <= d.cols && k == kpt;
+      for (int r0 = 0; r0 < nrows; r0 += 64) {
+        if (full) mfma_row_block<T, P, WRITE_Z, BATCH, true>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
+        else      mfma_row_block<T, P, WRITE_Z, BATCH, false>(d, a, c, tab, Rs, th, zout, row0, col0, r0, nrows, k, kq4, wave, n16, rg);
+      }
     }
   }
 }
