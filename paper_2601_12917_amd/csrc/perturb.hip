@@ -503,13 +503,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   const bool by_xcd = (nblk & 7) == 0;
   const int n_pass = by_xcd ? kTilePasses : 1;
   const int per_xcd = nblk >> 3;
-  const int run_len = (a.n_tiles + nblk * n_pass - 1) / (nblk * n_pass);
+  const int64_t n_runs = (int64_t)nblk * n_pass;          // run r is tiles [r n / R, (r + 1) n / R): lengths differ by at most one
   int prev_tensor = -1;
   int64_t prev_col0 = -1;
   for (int pass = 0; pass < n_pass; ++pass) {
     const int run = by_xcd ? (((int)blockIdx.x & 7) * n_pass + pass) * per_xcd + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
-    const int w_end = min(a.n_tiles, (run + 1) * run_len);
-    for (int w = run * run_len; w < w_end; ++w) {
+    const int w_end = (int)(((int64_t)run + 1) * a.n_tiles / n_runs);
+    for (int w = (int)((int64_t)run * a.n_tiles / n_runs); w < w_end; ++w) {
       const WorkItem it = items[w];
       const TensorDesc d = descs[it.tensor];
       const int64_t row0 = it.first >> 32, col0 = it.first & 0xFFFFFFFFll;

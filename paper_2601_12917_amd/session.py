@@ -290,22 +290,30 @@ def debug_cossin_table(bits, device="cuda:0"):
 
 
 # ---- cloud block of Algorithm 1 (context-free) ----------------------------------
-def cloud_basis(snapshots, k, omega, n_iter, ldu=None, device="cuda:0"):
-    """U [rows, ldu] and the number of dependent columns: zgr_cloud_basis on host arrays (marshalling only)."""
+def cloud_basis_device(snaps, k, omega, n_iter, ldu=None):
+    """(U [rows, ldu] device tensor, dependent columns) from device fp32 snapshots [rows, cols] and a device start omega [cols, k]."""
     lib = B.lib()
-    snaps = [torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to(device) for g in snapshots]
+    snaps = [g.contiguous() for g in snaps]
     rows, cols = snaps[0].shape
     ldu = ldu or k
-    om = torch.from_numpy(np.ascontiguousarray(omega, dtype=np.float32)).to(device)
-    U = torch.zeros(rows, ldu, dtype=torch.float32, device=device)
+    om = omega.contiguous()
+    U = torch.zeros(rows, ldu, dtype=torch.float32, device=snaps[0].device)
     nbytes = lib.zgr_cloud_basis_workspace(rows, cols, k)
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=snaps[0].device)
     ptrs = (C.c_void_p * len(snaps))(*[t.data_ptr() for t in snaps])
     dep = C.c_int32(-1)
     B.check(lib.zgr_cloud_basis(ptrs, len(snaps), rows, cols, k, om.data_ptr(), n_iter, U.data_ptr(), ldu, C.byref(dep), ws.data_ptr(), nbytes,
                                 torch.cuda.current_stream().cuda_stream))
     torch.cuda.synchronize()
-    return U.cpu().numpy(), dep.value
+    return U, dep.value
+
+
+def cloud_basis(snapshots, k, omega, n_iter, ldu=None, device="cuda:0"):
+    """U [rows, ldu] and the number of dependent columns: zgr_cloud_basis on host arrays (marshalling only)."""
+    snaps = [torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to(device) for g in snapshots]
+    om = torch.from_numpy(np.ascontiguousarray(omega, dtype=np.float32)).to(device)
+    U, dep = cloud_basis_device(snaps, k, om, n_iter, ldu)
+    return U.cpu().numpy(), dep
 
 
 def cloud_lsq_gradient(W, X, Y, device="cuda:0"):
