@@ -218,7 +218,7 @@ def main():
     ap.add_argument("--with-library", action="store_true", help="with --gemm-shapes: also time torch.matmul (the vendor library) on the same operands, as context")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

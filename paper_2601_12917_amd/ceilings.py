@@ -2,7 +2,7 @@
 summary (and, with --json FILE, as JSON): the bare in-place read-modify-write stream in GB/s and the
 vector-instruction issue rate in cycles per wave64 instruction and SIMD.
 
-    python -m paper_2601_12917_amd.ceilings [--json gpurun_out/ceilings.json]
+    python -m paper_2601_12917_amd.ceilings [--json ceilings.json]
 
 Argument marshalling and arithmetic on the measured times only; the kernels are in csrc/ceilings.hip.
 """

@@ -863,6 +863,9 @@ struct BwCarve {
   std::vector<PerLayer> layer;
   size_t xfin = 0, hf = 0, logits = 0, targets = 0, row_loss = 0, loss = 0;
   size_t dx = 0, dt = 0, dff = 0, dqkv = 0, P = 0, dS = 0, stats = 0;
+  size_t part = 0;                   // chunk sums of the column reductions
+  size_t tA = 0, tB = 0, tW = 0;     // bf16 operands of the matrix-core products (bf16 models with a token count that is a multiple of 64)
+  bool mfma = false;
   size_t total = 0;
 };
 
@@ -896,15 +899,18 @@ BwCarve bw_carve(const zgr_ctx* c, int batch, int seq) {
   v.P = take((size_t)batch * m.n_head * seq * seq * 4);
   v.dS = take((size_t)batch * m.n_head * seq * seq * 4);
   v.stats = take(M * 2 * 4);
+  v.part = take(4 * bw_colsum_scratch_floats((int)std::max(std::max(ff, 3 * d), (size_t)m.n_class)));
+  v.mfma = c->dtype == ZGR_BF16 && M % 64 == 0;
+  if (v.mfma) {
+    // widest contraction of a product: the feed-forward width, the three projections side by side, or (decoder) the
+    // vocabulary, rounded up to the multiple of 64 the GEMM takes
+    const size_t widest = std::max(std::max(ff, 3 * d), m.arch == ZGR_ARCH_DECODER_LM ? align_up((size_t)m.vocab, 64) : (size_t)0);
+    v.tA = take(2 * M * widest);
+    v.tB = take(2 * M * std::max(ff, d));
+    v.tW = take(2 * d * widest);
+  }
   v.total = off;
   return v;
-}
-
-// y = a W^T + bias with a [M, K] kept in the storage type and dy [M, N] known: dW [N, K] = dy^T a, dbias = column sums of dy
-zgr_status linear_param_grads(zgr_ctx* c, const float* dy, int64_t ldy, const void* a, int M, int N, int K, float* dW, float* dbias) {
-  HIP_TRY(c, launch_bw_gemm(c->dtype, dy, 1, ldy, a, K, 1, dW, K, N, K, M, 1.0f, 0, c->stream));
-  HIP_TRY(c, launch_bw_colsum(dy, M, N, ldy, dbias, c->stream));
-  return ZGR_OK;
 }
 
 }  // namespace
@@ -951,6 +957,36 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
   const int32_t* tok = reinterpret_cast<const int32_t*>(b->x);
   const int32_t* lengths = lm ? nullptr : b->lengths;
   const size_t xbytes = (size_t)M * d * 4;
+  // The products of the backward half.  fp32 models: the strided fp32 kernel on the operands as they lie.  bf16 models
+  // (token count a multiple of 64): the forward pass's matrix-core GEMM, which contracts along the rows of both
+  // operands, on bf16 copies written out with the contraction index innermost.
+  unsigned char* tA = ws + v.tA; unsigned char* tB = ws + v.tB; unsigned char* tW = ws + v.tW;
+  const void* tB_holds = nullptr;                       // the kept activation whose transpose tB holds
+  // dA [M, Kp] = dY [M, Np] W [Np, Kp]
+  auto input_grad = [&](const float* dy, int Np, const void* W, int Kp, float* out) -> zgr_status {
+    if (v.mfma) {
+      const int Npad = (Np + 63) & ~63;                          // zeros in both operands past Np
+      HIP_TRY(c, launch_bw_round_bf16(dy, M, Np, Np, tA, Npad, s));
+      HIP_TRY(c, launch_bw_transpose_bf16(1, W, Np, Kp, Kp, tW, Npad, s));
+      HIP_TRY(c, launch_gemm(ZGR_BF16, tA, tW, nullptr, out, EPI_F32, M, Kp, Npad, s));
+    } else {
+      HIP_TRY(c, launch_bw_gemm(dt, dy, Np, 1, W, Kp, 1, out, Kp, M, Kp, Np, 1.0f, 0, s));
+    }
+    return ZGR_OK;
+  };
+  // y = a W^T + bias with a [M, Kp] kept in the storage type and dy = columns of a row-major array with row stride ldy:
+  // dW [Np, Kp] = dy^T a, dbias = column sums of dy
+  auto param_grads = [&](const float* dy, int64_t ldy, const void* a, int Np, int Kp, float* dW, float* dbias) -> zgr_status {
+    if (v.mfma) {
+      HIP_TRY(c, launch_bw_transpose_bf16(0, dy, M, Np, ldy, tA, M, s));
+      if (tB_holds != a) { HIP_TRY(c, launch_bw_transpose_bf16(1, a, M, Kp, Kp, tB, M, s)); tB_holds = a; }
+      HIP_TRY(c, launch_gemm(ZGR_BF16, tA, tB, nullptr, dW, EPI_F32, Np, Kp, M, s));
+    } else {
+      HIP_TRY(c, launch_bw_gemm(dt, dy, 1, ldy, a, Kp, 1, dW, Kp, Np, Kp, M, 1.0f, 0, s));
+    }
+    if (dbias) HIP_TRY(c, launch_bw_colsum(dy, M, Np, ldy, dbias, F(v.part), s));
+    return ZGR_OK;
+  };
   // ---- forward, every layer's intermediate results kept
   HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), F(v.layer.empty() ? v.xfin : v.layer[0].xin), M, Tn, d, m.vocab, s));
   for (int l = 0; l < m.n_layer; ++l) {
@@ -983,8 +1019,8 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     HIP_TRY(c, launch_mean_f64(F(v.row_loss), M, inv_n, loss_dev, s));
     HIP_TRY(c, launch_bw_cross_entropy(logits, tgt, M, m.vocab, (float)inv_n, s));
     // tied head: logits = hf E^T, so dE = dlogits^T hf (the embedding rule adds its share below), dhf = dlogits E
-    HIP_TRY(c, launch_bw_gemm(dt, logits, 1, m.vocab, ws + v.hf, d, 1, grads[c->tok_emb], d, m.vocab, d, M, 1.0f, 0, s));
-    HIP_TRY(c, launch_bw_gemm(dt, logits, m.vocab, 1, T(c, c->tok_emb), d, 1, dtb, d, M, d, m.vocab, 1.0f, 0, s));
+    if ((st = param_grads(logits, m.vocab, ws + v.hf, m.vocab, d, grads[c->tok_emb], nullptr)) != ZGR_OK) return st;
+    if ((st = input_grad(logits, m.vocab, T(c, c->tok_emb), d, dtb)) != ZGR_OK) return st;
   } else {
     const int32_t* labels = reinterpret_cast<const int32_t*>(b->y);
     const int C = m.n_class;
@@ -994,12 +1030,12 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     HIP_TRY(c, launch_bw_cross_entropy(logits, labels, B, C, 1.0f / (float)B, s));
     // the head reads the first token of each sequence: rows b T of hf
     HIP_TRY(c, launch_bw_gemm(dt, logits, 1, C, ws + v.hf, (int64_t)Tn * d, 1, grads[c->cls_w], d, C, d, B, 1.0f, 0, s));
-    HIP_TRY(c, launch_bw_colsum(logits, B, C, C, grads[c->cls_b], s));
+    HIP_TRY(c, launch_bw_colsum(logits, B, C, C, grads[c->cls_b], F(v.part), s));
     HIP_TRY(c, launch_bw_fill(dtb, (int64_t)M * d, 0.f, s));
     HIP_TRY(c, launch_bw_gemm(dt, logits, C, 1, T(c, c->cls_w), d, 1, dtb, (int64_t)Tn * d, B, d, C, 1.0f, 0, s));
     HIP_TRY(c, launch_bw_fill(grads[c->tok_emb], (int64_t)m.vocab * d, 0.f, s));
   }
-  HIP_TRY(c, launch_bw_layernorm(dt, F(v.xfin), T(c, c->lnf_g), dtb, nullptr, dx, F(v.stats), grads[c->lnf_g], grads[c->lnf_b], M, d, m.ln_eps, s));
+  HIP_TRY(c, launch_bw_layernorm(dt, F(v.xfin), T(c, c->lnf_g), dtb, nullptr, dx, F(v.stats), grads[c->lnf_g], grads[c->lnf_b], F(v.part), M, d, m.ln_eps, s));
   // ---- the blocks in reverse; dx holds dL/d(residual stream) at the block's output
   for (int l = m.n_layer - 1; l >= 0; --l) {
     const Layer& L = c->layers[l];
@@ -1007,23 +1043,23 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     float* dff = F(v.dff);
     float* dqkv = F(v.dqkv);
     // x_out = x_mid + f W2^T + b2
-    if ((st = linear_param_grads(c, dx, d, ws + W.f, M, d, ff, grads[L.w2], grads[L.b2])) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_gemm(dt, dx, d, 1, T(c, L.w2), ff, 1, dff, ff, M, ff, d, 1.0f, 0, s));
+    if ((st = param_grads(dx, d, ws + W.f, d, ff, grads[L.w2], grads[L.b2])) != ZGR_OK) return st;
+    if ((st = input_grad(dx, d, T(c, L.w2), ff, dff)) != ZGR_OK) return st;
     HIP_TRY(c, launch_bw_gelu(F(W.u), dff, (int64_t)M * ff, s));
     // u = h2 W1^T + b1
-    if ((st = linear_param_grads(c, dff, ff, ws + W.h2, M, ff, d, grads[L.w1], grads[L.b1])) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_gemm(dt, dff, ff, 1, T(c, L.w1), d, 1, dtb, d, M, d, ff, 1.0f, 0, s));
-    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xmid), T(c, L.ln2_g), dtb, dx, dx, F(v.stats), grads[L.ln2_g], grads[L.ln2_b], M, d, m.ln_eps, s));
+    if ((st = param_grads(dff, ff, ws + W.h2, ff, d, grads[L.w1], grads[L.b1])) != ZGR_OK) return st;
+    if ((st = input_grad(dff, ff, T(c, L.w1), d, dtb)) != ZGR_OK) return st;
+    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xmid), T(c, L.ln2_g), dtb, dx, dx, F(v.stats), grads[L.ln2_g], grads[L.ln2_b], F(v.part), M, d, m.ln_eps, s));
     // x_mid = x_in + ctx Wo^T + bo
-    if ((st = linear_param_grads(c, dx, d, ws + W.ctx, M, d, d, grads[L.wo], grads[L.bo])) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_gemm(dt, dx, d, 1, T(c, L.wo), d, 1, dtb, d, M, d, d, 1.0f, 0, s));
+    if ((st = param_grads(dx, d, ws + W.ctx, d, d, grads[L.wo], grads[L.bo])) != ZGR_OK) return st;
+    if ((st = input_grad(dx, d, T(c, L.wo), d, dtb)) != ZGR_OK) return st;
     HIP_TRY(c, launch_bw_attention(dt, ws + W.qkv, dtb, lengths, B, Tn, d, H, lm ? 1 : 0, F(v.P), F(v.dS), dqkv, s));
     // q, k, v = h1 W{q,k,v}^T + b{q,k,v}: three column blocks of dqkv; Wq, Wk, Wv are adjacent, one [3 d, d] matrix
     const int wi[3] = {L.wq, L.wk, L.wv}, bi[3] = {L.bq, L.bk, L.bv};
     for (int p = 0; p < 3; ++p)
-      if ((st = linear_param_grads(c, dqkv + (size_t)p * d, 3 * d, ws + W.h1, M, d, d, grads[wi[p]], grads[bi[p]])) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_gemm(dt, dqkv, 3 * d, 1, T(c, L.wq), d, 1, dtb, d, M, d, 3 * d, 1.0f, 0, s));
-    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xin), T(c, L.ln1_g), dtb, dx, dx, F(v.stats), grads[L.ln1_g], grads[L.ln1_b], M, d, m.ln_eps, s));
+      if ((st = param_grads(dqkv + (size_t)p * d, 3 * d, ws + W.h1, d, d, grads[wi[p]], grads[bi[p]])) != ZGR_OK) return st;
+    if ((st = input_grad(dqkv, 3 * d, T(c, L.wq), d, dtb)) != ZGR_OK) return st;
+    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xin), T(c, L.ln1_g), dtb, dx, dx, F(v.stats), grads[L.ln1_g], grads[L.ln1_b], F(v.part), M, d, m.ln_eps, s));
   }
   HIP_TRY(c, launch_bw_embedding(tok, dx, M, Tn, d, m.vocab, grads[c->tok_emb], grads[c->pos_emb], m.max_pos, s));
   HIP_TRY(c, hipMemcpyAsync(c->host_loss, loss_dev, sizeof(double), hipMemcpyDeviceToHost, s));

@@ -52,10 +52,19 @@ __device__ __forceinline__ float block_max(float v, float* red) {
 // type (a weight or a kept activation).  64 x 64 tile, 16 deep, 4 x 4 outputs per thread.  The two uses:
 //   input gradient   dA [M, K'] = dY [M, N'] W [N', K']      : A = dY (ars = N', acs = 1), B = W  (brs = K', bcs = 1)
 //   weight gradient  dW [N', K'] = dY^T [N', M] A_in [M, K'] : A = dY (ars = 1, acs = N'), B = A_in (brs = K', bcs = 1)
+// Batched over blockIdx.z = z: operand X of batch z starts at X + (z / zdiv) * x_outer + (z % zdiv) * x_inner (elements).
+struct BatchOffsets { int zdiv; int64_t a_outer, a_inner, b_outer, b_inner, c_outer, c_inner; };
+
 template <typename TB>
 __global__ void __launch_bounds__(256) gemm_strided_kernel(const float* __restrict__ A, int64_t ars, int64_t acs, const TB* __restrict__ B, int64_t brs, int64_t bcs,
-                                                           float* __restrict__ C, int64_t ldc, int M, int N, int K, float alpha, int accumulate) {
+                                                           float* __restrict__ C, int64_t ldc, int M, int N, int K, float alpha, int accumulate, BatchOffsets bo) {
   __shared__ float As[16][64 + 4], Bs[16][64 + 4];
+  {
+    const int zo = (int)blockIdx.z / bo.zdiv, zi = (int)blockIdx.z % bo.zdiv;
+    A += zo * bo.a_outer + zi * bo.a_inner;
+    B += zo * bo.b_outer + zi * bo.b_inner;
+    C += zo * bo.c_outer + zi * bo.c_inner;
+  }
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const bool a_rows_contig = ars == 1, b_k_contig = brs == 1;       // which index consecutive threads should walk
@@ -87,16 +96,56 @@ __global__ void __launch_bounds__(256) gemm_strided_kernel(const float* __restri
     }
 }
 
-// out[n] = sum_m Y[m ld + n]  (bias gradients): 64 columns per block, 4 row groups, rows in increasing order per group
-__global__ void __launch_bounds__(256) colsum_kernel(const float* __restrict__ Y, int M, int N, int64_t ld, float* __restrict__ out) {
-  __shared__ float part[4][64];
+// ------------------------------------------------------------------ operands for the matrix-core products (bf16 models)
+// The bf16 GEMM of the forward pass computes A W^T with both operands contiguous along the contraction.  A backward
+// product contracts over another index, so its operands are first written out in bf16 with that index innermost:
+//   out[c][r] = in[r][c]   (transpose, 64 x 64 tiles through LDS)      or      out[r][c] = in[r][c]   (rounding only)
+// Elements [rows, ld_out) of every output row (transpose) and [cols, ld_out) (rounding) are written as zeros: padding of the
+// contraction up to the multiple of 64 the GEMM asks for.
+template <typename TIN>
+__global__ void __launch_bounds__(256) transpose_bf16_kernel(const TIN* __restrict__ in, int rows, int cols, int64_t ld_in, bf16_t* __restrict__ out, int64_t ld_out) {
+  __shared__ float tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int r = i >> 6, c = i & 63;
+    tile[r][c] = (r0 + r < rows && c0 + c < cols) ? to_f32(in[(int64_t)(r0 + r) * ld_in + c0 + c]) : 0.f;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int c = i >> 6, r = i & 63;
+    if (r0 + r < ld_out && c0 + c < cols) from_f32(tile[r][c], out[(int64_t)(c0 + c) * ld_out + r0 + r]);      // tile holds zeros past `rows`
+  }
+}
+__global__ void __launch_bounds__(256) round_bf16_kernel(const float* __restrict__ in, int rows, int cols, int64_t ld_in, bf16_t* __restrict__ out, int64_t ld_out) {
+  const int64_t n = (int64_t)rows * ld_out;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / ld_out, c = i % ld_out;
+    from_f32(c < cols ? in[r * ld_in + c] : 0.f, out[i]);
+  }
+}
+
+// out[n] = sum_m Y[m ld + n]  (bias gradients), in two stages with a fixed shape so that the order of the additions
+// never depends on scheduling: kColParts row chunks are summed side by side (64 columns per block, 4 row groups),
+// then the chunk sums are added in chunk order.
+constexpr int kColParts = 64;
+__global__ void __launch_bounds__(256) colsum_partial_kernel(const float* __restrict__ Y, int M, int N, int64_t ld, float* __restrict__ part) {
+  __shared__ float acc[4][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
+  const int chunk = (M + kColParts - 1) / kColParts;
+  const int m_begin = blockIdx.y * chunk, m_end = min(M, m_begin + chunk);
   float s = 0.f;
   if (c < N)
-    for (int m = g; m < M; m += 4) s += Y[(int64_t)m * ld + c];
-  part[g][threadIdx.x & 63] = s;
+    for (int m = m_begin + g; m < m_end; m += 4) s += Y[(int64_t)m * ld + c];
+  acc[g][threadIdx.x & 63] = s;
   __syncthreads();
-  if (g == 0 && c < N) out[c] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+  if (g == 0 && c < N) part[(size_t)blockIdx.y * N + c] = (acc[0][threadIdx.x] + acc[1][threadIdx.x]) + (acc[2][threadIdx.x] + acc[3][threadIdx.x]);
+}
+__global__ void __launch_bounds__(256) colsum_final_kernel(const float* __restrict__ part, int N, float* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= N) return;
+  float s = 0.f;
+  for (int p = 0; p < kColParts; ++p) s += part[(size_t)p * N + c];
+  out[c] = s;
 }
 
 __global__ void __launch_bounds__(256) fill_kernel(float* __restrict__ p, int64_t n, float v) {
@@ -155,14 +204,17 @@ __global__ void __launch_bounds__(256) ln_backward_kernel(const float* __restric
   if (threadIdx.x == 0) { stats[2 * blockIdx.x] = mu; stats[2 * blockIdx.x + 1] = rstd; }
 }
 
-// dg[c] = sum_m dy[m][c] xhat[m][c], db[c] = sum_m dy[m][c]
-__global__ void __launch_bounds__(256) ln_param_grad_kernel(const float* __restrict__ x, const float* __restrict__ dy, const float* __restrict__ stats,
-                                                            int M, int d, float* __restrict__ dg, float* __restrict__ db) {
+// dg[c] = sum_m dy[m][c] xhat[m][c], db[c] = sum_m dy[m][c]: chunk sums as above (part: [2][kColParts][d]), then
+// colsum_final_kernel on each half
+__global__ void __launch_bounds__(256) ln_param_grad_partial_kernel(const float* __restrict__ x, const float* __restrict__ dy, const float* __restrict__ stats,
+                                                                    int M, int d, float* __restrict__ part) {
   __shared__ float pg[4][64], pb[4][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63), grp = threadIdx.x >> 6;
+  const int chunk = (M + kColParts - 1) / kColParts;
+  const int m_begin = blockIdx.y * chunk, m_end = min(M, m_begin + chunk);
   float sg = 0.f, sb = 0.f;
   if (c < d)
-    for (int m = grp; m < M; m += 4) {
+    for (int m = m_begin + grp; m < m_end; m += 4) {
       const float dyv = dy[(size_t)m * d + c];
       sg += dyv * ((x[(size_t)m * d + c] - stats[2 * m]) * stats[2 * m + 1]);
       sb += dyv;
@@ -170,8 +222,8 @@ __global__ void __launch_bounds__(256) ln_param_grad_kernel(const float* __restr
   pg[grp][threadIdx.x & 63] = sg; pb[grp][threadIdx.x & 63] = sb;
   __syncthreads();
   if (grp == 0 && c < d) {
-    dg[c] = (pg[0][threadIdx.x] + pg[1][threadIdx.x]) + (pg[2][threadIdx.x] + pg[3][threadIdx.x]);
-    db[c] = (pb[0][threadIdx.x] + pb[1][threadIdx.x]) + (pb[2][threadIdx.x] + pb[3][threadIdx.x]);
+    part[(size_t)blockIdx.y * d + c] = (pg[0][threadIdx.x] + pg[1][threadIdx.x]) + (pg[2][threadIdx.x] + pg[3][threadIdx.x]);
+    part[(size_t)(kColParts + blockIdx.y) * d + c] = (pb[0][threadIdx.x] + pb[1][threadIdx.x]) + (pb[2][threadIdx.x] + pb[3][threadIdx.x]);
   }
 }
 
@@ -198,7 +250,7 @@ __global__ void __launch_bounds__(256) gelu_backward_kernel(const float* __restr
 // softmax when j < length (the sequence's length, or T) and, under the causal mask, j <= i.
 //
 // Per query row (one block per (b, h, i)): p = softmax(q k^T / sqrt dh), dp_j = dctx_i . v_j, ds = p (dp - p . dp);
-// P and dS rows (zeros at masked keys) go to memory for the key-side kernel, dq_i = sum_j ds_j k_j / sqrt dh.
+// P and dS rows (zeros at masked keys) go to memory for the key-side products, dq_i = sum_j ds_j k_j / sqrt dh.
 template <typename T>
 __global__ void __launch_bounds__(256) attn_backward_query_kernel(const T* __restrict__ qkv, const float* __restrict__ dctx, const int32_t* __restrict__ lengths,
                                                                   int seq, int d, int n_head, int dh, int causal, float* __restrict__ P, float* __restrict__ dS,
@@ -263,26 +315,7 @@ __global__ void __launch_bounds__(256) attn_backward_query_kernel(const T* __res
   }
 }
 
-// Per key row (one block per (b, h, j)): dk_j = sum_i dS[i][j] q_i / sqrt dh, dv_j = sum_i P[i][j] dctx_i.
-template <typename T>
-__global__ void __launch_bounds__(128) attn_backward_key_kernel(const T* __restrict__ qkv, const float* __restrict__ dctx, int seq, int d, int n_head, int dh,
-                                                                const float* __restrict__ P, const float* __restrict__ dS, float* __restrict__ dqkv) {
-  const int j = blockIdx.x % seq, h = (blockIdx.x / seq) % n_head, b = blockIdx.x / (seq * n_head);
-  const size_t ld = (size_t)3 * d;
-  const T* base = qkv + (size_t)b * seq * ld + (size_t)h * dh;
-  const float scale = 1.0f / sqrtf((float)dh);
-  const float* pcol = P + ((size_t)b * n_head + h) * seq * seq + j;
-  const float* scol = dS + ((size_t)b * n_head + h) * seq * seq + j;
-  for (int t = threadIdx.x; t < dh; t += 128) {
-    float dk = 0.f, dv = 0.f;
-    for (int i = 0; i < seq; ++i) {
-      dk = __builtin_fmaf(scol[(size_t)i * seq], to_f32(base[(size_t)i * ld + t]), dk);
-      dv = __builtin_fmaf(pcol[(size_t)i * seq], dctx[((size_t)b * seq + i) * d + (size_t)h * dh + t], dv);
-    }
-    dqkv[((size_t)b * seq + j) * ld + d + (size_t)h * dh + t] = dk * scale;
-    dqkv[((size_t)b * seq + j) * ld + 2 * d + (size_t)h * dh + t] = dv;
-  }
-}
+// The key side, dK = dS^T Q / sqrt dh and dV = P^T dctx per head, are two batched products of gemm_strided_kernel.
 
 // ------------------------------------------------------------------ embeddings
 // x0[m] = E[tok[m]] + Pe[m mod seq]: one thread per column walks the rows in order (tokens repeat, so the adds into
@@ -305,17 +338,40 @@ __global__ void __launch_bounds__(256) embed_backward_kernel(const int32_t* __re
 
 static unsigned grid_1d(int64_t n) { const int64_t b = (n + 255) / 256; return (unsigned)(b < 1 ? 1 : (b > 4096 ? 4096 : b)); }
 
-hipError_t launch_bw_gemm(int b_dtype, const float* A, int64_t ars, int64_t acs, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
-                          int M, int N, int K, float alpha, int accumulate, hipStream_t s) {
-  if (M < 1 || N < 1) return hipSuccess;
-  const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
-  if (b_dtype == 1) hipLaunchKernelGGL(gemm_strided_kernel<bf16_t>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const bf16_t*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate);
-  else              hipLaunchKernelGGL(gemm_strided_kernel<float>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const float*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate);
+static hipError_t launch_bw_gemm_batched(int b_dtype, const float* A, int64_t ars, int64_t acs, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
+                                         int M, int N, int K, float alpha, int accumulate, int batches, const BatchOffsets& bo, hipStream_t s) {
+  if (M < 1 || N < 1 || batches < 1) return hipSuccess;
+  if (batches > 65535) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64), (unsigned)batches);
+  if (b_dtype == 1) hipLaunchKernelGGL(gemm_strided_kernel<bf16_t>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const bf16_t*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate, bo);
+  else              hipLaunchKernelGGL(gemm_strided_kernel<float>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const float*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate, bo);
   return hipGetLastError();
 }
 
-hipError_t launch_bw_colsum(const float* Y, int M, int N, int64_t ld, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, s, Y, M, N, ld, out);
+hipError_t launch_bw_gemm(int b_dtype, const float* A, int64_t ars, int64_t acs, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
+                          int M, int N, int K, float alpha, int accumulate, hipStream_t s) {
+  return launch_bw_gemm_batched(b_dtype, A, ars, acs, B, brs, bcs, C, ldc, M, N, K, alpha, accumulate, 1, BatchOffsets{1, 0, 0, 0, 0, 0, 0}, s);
+}
+
+hipError_t launch_bw_transpose_bf16(int in_dtype, const void* in, int rows, int cols, int64_t ld_in, void* out, int64_t ld_out, hipStream_t s) {
+  if (rows < 1 || cols < 1) return hipSuccess;
+  const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((ld_out + 63) / 64));
+  if (in_dtype == 1) hipLaunchKernelGGL(transpose_bf16_kernel<bf16_t>, grid, dim3(256), 0, s, reinterpret_cast<const bf16_t*>(in), rows, cols, ld_in, reinterpret_cast<bf16_t*>(out), ld_out);
+  else               hipLaunchKernelGGL(transpose_bf16_kernel<float>, grid, dim3(256), 0, s, reinterpret_cast<const float*>(in), rows, cols, ld_in, reinterpret_cast<bf16_t*>(out), ld_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_round_bf16(const float* in, int rows, int cols, int64_t ld_in, void* out, int64_t ld_out, hipStream_t s) {
+  if (rows < 1 || cols < 1) return hipSuccess;
+  hipLaunchKernelGGL(round_bf16_kernel, dim3(grid_1d((int64_t)rows * ld_out)), dim3(256), 0, s, in, rows, cols, ld_in, reinterpret_cast<bf16_t*>(out), ld_out);
+  return hipGetLastError();
+}
+
+size_t bw_colsum_scratch_floats(int n_max) { return (size_t)2 * kColParts * (size_t)n_max; }
+
+hipError_t launch_bw_colsum(const float* Y, int M, int N, int64_t ld, float* out, float* part, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)((N + 63) / 64), kColParts), dim3(256), 0, s, Y, M, N, ld, part);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, part, N, out);
   return hipGetLastError();
 }
 
@@ -331,12 +387,14 @@ hipError_t launch_bw_cross_entropy(float* logits, const int32_t* targets, int ro
 }
 
 hipError_t launch_bw_layernorm(int dtype, const float* x, const void* g, const float* dy, const float* add, float* dx_out, float* stats, float* dg, float* db,
-                               int M, int d, float eps, hipStream_t s) {
+                               float* part, int M, int d, float eps, hipStream_t s) {
   if (dtype == 1) hipLaunchKernelGGL(ln_backward_kernel<bf16_t>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const bf16_t*>(g), dy, add, dx_out, stats, d, eps);
   else            hipLaunchKernelGGL(ln_backward_kernel<float>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const float*>(g), dy, add, dx_out, stats, d, eps);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(ln_param_grad_kernel, dim3((unsigned)((d + 63) / 64)), dim3(256), 0, s, x, dy, stats, M, d, dg, db);
+  hipLaunchKernelGGL(ln_param_grad_partial_kernel, dim3((unsigned)((d + 63) / 64), kColParts), dim3(256), 0, s, x, dy, stats, M, d, part);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s, part, d, dg);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s, part + (size_t)kColParts * d, d, db);
   return hipGetLastError();
 }
 
@@ -358,14 +416,18 @@ hipError_t launch_bw_attention(int dtype, const void* qkv, const float* dctx, co
   const size_t lds = (size_t)(2 * dh + seq) * sizeof(float);
   if (lds > 48 * 1024) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)batch * n_head * seq;
-  if (dtype == 1) {
-    hipLaunchKernelGGL(attn_backward_query_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const bf16_t*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
-    hipLaunchKernelGGL(attn_backward_key_kernel<bf16_t>, dim3(blocks), dim3(128), 0, s, reinterpret_cast<const bf16_t*>(qkv), dctx, seq, d, n_head, dh, P, dS, dqkv);
-  } else {
-    hipLaunchKernelGGL(attn_backward_query_kernel<float>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const float*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
-    hipLaunchKernelGGL(attn_backward_key_kernel<float>, dim3(blocks), dim3(128), 0, s, reinterpret_cast<const float*>(qkv), dctx, seq, d, n_head, dh, P, dS, dqkv);
-  }
-  return hipGetLastError();
+  if (dtype == 1) hipLaunchKernelGGL(attn_backward_query_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const bf16_t*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
+  else            hipLaunchKernelGGL(attn_backward_query_kernel<float>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const float*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // per head z = (b, h): dK [T, dh] = dS^T Q / sqrt dh, dV [T, dh] = P^T dctx; A(j, i) = X[i T + j]
+  const int64_t tt = (int64_t)seq * seq, ld = (int64_t)3 * d;
+  const float scale = 1.0f / sqrtf((float)dh);
+  BatchOffsets bk{n_head, n_head * tt, tt, (int64_t)seq * ld, dh, (int64_t)seq * ld, dh};
+  e = launch_bw_gemm_batched(dtype, dS, 1, seq, qkv, ld, 1, dqkv + d, ld, seq, dh, seq, scale, 0, batch * n_head, bk, s);
+  if (e != hipSuccess) return e;
+  BatchOffsets bv{n_head, n_head * tt, tt, (int64_t)seq * d, dh, (int64_t)seq * ld, dh};
+  return launch_bw_gemm_batched(0, P, 1, seq, dctx, d, 1, dqkv + 2 * d, ld, seq, dh, seq, 1.0f, 0, batch * n_head, bv, s);
 }
 
 hipError_t launch_bw_embedding(const int32_t* tok, const float* dx, int M, int seq, int d, int vocab, float* dE, float* dPe, int max_pos, hipStream_t s) {
