@@ -964,8 +964,9 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
   const void* tB_holds = nullptr;                       // the kept activation whose transpose tB holds
   // dA [M, Kp] = dY [M, Np] W [Np, Kp]
   auto input_grad = [&](const float* dy, int Np, const void* W, int Kp, float* out) -> zgr_status {
-    if (v.mfma) {
-      const int Npad = (Np + 63) & ~63;                          // zeros in both operands past Np
+    const size_t lim = (size_t)1 << 31;                          // the GEMM addresses its operands with 32-bit offsets
+    const int Npad = (Np + 63) & ~63;                            // zeros in both operands past Np
+    if (v.mfma && (size_t)M * Npad < lim && (size_t)Kp * Npad < lim) {
       HIP_TRY(c, launch_bw_round_bf16(dy, M, Np, Np, tA, Npad, s));
       HIP_TRY(c, launch_bw_transpose_bf16(1, W, Np, Kp, Kp, tW, Npad, s));
       HIP_TRY(c, launch_gemm(ZGR_BF16, tA, tW, nullptr, out, EPI_F32, M, Kp, Npad, s));
@@ -977,7 +978,8 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
   // y = a W^T + bias with a [M, Kp] kept in the storage type and dy = columns of a row-major array with row stride ldy:
   // dW [Np, Kp] = dy^T a, dbias = column sums of dy
   auto param_grads = [&](const float* dy, int64_t ldy, const void* a, int Np, int Kp, float* dW, float* dbias) -> zgr_status {
-    if (v.mfma) {
+    const size_t lim = (size_t)1 << 31;
+    if (v.mfma && (size_t)Np * M < lim && (size_t)Kp * M < lim) {
       HIP_TRY(c, launch_bw_transpose_bf16(0, dy, M, Np, ldy, tA, M, s));
       if (tB_holds != a) { HIP_TRY(c, launch_bw_transpose_bf16(1, a, M, Kp, Kp, tB, M, s)); tB_holds = a; }
       HIP_TRY(c, launch_gemm(ZGR_BF16, tA, tB, nullptr, dW, EPI_F32, Np, Kp, M, s));

@@ -122,6 +122,20 @@ def test_bf16_gradients_at_the_size_of_a_real_model(say):
     say(f"worst cosine {worst[0]:.5f} at {worst[1]}")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_runs_agree_bit_for_bit(dtype):
+    """No sum of the backward pass depends on scheduling: the same call twice gives the same bits."""
+    from tests.util import session_batch
+    cfg = I.shrink(I.CONFIGS["cfg3"], name="bw_det", dtype=dtype, n_layer=2, d_model=128, n_head=2, d_ff=256, vocab=389, max_pos=64, batch=4, seq=64, k=8, k_full=8)
+    sess, specs, P = _setup(cfg, scale=3.0)
+    batch = session_batch(sess, cfg, _batch(cfg, 5))
+    l1, g1 = sess.cloud_backward(batch)
+    l2, g2 = sess.cloud_backward(batch)
+    assert l1 == l2
+    for a, b, s_ in zip(g1, g2, specs):
+        assert bool((a == b).all()), s_.name
+
+
 def test_lsq_gradient_through_the_same_entry_point():
     cfg = I.CONFIGS["cfg1"]
     sess, specs, P = _setup(cfg, scale=1.0)
