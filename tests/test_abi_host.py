@@ -155,3 +155,12 @@ def test_cloud_entry_points_validate_their_arguments_without_a_gpu():
     assert lib.zgr_cloud_backward_workspace(None, 4, 16) == 0
     v = C.c_double()
     assert lib.zgr_cloud_backward(None, None, None, 0, C.byref(v), None, 0) == B.ZGR_ERR_NULL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is all the library runs on: the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
