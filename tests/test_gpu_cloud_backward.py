@@ -98,16 +98,18 @@ def test_bf16_gradients_point_where_the_oracle_gradients_point(batch, seq, say):
         assert cos >= 0.995 and abs(ratio - 1.0) <= 0.05, (s.name, cos, ratio)
 
 
-@pytest.mark.timeout(600)
-def test_bf16_gradients_at_the_size_of_a_real_model(say):
-    """cfg3 (12 blocks of d = 768, the 50272-word vocabulary) on two of its sequences: every tensor's gradient against the
-    oracle's.  Twelve blocks of bf16-rounded activations leave a few per cent: direction and norm are what is asked."""
-    cfg = I.shrink(I.CONFIGS["cfg3"], name="bw_cfg3", batch=2)
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,batch", [("cfg3", 2), ("cfg5", 1)])
+def test_bf16_gradients_at_the_size_of_a_real_model(name, batch, say):
+    """cfg3 (12 blocks of d = 768) on two of its sequences and cfg5 (24 blocks of d = 2048, the benchmark's model) on one,
+    both with the 50272-word vocabulary: every tensor's gradient against the oracle's.  The blocks' bf16-rounded
+    activations leave a few per cent: direction and norm are what is asked."""
+    cfg = I.shrink(I.CONFIGS[name], name="bw_" + name, batch=batch)
     sess, specs, P = _setup(cfg, scale=1.0)
     arrays = _batch(cfg, 0)
-    say("cloud backward at cfg3, 2 sequences: device")
+    say(f"cloud backward at {name}, {batch} sequence(s): device")
     loss, grads = _device(sess, cfg, arrays)
-    say("cloud backward at cfg3, 2 sequences: oracle")
+    say(f"cloud backward at {name}, {batch} sequence(s): oracle")
     loss_or, grads_or = _oracle(cfg, P, arrays)
     assert abs(loss - loss_or) <= 1e-2 * abs(loss_or)
     worst = (1.0, None)
