@@ -70,14 +70,26 @@ def _merge(xh):
     return xh.transpose(0, 2, 1, 3).reshape(B, T, H * dh)
 
 
-def _trunk_fwd(P, tokens, n_layer, n_head, causal, lengths, ln_eps):
+def _act_fwd(u, act):
+    return F.gelu(u) if act == "gelu" else F.relu(u)
+
+
+def _act_grad(u, act):
+    return _gelu_grad(u) if act == "gelu" else (u > 0).astype(np.float64)
+
+
+def _trunk_fwd(P, tokens, n_layer, n_head, causal, lengths, ln_eps, act="gelu", post_ln=False):
+    """Forward of forward.trunk keeping what the backward rules need.  post_ln: see oracle/forward.py."""
     tokens = np.asarray(tokens)
     B, T = tokens.shape
     x = P["tok_emb"][tokens] + P["pos_emb"][:T][None]
+    c_emb = None
+    if post_ln:
+        x, c_emb = _ln_fwd(x, P["lnf_g"], P["lnf_b"], ln_eps)
     caches = []
     for l in range(n_layer):
         g = lambda n: P[f"l{l}.{n}"]
-        h1, c1 = _ln_fwd(x, g("ln1_g"), g("ln1_b"), ln_eps)
+        h1, c1 = (x, None) if post_ln else _ln_fwd(x, g("ln1_g"), g("ln1_b"), ln_eps)
         q = h1 @ g("wq").T + g("bq").reshape(-1)
         k = h1 @ g("wk").T + g("bk").reshape(-1)
         v = h1 @ g("wv").T + g("bv").reshape(-1)
@@ -92,35 +104,52 @@ def _trunk_fwd(P, tokens, n_layer, n_head, causal, lengths, ln_eps):
         p = np.exp(F.log_softmax(s))
         a = _merge(p @ vh)
         x1 = x + a @ g("wo").T + g("bo").reshape(-1)
-        h2, c2 = _ln_fwd(x1, g("ln2_g"), g("ln2_b"), ln_eps)
+        if post_ln:
+            x1, c1 = _ln_fwd(x1, g("ln1_g"), g("ln1_b"), ln_eps)
+        h2, c2 = (x1, None) if post_ln else _ln_fwd(x1, g("ln2_g"), g("ln2_b"), ln_eps)
         u = h2 @ g("w1").T + g("b1").reshape(-1)
-        f = F.gelu(u)
+        f = _act_fwd(u, act)
         x2 = x1 + f @ g("w2").T + g("b2").reshape(-1)
+        if post_ln:
+            x2, c2 = _ln_fwd(x2, g("ln2_g"), g("ln2_b"), ln_eps)
         caches.append((h1, c1, qh, kh, vh, p, a, h2, c2, u, f))
         x = x2
+    if post_ln:
+        return x, c_emb, caches
     hf, cf = _ln_fwd(x, P["lnf_g"], P["lnf_b"], ln_eps)
     return hf, cf, caches
 
 
-def _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads):
+def _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads, act="gelu", post_ln=False):
+    """cf: what _trunk_fwd returned second (the final LayerNorm's cache, or the embedding LayerNorm's with post_ln)."""
     tokens = np.asarray(tokens)
     B, T = tokens.shape
-    dx, dg, db = _ln_bwd(dhf, cf, P["lnf_g"])
-    grads["lnf_g"], grads["lnf_b"] = dg.reshape(1, -1), db.reshape(1, -1)
+    if post_ln:
+        dx = dhf
+    else:
+        dx, dg, db = _ln_bwd(dhf, cf, P["lnf_g"])
+        grads["lnf_g"], grads["lnf_b"] = dg.reshape(1, -1), db.reshape(1, -1)
     for l in reversed(range(n_layer)):
         g = lambda n: P[f"l{l}.{n}"]
         h1, c1, qh, kh, vh, p, a, h2, c2, u, f = caches[l]
         dh_scale = 1.0 / np.sqrt(qh.shape[-1])
-        # x2 = x1 + f W2^T + b2
+        if post_ln:                                                # x2 = LN2(y2), y2 = x1 + f W2^T + b2
+            dx, dg2, db2 = _ln_bwd(dx, c2, g("ln2_g"))
+            grads[f"l{l}.ln2_g"], grads[f"l{l}.ln2_b"] = dg2.reshape(1, -1), db2.reshape(1, -1)
+        # (pre-LN: x2 = x1 + f W2^T + b2)
         df, grads[f"l{l}.w2"], b2 = _linear_bwd(dx, f, g("w2"))
         grads[f"l{l}.b2"] = b2.reshape(1, -1)
-        du = df * _gelu_grad(u)
+        du = df * _act_grad(u, act)
         dh2, grads[f"l{l}.w1"], b1 = _linear_bwd(du, h2, g("w1"))
         grads[f"l{l}.b1"] = b1.reshape(1, -1)
-        d1, dg2, db2 = _ln_bwd(dh2, c2, g("ln2_g"))
-        grads[f"l{l}.ln2_g"], grads[f"l{l}.ln2_b"] = dg2.reshape(1, -1), db2.reshape(1, -1)
-        dx1 = dx + d1
-        # x1 = x + a Wo^T + bo
+        if post_ln:                                                # h2 = x1 = LN1(y1), y1 = x + a Wo^T + bo
+            dx1, dg1, db1 = _ln_bwd(dx + dh2, c1, g("ln1_g"))
+            grads[f"l{l}.ln1_g"], grads[f"l{l}.ln1_b"] = dg1.reshape(1, -1), db1.reshape(1, -1)
+        else:                                                      # h2 = LN2(x1)
+            d1, dg2, db2 = _ln_bwd(dh2, c2, g("ln2_g"))
+            grads[f"l{l}.ln2_g"], grads[f"l{l}.ln2_b"] = dg2.reshape(1, -1), db2.reshape(1, -1)
+            dx1 = dx + d1
+        # x1 (or y1) = x + a Wo^T + bo
         da, grads[f"l{l}.wo"], bo = _linear_bwd(dx1, a, g("wo"))
         grads[f"l{l}.bo"] = bo.reshape(1, -1)
         dah = _split(da, n_head)
@@ -134,10 +163,16 @@ def _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads):
             dpart, grads[f"l{l}.w{name}"], bb = _linear_bwd(_merge(dyh), h1, g("w" + name))
             grads[f"l{l}.b{name}"] = bb.reshape(1, -1)
             dh1 = dh1 + dpart
-        d0, dg1, db1 = _ln_bwd(dh1, c1, g("ln1_g"))
-        grads[f"l{l}.ln1_g"], grads[f"l{l}.ln1_b"] = dg1.reshape(1, -1), db1.reshape(1, -1)
-        dx = dx1 + d0
-    # x0 = tok_emb[tokens] + pos_emb[:T]
+        if post_ln:                                                # h1 = x
+            dx = dx1 + dh1
+        else:                                                      # h1 = LN1(x)
+            d0, dg1, db1 = _ln_bwd(dh1, c1, g("ln1_g"))
+            grads[f"l{l}.ln1_g"], grads[f"l{l}.ln1_b"] = dg1.reshape(1, -1), db1.reshape(1, -1)
+            dx = dx1 + d0
+    if post_ln:                                                    # x0 = LN_emb(embeddings)
+        dx, dg, db = _ln_bwd(dx, cf, P["lnf_g"])
+        grads["lnf_g"], grads["lnf_b"] = dg.reshape(1, -1), db.reshape(1, -1)
+    # embeddings: tok_emb[tokens] + pos_emb[:T]
     demb = np.zeros_like(P["tok_emb"])
     np.add.at(demb, tokens.reshape(-1), dx.reshape(-1, dx.shape[-1]))
     dpos = np.zeros_like(P["pos_emb"])
@@ -146,10 +181,10 @@ def _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads):
     grads["pos_emb"] = dpos
 
 
-def lm_loss_and_gradients(P, tokens, n_layer, n_head, ln_eps=1e-5):
+def lm_loss_and_gradients(P, tokens, n_layer, n_head, ln_eps=1e-5, act="gelu", post_ln=False):
     """(loss, {name: dL/dtensor}) of forward.lm_loss."""
     tokens = np.asarray(tokens)
-    hf, cf, caches = _trunk_fwd(P, tokens, n_layer, n_head, True, None, ln_eps)
+    hf, cf, caches = _trunk_fwd(P, tokens, n_layer, n_head, True, None, ln_eps, act, post_ln)
     E = P["tok_emb"]
     logp = F.log_softmax(hf[:, :-1] @ E.T)
     tgt = tokens[:, 1:].astype(np.int64)
@@ -161,14 +196,14 @@ def lm_loss_and_gradients(P, tokens, n_layer, n_head, ln_eps=1e-5):
     grads = {"tok_emb": dlogits.reshape(-1, E.shape[0]).T @ hf[:, :-1].reshape(-1, E.shape[1])}      # the tied head
     dhf = np.zeros_like(hf)
     dhf[:, :-1] = dlogits @ E
-    _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads)
+    _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads, act, post_ln)
     return loss, grads
 
 
-def cls_loss_and_gradients(P, tokens, lengths, labels, n_layer, n_head, ln_eps=1e-5):
+def cls_loss_and_gradients(P, tokens, lengths, labels, n_layer, n_head, ln_eps=1e-5, act="gelu", post_ln=False):
     """(loss, {name: dL/dtensor}) of forward.cls_loss."""
     tokens = np.asarray(tokens)
-    hf, cf, caches = _trunk_fwd(P, tokens, n_layer, n_head, False, lengths, ln_eps)
+    hf, cf, caches = _trunk_fwd(P, tokens, n_layer, n_head, False, lengths, ln_eps, act, post_ln)
     logits = hf[:, 0] @ P["cls_w"].T + P["cls_b"].reshape(-1)
     logp = F.log_softmax(logits)
     lab = np.asarray(labels).astype(np.int64)
@@ -179,7 +214,7 @@ def cls_loss_and_gradients(P, tokens, lengths, labels, n_layer, n_head, ln_eps=1
     grads = {"cls_w": dlogits.T @ hf[:, 0], "cls_b": dlogits.sum(axis=0).reshape(1, -1)}
     dhf = np.zeros_like(hf)
     dhf[:, 0] = dlogits @ P["cls_w"]
-    _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads)
+    _trunk_bwd(P, tokens, n_layer, n_head, dhf, cf, caches, grads, act, post_ln)
     return loss, grads
 
 

@@ -108,9 +108,9 @@ def make_lsq_loss(X, Y):
     return lambda P: F.lsq_loss(P["W"], X, Y)
 
 
-def make_lm_loss(tokens, n_layer, n_head, ln_eps=1e-5):
-    return lambda P: F.lm_loss(P, tokens, n_layer, n_head, ln_eps)
+def make_lm_loss(tokens, n_layer, n_head, ln_eps=1e-5, act="gelu", post_ln=False):
+    return lambda P: F.lm_loss(P, tokens, n_layer, n_head, ln_eps, act, post_ln)
 
 
-def make_cls_loss(tokens, lengths, labels, n_layer, n_head, ln_eps=1e-5):
-    return lambda P: F.cls_loss(P, tokens, lengths, labels, n_layer, n_head, ln_eps)
+def make_cls_loss(tokens, lengths, labels, n_layer, n_head, ln_eps=1e-5, act="gelu", post_ln=False):
+    return lambda P: F.cls_loss(P, tokens, lengths, labels, n_layer, n_head, ln_eps, act, post_ln)

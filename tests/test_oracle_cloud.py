@@ -13,7 +13,7 @@ from oracle import forward as F
 from tests.test_oracle_forward import TINY_CLS, TINY_LM, _params, _torch_trunk
 
 
-def _torch_loss_and_grads(cfg, P, tokens, lengths=None, labels=None):
+def _torch_loss_and_grads(cfg, P, tokens, lengths=None, labels=None, act="gelu", post_ln=False):
     """Re-runs the library-layer trunk of the forward pins with gradients enabled, parameters as leaves."""
     import torch.nn as nn
     d = cfg.d_model
@@ -22,21 +22,28 @@ def _torch_loss_and_grads(cfg, P, tokens, lengths=None, labels=None):
     B, T = tok.shape
     causal = cfg.arch == I.ARCH_DECODER_LM
     x = leaves["tok_emb"][tok] + leaves["pos_emb"][:T][None]
+    activation = TF.gelu if act == "gelu" else TF.relu
+    if post_ln:
+        x = TF.layer_norm(x, (d,), leaves["lnf_g"].reshape(-1), leaves["lnf_b"].reshape(-1), cfg.ln_eps)
     for l in range(cfg.n_layer):
         g = lambda n: leaves[f"l{l}.{n}"]
         mask = torch.triu(torch.ones(T, T, dtype=torch.bool), 1) if causal else None
         kpm = None
         if lengths is not None:
             kpm = torch.arange(T)[None, :] >= torch.tensor(np.asarray(lengths), dtype=torch.long)[:, None]
-        h = TF.layer_norm(x, (d,), g("ln1_g").reshape(-1), g("ln1_b").reshape(-1), cfg.ln_eps)
+        h = x if post_ln else TF.layer_norm(x, (d,), g("ln1_g").reshape(-1), g("ln1_b").reshape(-1), cfg.ln_eps)
         a, _ = TF.multi_head_attention_forward(
             h.transpose(0, 1), h.transpose(0, 1), h.transpose(0, 1), d, cfg.n_head,
             torch.cat([g("wq"), g("wk"), g("wv")], 0), torch.cat([g("bq"), g("bk"), g("bv")], 1).reshape(-1),
             None, None, False, 0.0, g("wo"), g("bo").reshape(-1), training=True, key_padding_mask=kpm, need_weights=False, attn_mask=mask)
         x = x + a.transpose(0, 1)
-        h = TF.layer_norm(x, (d,), g("ln2_g").reshape(-1), g("ln2_b").reshape(-1), cfg.ln_eps)
-        x = x + TF.linear(TF.gelu(TF.linear(h, g("w1"), g("b1").reshape(-1))), g("w2"), g("b2").reshape(-1))
-    hf = TF.layer_norm(x, (d,), leaves["lnf_g"].reshape(-1), leaves["lnf_b"].reshape(-1), cfg.ln_eps)
+        if post_ln:
+            x = TF.layer_norm(x, (d,), g("ln1_g").reshape(-1), g("ln1_b").reshape(-1), cfg.ln_eps)
+        h = x if post_ln else TF.layer_norm(x, (d,), g("ln2_g").reshape(-1), g("ln2_b").reshape(-1), cfg.ln_eps)
+        x = x + TF.linear(activation(TF.linear(h, g("w1"), g("b1").reshape(-1))), g("w2"), g("b2").reshape(-1))
+        if post_ln:
+            x = TF.layer_norm(x, (d,), g("ln2_g").reshape(-1), g("ln2_b").reshape(-1), cfg.ln_eps)
+    hf = x if post_ln else TF.layer_norm(x, (d,), leaves["lnf_g"].reshape(-1), leaves["lnf_b"].reshape(-1), cfg.ln_eps)
     if causal:
         logits = hf[:, :-1] @ leaves["tok_emb"].T
         loss = TF.cross_entropy(logits.reshape(-1, cfg.vocab), tok[:, 1:].reshape(-1))
@@ -75,6 +82,39 @@ def test_cls_backward_matches_autograd_through_library_layers():
     for k in P:
         scale = np.abs(tg[k]).max() + 1e-30
         assert np.abs(grads[k] - tg[k]).max() <= 1e-10 * scale + 1e-14, k
+
+
+@pytest.mark.parametrize("act,post_ln", [("relu", False), ("gelu", True), ("relu", True)])
+def test_backward_of_the_model_family_variants(act, post_ln):
+    """ReLU feed-forward and post-LayerNorm blocks: autograd through the library layers in the same order, and an
+    extrapolated central difference of the forward oracle along a whole-model direction."""
+    cfg = TINY_LM
+    P = _params(cfg, scale=15.0)
+    tokens = I.make_tokens(cfg)
+    loss, grads = C.lm_loss_and_gradients(P, tokens, cfg.n_layer, cfg.n_head, cfg.ln_eps, act, post_ln)
+    tl, tg = _torch_loss_and_grads(cfg, P, tokens, act=act, post_ln=post_ln)
+    assert np.isclose(loss, tl, rtol=1e-12) and np.isclose(loss, F.lm_loss(P, tokens, cfg.n_layer, cfg.n_head, cfg.ln_eps, act, post_ln), rtol=1e-13)
+    for k in P:
+        scale = np.abs(tg[k]).max() + 1e-30
+        assert np.abs(grads[k] - tg[k]).max() <= 1e-10 * scale + 1e-14, (k, np.abs(grads[k] - tg[k]).max(), scale)
+    cfgc = TINY_CLS
+    Pc = _params(cfgc, scale=15.0)
+    tok, labels = I.make_tokens(cfgc), I.make_labels(cfgc)
+    lengths = np.array([14, 5, 9, 1], dtype=np.int32)
+    lossc, gradsc = C.cls_loss_and_gradients(Pc, tok, lengths, labels, cfgc.n_layer, cfgc.n_head, cfgc.ln_eps, act, post_ln)
+    tlc, tgc = _torch_loss_and_grads(cfgc, Pc, tok, lengths, labels, act, post_ln)
+    assert np.isclose(lossc, tlc, rtol=1e-12)
+    for k in Pc:
+        scale = np.abs(tgc[k]).max() + 1e-30
+        assert np.abs(gradsc[k] - tgc[k]).max() <= 1e-10 * scale + 1e-14, k
+    if act == "gelu":                                    # smooth: the difference quotient converges
+        f = lambda Q: F.lm_loss(Q, tokens, cfg.n_layer, cfg.n_head, cfg.ln_eps, act, post_ln)
+        rng = np.random.default_rng(4)
+        D = {k: rng.standard_normal(v.shape) for k, v in P.items()}
+        want = sum(float((grads[k] * D[k]).sum()) for k in P)
+        cd = lambda h: (f({k: P[k] + h * D[k] for k in P}) - f({k: P[k] - h * D[k] for k in P})) / (2 * h)
+        fd = (4.0 * cd(1e-4) - cd(2e-4)) / 3.0
+        assert abs(fd - want) <= 1e-8 * max(1.0, abs(want)), (fd, want)
 
 
 @pytest.mark.parametrize("which", ["lm", "cls"])

@@ -32,15 +32,17 @@ def _params(cfg, scale=1.0):
 
 
 @torch.no_grad()
-def _torch_trunk(cfg, P, tokens, causal, lengths):
+def _torch_trunk(cfg, P, tokens, causal, lengths, act="gelu", post_ln=False):
     d = cfg.d_model
     tt = lambda a: torch.tensor(a, dtype=torch.float64)
     tok = torch.tensor(tokens, dtype=torch.long)
     B, T = tok.shape
     x = tt(P["tok_emb"])[tok] + tt(P["pos_emb"])[:T][None]
+    if post_ln:
+        x = TF.layer_norm(x, (d,), tt(P["lnf_g"]).reshape(-1), tt(P["lnf_b"]).reshape(-1), cfg.ln_eps)
     for l in range(cfg.n_layer):
-        layer = nn.TransformerEncoderLayer(d, cfg.n_head, cfg.d_ff, dropout=0.0, activation="gelu",
-                                           layer_norm_eps=cfg.ln_eps, batch_first=True, norm_first=True,
+        layer = nn.TransformerEncoderLayer(d, cfg.n_head, cfg.d_ff, dropout=0.0, activation=act,
+                                           layer_norm_eps=cfg.ln_eps, batch_first=True, norm_first=not post_ln,
                                            dtype=torch.float64)
         g = lambda n: tt(P[f"l{l}.{n}"])
         sd = {
@@ -59,6 +61,8 @@ def _torch_trunk(cfg, P, tokens, causal, lengths):
         if lengths is not None:
             kpm = torch.arange(T)[None, :] >= torch.tensor(lengths, dtype=torch.long)[:, None]
         x = layer(x, src_mask=mask, src_key_padding_mask=kpm)
+    if post_ln:
+        return x
     return TF.layer_norm(x, (d,), tt(P["lnf_g"]).reshape(-1), tt(P["lnf_b"]).reshape(-1), cfg.ln_eps)
 
 
@@ -87,6 +91,31 @@ def test_cls_loss_matches_torch_library_layers():
     got = F.cls_row_losses(P, tokens, lengths, labels, cfg.n_layer, cfg.n_head, cfg.ln_eps)
     assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
     assert np.isclose(F.cls_loss(P, tokens, lengths, labels, cfg.n_layer, cfg.n_head, cfg.ln_eps), want.mean(), rtol=1e-12)
+
+
+@pytest.mark.parametrize("act,post_ln", [("relu", False), ("gelu", True), ("relu", True)])
+def test_model_family_variants_match_torch_library_layers(act, post_ln):
+    """ReLU feed-forward and post-LayerNorm blocks (with the embedding LayerNorm) against the library layer built
+    with the same two switches, for the decoder loss and the classifier loss."""
+    cfg = TINY_LM
+    P = _params(cfg, scale=15.0)
+    tokens = I.make_tokens(cfg)
+    h = _torch_trunk(cfg, P, tokens, True, None, act, post_ln)
+    logits = h[:, :-1] @ torch.tensor(P["tok_emb"]).T
+    tgt = torch.tensor(tokens[:, 1:], dtype=torch.long)
+    want_tok = TF.cross_entropy(logits.reshape(-1, cfg.vocab), tgt.reshape(-1), reduction="none").reshape(tgt.shape).numpy()
+    got_tok = F.lm_token_losses(P, tokens, cfg.n_layer, cfg.n_head, cfg.ln_eps, act, post_ln)
+    assert np.allclose(got_tok, want_tok, rtol=1e-10, atol=1e-12)
+    assert not np.allclose(got_tok, F.lm_token_losses(P, tokens, cfg.n_layer, cfg.n_head, cfg.ln_eps), rtol=1e-3)   # the switches matter
+    cfgc = TINY_CLS
+    Pc = _params(cfgc, scale=15.0)
+    tok, labels = I.make_tokens(cfgc), I.make_labels(cfgc)
+    lengths = np.array([14, 5, 9, 1], dtype=np.int32)
+    hc = _torch_trunk(cfgc, Pc, tok, False, lengths, act, post_ln)
+    lc = hc[:, 0] @ torch.tensor(Pc["cls_w"]).T + torch.tensor(Pc["cls_b"]).reshape(-1)
+    want = TF.cross_entropy(lc, torch.tensor(labels, dtype=torch.long), reduction="none").numpy()
+    got = F.cls_row_losses(Pc, tok, lengths, labels, cfgc.n_layer, cfgc.n_head, cfgc.ln_eps, act, post_ln)
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
 
 
 def test_causality_and_padding_invariants():

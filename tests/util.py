@@ -17,8 +17,8 @@ def oracle_loss_fn(cfg, batch):
     if cfg.arch == I.ARCH_LINEAR_LSQ:
         return Z.make_lsq_loss(batch["x"], batch["y"])
     if cfg.arch == I.ARCH_DECODER_LM:
-        return Z.make_lm_loss(batch["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
-    return Z.make_cls_loss(batch["x"], batch["lengths"], batch["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        return Z.make_lm_loss(batch["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
+    return Z.make_cls_loss(batch["x"], batch["lengths"], batch["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
 
 
 def ulp_diff(got, want):

@@ -85,6 +85,8 @@ class Config:
     scale_mode: int = 0       # 0: unit-variance scaling of Eq. (10); 1: Eq. (10) as printed
     tokens: str = "uniform"   # "uniform" | "zipf"
     ln_eps: float = 1e-5
+    act: str = "gelu"         # feed-forward activation: "gelu" (erf form) | "relu"
+    post_ln: bool = False     # LayerNorm after each residual sum (and on the embeddings) instead of before each sublayer
 
 
 CONFIGS: Dict[str, Config] = {
