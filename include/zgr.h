@@ -92,10 +92,17 @@ typedef struct {
  * must be adjacent in memory in that order (one [3 d, d] matrix), and so must
  * bq, bk, bv.  LINEAR_LSQ: one fp32 tensor ZGR_ROLE_LSQ_W [out, in]; the other
  * fields are ignored.                                                           */
+/* The two model families of the paper's experiments (Sec. 4, models and datasets) differ in two textbook choices. */
+typedef enum { ZGR_ACT_GELU = 0, ZGR_ACT_RELU = 1 } zgr_act;   /* feed-forward activation: erf-GELU | ReLU */
+
 typedef struct {
   int32_t arch;            /* zgr_arch                                                         */
   int32_t n_layer, d_model, n_head, d_ff, vocab, max_pos, n_class;
   float   ln_eps;
+  int32_t act;             /* zgr_act                                                          */
+  int32_t post_ln;         /* 0: LayerNorm before each sublayer, final LayerNorm LNF before the head;
+                            * 1: LayerNorm after each residual sum, x <- LN(x + sublayer(x)), LNF applied to
+                            *    the embeddings, none before the head                           */
 } zgr_model;
 
 /* Hyper-parameters of Algorithm 1 ("Require" list). */
@@ -149,7 +156,7 @@ zgr_status zgr_init(zgr_ctx** out, const zgr_model* model, const zgr_tensor* ten
                     int32_t max_batch, int32_t max_seq, void* hip_stream);
 
 /* Guided round: install the basis the cloud sent for one tensor (Algorithm 1,
- * "broadcast guided perturbation"); U = NULL or k = 0 makes the tensor
+ * the cloud's broadcast in a guided round); U = NULL or k = 0 makes the tensor
  * isotropic (non-guided round).                                                */
 zgr_status zgr_set_basis(zgr_ctx* ctx, int32_t tensor_index, const float* U, int32_t k, int32_t ldu);
 
@@ -220,12 +227,12 @@ zgr_status zgr_dtc_omega(double data_bytes, double bandwidth_bytes_per_s, double
  * when a share omega travels and is held compressed.  HOST arithmetic.        */
 zgr_status zgr_dtc_memory_factor(int32_t n_layers, double omega, double theta, double* factor);
 
-/* ---- cloud block of Algorithm 1 ("perform BP on D_p; collect gradients to build basis V_r"; Sec. 3.2, "Guided
- * Perturbation Sampling on Cloud") ---- */
+/* ---- cloud block of Algorithm 1 (back-propagation on the public dataset, whose gradients build the basis;
+ * Sec. 3.2, paragraph on guided perturbation sampling on the cloud) ---- */
 /* The basis U [rows, k] (row stride ldu >= k, DEVICE, orthonormal columns) of one weight matrix from n_snap stored
  * gradient snapshots of it (snapshots: HOST array of n_snap DEVICE pointers, each fp32 [rows, cols] row-major): the
  * k-dimensional subspace of R^rows that captures the most of them, i.e. the span of the k leading left singular
- * vectors of [G_1 | ... | G_s] (the paper asks for "the orthonormal basis of the subspace of gradients" and does
+ * vectors of [G_1 | ... | G_s] (the paper asks for an orthonormal basis of the gradients' subspace and does
  * not say how a rank is chosen; this is the reading for a basis that acts on every column of the matrix).  Reached by
  * n_iter sweeps of block subspace iteration Q <- orth(sum_t G_t G_t^T Q) from Q = orth(sum_t G_t omega), omega
  * [cols, k] DEVICE fp32 being the caller's seeded standard-normal start; the subspace converges like
@@ -239,12 +246,13 @@ zgr_status zgr_cloud_basis(const float* const* snapshots, int32_t n_snap, int64_
  * workspace: DEVICE, batch * n_out floats.  Asynchronous.                                                            */
 zgr_status zgr_cloud_lsq_gradient(const float* W, const float* X, const float* Y, int32_t batch, int32_t n_out, int32_t n_in, float* G,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
-/* The cloud's backward pass over the context's model ("Perform BP on D_p with W^r; collect gradients", cloud block of
+/* The cloud's backward pass over the context's model (the back-propagation step of the cloud block of
  * Algorithm 1): *loss_out (HOST) = L(theta; batch) as zgr_loss defines it, and grads[i] (HOST array of n_grads = n_t
  * DEVICE pointers, caller-owned, each rows_i * cols_i fp32 row-major, overwritten) = dL/dtheta_i for every tensor the
  * context was created with, in fp32 whatever the storage type; theta itself is left untouched.  The forward half runs
  * the client's own kernels (so a bf16 model's intermediate results are bf16-rounded exactly as in zgr_loss, except
- * that GELU is evaluated from the fp32 pre-activation by its erf form) and keeps every layer's results in
+ * that the activation is evaluated from the fp32 pre-activation, GELU by its erf form); both activations and both
+ * LayerNorm placements of zgr_model are covered and keeps every layer's results in
  * `workspace` (DEVICE, 256-byte aligned, zgr_cloud_backward_workspace(ctx, batch, seq) bytes: it grows with
  * n_layer * batch * seq * (d_model + d_ff)); the backward half is deterministic (no atomics).  Runs on the context's
  * stream and returns after it has finished.  seq <= 2048.  Errors: ZGR_ERR_NULL, ZGR_ERR_SHAPE (batch outside the

@@ -1,8 +1,8 @@
 """TEST INFRASTRUCTURE ONLY: CPU oracle, never imported by the product path.
 
-Cloud block of Algorithm 1 ("Perform BP on D_p with W^r; collect gradients to
-build basis V_r") and the paragraph "Guided Perturbation Sampling on Cloud" of
-Sec. 3.2: the cloud trains by backpropagation on a public dataset, stores the
+Cloud block of Algorithm 1 (back-propagation on the public dataset with the
+current weights, whose gradients build the basis) and the paragraph on guided
+perturbation sampling on the cloud of Sec. 3.2: the cloud trains by backpropagation on a public dataset, stores the
 gradients it computes, and keeps an orthonormal basis of the subspace they span.
 
 Two parts, both in fp64 with numpy, one line per layer rule:
@@ -22,8 +22,8 @@ Two parts, both in fp64 with numpy, one line per layer rule:
     that returns it.  The subspace is what is defined (a basis of it is fixed only
     up to a rotation), so comparisons use the projector U U^T.
 
-The paper also says the mixing ratio is tuned "based on the relative scales of
-BP-based and ZOO-based perturbations" and gives no rule for it: nothing to build.
+The paper also says the mixing ratio is tuned from how large the two kinds of
+perturbation are relative to each other, and gives no rule for it: nothing to build.
 """
 import numpy as np
 from scipy.special import erf

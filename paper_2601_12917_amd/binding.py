@@ -11,6 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libzgr.so")
 
 # enums of zgr.h
+ZGR_ACT_GELU, ZGR_ACT_RELU = 0, 1
 ZGR_OK, ZGR_ERR_NULL, ZGR_ERR_SHAPE, ZGR_ERR_DTYPE, ZGR_ERR_CONFIG = 0, 1, 2, 3, 4
 ZGR_ERR_WORKSPACE, ZGR_ERR_DEVICE, ZGR_ERR_NONFINITE, ZGR_ERR_STATE = 5, 6, 7, 8
 ZGR_F32, ZGR_BF16 = 0, 1
@@ -30,7 +31,7 @@ class zgr_tensor(C.Structure):
 class zgr_model(C.Structure):
     _fields_ = [("arch", C.c_int32), ("n_layer", C.c_int32), ("d_model", C.c_int32), ("n_head", C.c_int32),
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("max_pos", C.c_int32), ("n_class", C.c_int32),
-                ("ln_eps", C.c_float)]
+                ("ln_eps", C.c_float), ("act", C.c_int32), ("post_ln", C.c_int32)]
 
 
 class zgr_config(C.Structure):

@@ -305,6 +305,8 @@ zgr_status check_model(zgr_ctx* c, const zgr_model& m, int dtype) {
   if (dtype == ZGR_BF16 && (m.d_model % 64 || m.d_ff % 64)) return fail(c, ZGR_ERR_SHAPE, "bf16 storage needs d_model and d_ff to be multiples of 64");
   if (m.arch == ZGR_ARCH_ENCODER_CLS && m.n_class < 2) return fail(c, ZGR_ERR_SHAPE, "n_class must be >= 2");
   if (!(m.ln_eps > 0.f)) return fail(c, ZGR_ERR_CONFIG, "ln_eps must be positive");
+  if (m.act != ZGR_ACT_GELU && m.act != ZGR_ACT_RELU) return fail(c, ZGR_ERR_CONFIG, "unknown activation %d", m.act);
+  if (m.post_ln != 0 && m.post_ln != 1) return fail(c, ZGR_ERR_CONFIG, "post_ln must be 0 or 1");
   return ZGR_OK;
 }
 
@@ -521,17 +523,25 @@ zgr_status forward_loss(zgr_ctx* c, const zgr_batch* b, int slot) {
   const int32_t* tok = reinterpret_cast<const int32_t*>(b->x);
   const bool lm = m.arch == ZGR_ARCH_DECODER_LM;
   { ProfScope ps(c, ZGR_K_EMBED); HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), x, M, b->seq, d, m.vocab, s)); }
+  const int act_epi = m.act == ZGR_ACT_RELU ? EPI_RELU : EPI_GELU;
+  // post_ln: the residual stream x is itself normalised after every sum (and after the embeddings), and h is its copy
+  // in the storage type; otherwise h = LN(x) feeds each sublayer and x stays the raw sum.
+  float* xn = m.post_ln ? x : nullptr;
+  if (m.post_ln) { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, c->lnf_g), T(c, c->lnf_b), h, M, d, m.ln_eps, s, xn)); }
   for (int l = 0; l < m.n_layer; ++l) {
     const Layer& L = c->layers[l];
-    { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, L.ln1_g), T(c, L.ln1_b), h, M, d, m.ln_eps, s)); }
+    if (!m.post_ln) { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, L.ln1_g), T(c, L.ln1_b), h, M, d, m.ln_eps, s)); }
     { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, L.wq), T(c, L.bq), qkv, EPI_STORE, M, 3 * d, d, s)); }
     { ProfScope ps(c, ZGR_K_ATTN); HIP_TRY(c, launch_attention(dt, qkv, ctx, lm ? nullptr : b->lengths, b->batch, b->seq, d, m.n_head, lm ? 1 : 0, s)); }
     { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, ctx, T(c, L.wo), T(c, L.bo), x, EPI_RESID, M, d, d, s)); }
-    { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, L.ln2_g), T(c, L.ln2_b), h, M, d, m.ln_eps, s)); }
-    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, L.w1), T(c, L.b1), ffb, EPI_GELU, M, ff, d, s)); }
+    { ProfScope ps(c, ZGR_K_NORM);
+      HIP_TRY(c, m.post_ln ? launch_layernorm(dt, x, T(c, L.ln1_g), T(c, L.ln1_b), h, M, d, m.ln_eps, s, xn)
+                           : launch_layernorm(dt, x, T(c, L.ln2_g), T(c, L.ln2_b), h, M, d, m.ln_eps, s)); }
+    { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, h, T(c, L.w1), T(c, L.b1), ffb, act_epi, M, ff, d, s)); }
     { ProfScope ps(c, ZGR_K_GEMM); HIP_TRY(c, launch_gemm(dt, ffb, T(c, L.w2), T(c, L.b2), x, EPI_RESID, M, d, ff, s)); }
+    if (m.post_ln) { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, L.ln2_g), T(c, L.ln2_b), h, M, d, m.ln_eps, s, xn)); }
   }
-  { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, c->lnf_g), T(c, c->lnf_b), h, M, d, m.ln_eps, s)); }
+  if (!m.post_ln) { ProfScope ps(c, ZGR_K_NORM); HIP_TRY(c, launch_layernorm(dt, x, T(c, c->lnf_g), T(c, c->lnf_b), h, M, d, m.ln_eps, s)); }
   if (lm) {
     int32_t* tgt = reinterpret_cast<int32_t*>(ws + c->cv.targets);
     { ProfScope ps(c, ZGR_K_LOSS); HIP_TRY(c, launch_lm_targets(tok, tgt, M, b->seq, m.vocab, s)); }
@@ -859,7 +869,8 @@ namespace {
 
 // Workspace of one backward pass over a batch of `batch` sequences of `seq` tokens (byte offsets).
 struct BwCarve {
-  struct PerLayer { size_t xin, h1, qkv, ctx, xmid, h2, u, f; };
+  struct PerLayer { size_t xin, h1, qkv, ctx, xmid, h2, u, f, x1n, y2; };   // x1n, y2: post-LayerNorm models only
+  size_t xout = 0;
   std::vector<PerLayer> layer;
   size_t xfin = 0, hf = 0, logits = 0, targets = 0, row_loss = 0, loss = 0;
   size_t dx = 0, dt = 0, dff = 0, dqkv = 0, P = 0, dS = 0, stats = 0;
@@ -885,7 +896,10 @@ BwCarve bw_carve(const zgr_ctx* c, int batch, int seq) {
     BwCarve::PerLayer& L = v.layer[l];
     L.xin = take(M * d * 4);  L.h1 = take(M * d * es);  L.qkv = take(M * 3 * d * es);  L.ctx = take(M * d * es);
     L.xmid = take(M * d * 4); L.h2 = take(M * d * es);  L.u = take(M * ff * 4);        L.f = take(M * ff * es);
+    L.x1n = L.y2 = 0;
+    if (m.post_ln) { L.x1n = take(M * d * 4); L.y2 = take(M * d * 4); }
   }
+  if (m.post_ln) v.xout = take(M * d * 4);
   v.xfin = take(M * d * 4);
   v.hf = take(M * d * es);
   v.logits = take(m.arch == ZGR_ARCH_DECODER_LM ? M * (size_t)m.vocab * 4 : (size_t)batch * m.n_class * 4);
@@ -990,23 +1004,47 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     return ZGR_OK;
   };
   // ---- forward, every layer's intermediate results kept
-  HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), F(v.layer.empty() ? v.xfin : v.layer[0].xin), M, Tn, d, m.vocab, s));
-  for (int l = 0; l < m.n_layer; ++l) {
-    const Layer& L = c->layers[l];
-    const BwCarve::PerLayer& W = v.layer[l];
-    float* xnext = F(l + 1 < m.n_layer ? v.layer[l + 1].xin : v.xfin);
-    HIP_TRY(c, launch_layernorm(dt, F(W.xin), T(c, L.ln1_g), T(c, L.ln1_b), ws + W.h1, M, d, m.ln_eps, s));
-    HIP_TRY(c, launch_gemm(dt, ws + W.h1, T(c, L.wq), T(c, L.bq), ws + W.qkv, EPI_STORE, M, 3 * d, d, s));
-    HIP_TRY(c, launch_attention(dt, ws + W.qkv, ws + W.ctx, lengths, B, Tn, d, H, lm ? 1 : 0, s));
-    HIP_TRY(c, hipMemcpyAsync(F(W.xmid), F(W.xin), xbytes, hipMemcpyDeviceToDevice, s));
-    HIP_TRY(c, launch_gemm(dt, ws + W.ctx, T(c, L.wo), T(c, L.bo), F(W.xmid), EPI_RESID, M, d, d, s));
-    HIP_TRY(c, launch_layernorm(dt, F(W.xmid), T(c, L.ln2_g), T(c, L.ln2_b), ws + W.h2, M, d, m.ln_eps, s));
-    HIP_TRY(c, launch_gemm(dt, ws + W.h2, T(c, L.w1), T(c, L.b1), F(W.u), EPI_F32, M, ff, d, s));
-    HIP_TRY(c, launch_bw_gelu_forward(dt, F(W.u), ws + W.f, (int64_t)M * ff, s));
-    HIP_TRY(c, hipMemcpyAsync(xnext, F(W.xmid), xbytes, hipMemcpyDeviceToDevice, s));
-    HIP_TRY(c, launch_gemm(dt, ws + W.f, T(c, L.w2), T(c, L.b2), xnext, EPI_RESID, M, d, ff, s));
+  const int relu = m.act == ZGR_ACT_RELU ? 1 : 0;
+  if (!m.post_ln) {
+    HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), F(v.layer[0].xin), M, Tn, d, m.vocab, s));
+    for (int l = 0; l < m.n_layer; ++l) {
+      const Layer& L = c->layers[l];
+      const BwCarve::PerLayer& W = v.layer[l];
+      float* xnext = F(l + 1 < m.n_layer ? v.layer[l + 1].xin : v.xfin);
+      HIP_TRY(c, launch_layernorm(dt, F(W.xin), T(c, L.ln1_g), T(c, L.ln1_b), ws + W.h1, M, d, m.ln_eps, s));
+      HIP_TRY(c, launch_gemm(dt, ws + W.h1, T(c, L.wq), T(c, L.bq), ws + W.qkv, EPI_STORE, M, 3 * d, d, s));
+      HIP_TRY(c, launch_attention(dt, ws + W.qkv, ws + W.ctx, lengths, B, Tn, d, H, lm ? 1 : 0, s));
+      HIP_TRY(c, hipMemcpyAsync(F(W.xmid), F(W.xin), xbytes, hipMemcpyDeviceToDevice, s));
+      HIP_TRY(c, launch_gemm(dt, ws + W.ctx, T(c, L.wo), T(c, L.bo), F(W.xmid), EPI_RESID, M, d, d, s));
+      HIP_TRY(c, launch_layernorm(dt, F(W.xmid), T(c, L.ln2_g), T(c, L.ln2_b), ws + W.h2, M, d, m.ln_eps, s));
+      HIP_TRY(c, launch_gemm(dt, ws + W.h2, T(c, L.w1), T(c, L.b1), F(W.u), EPI_F32, M, ff, d, s));
+      HIP_TRY(c, launch_bw_act_forward(dt, relu, F(W.u), ws + W.f, (int64_t)M * ff, s));
+      HIP_TRY(c, hipMemcpyAsync(xnext, F(W.xmid), xbytes, hipMemcpyDeviceToDevice, s));
+      HIP_TRY(c, launch_gemm(dt, ws + W.f, T(c, L.w2), T(c, L.b2), xnext, EPI_RESID, M, d, ff, s));
+    }
+    HIP_TRY(c, launch_layernorm(dt, F(v.xfin), T(c, c->lnf_g), T(c, c->lnf_b), ws + v.hf, M, d, m.ln_eps, s));
+  } else {
+    // post-LayerNorm blocks: xfin holds the raw embedding sum, a layer's xin / h1 its normalised input (fp32 / storage type),
+    // xmid and y2 the raw sums in front of LN1 and LN2, x1n / h2 the output of LN1
+    HIP_TRY(c, launch_embed(dt, tok, T(c, c->tok_emb), T(c, c->pos_emb), F(v.xfin), M, Tn, d, m.vocab, s));
+    HIP_TRY(c, launch_layernorm(dt, F(v.xfin), T(c, c->lnf_g), T(c, c->lnf_b), ws + v.layer[0].h1, M, d, m.ln_eps, s, F(v.layer[0].xin)));
+    for (int l = 0; l < m.n_layer; ++l) {
+      const Layer& L = c->layers[l];
+      const BwCarve::PerLayer& W = v.layer[l];
+      const bool last = l + 1 == m.n_layer;
+      HIP_TRY(c, launch_gemm(dt, ws + W.h1, T(c, L.wq), T(c, L.bq), ws + W.qkv, EPI_STORE, M, 3 * d, d, s));
+      HIP_TRY(c, launch_attention(dt, ws + W.qkv, ws + W.ctx, lengths, B, Tn, d, H, lm ? 1 : 0, s));
+      HIP_TRY(c, hipMemcpyAsync(F(W.xmid), F(W.xin), xbytes, hipMemcpyDeviceToDevice, s));
+      HIP_TRY(c, launch_gemm(dt, ws + W.ctx, T(c, L.wo), T(c, L.bo), F(W.xmid), EPI_RESID, M, d, d, s));
+      HIP_TRY(c, launch_layernorm(dt, F(W.xmid), T(c, L.ln1_g), T(c, L.ln1_b), ws + W.h2, M, d, m.ln_eps, s, F(W.x1n)));
+      HIP_TRY(c, launch_gemm(dt, ws + W.h2, T(c, L.w1), T(c, L.b1), F(W.u), EPI_F32, M, ff, d, s));
+      HIP_TRY(c, launch_bw_act_forward(dt, relu, F(W.u), ws + W.f, (int64_t)M * ff, s));
+      HIP_TRY(c, hipMemcpyAsync(F(W.y2), F(W.x1n), xbytes, hipMemcpyDeviceToDevice, s));
+      HIP_TRY(c, launch_gemm(dt, ws + W.f, T(c, L.w2), T(c, L.b2), F(W.y2), EPI_RESID, M, d, ff, s));
+      HIP_TRY(c, launch_layernorm(dt, F(W.y2), T(c, L.ln2_g), T(c, L.ln2_b), last ? ws + v.hf : ws + v.layer[l + 1].h1, M, d, m.ln_eps, s,
+                                  F(last ? v.xout : v.layer[l + 1].xin)));
+    }
   }
-  HIP_TRY(c, launch_layernorm(dt, F(v.xfin), T(c, c->lnf_g), T(c, c->lnf_b), ws + v.hf, M, d, m.ln_eps, s));
   // ---- the loss and its gradient with respect to the final hidden states (into dt), head parameters
   float* logits = F(v.logits);
   float* dx = F(v.dx);
@@ -1037,22 +1075,33 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     HIP_TRY(c, launch_bw_gemm(dt, logits, C, 1, T(c, c->cls_w), d, 1, dtb, (int64_t)Tn * d, B, d, C, 1.0f, 0, s));
     HIP_TRY(c, launch_bw_fill(grads[c->tok_emb], (int64_t)m.vocab * d, 0.f, s));
   }
-  HIP_TRY(c, launch_bw_layernorm(dt, F(v.xfin), T(c, c->lnf_g), dtb, nullptr, dx, F(v.stats), grads[c->lnf_g], grads[c->lnf_b], F(v.part), M, d, m.ln_eps, s));
   // ---- the blocks in reverse; dx holds dL/d(residual stream) at the block's output
+  const int64_t nx = (int64_t)M * d;
+  if (m.post_ln) HIP_TRY(c, hipMemcpyAsync(dx, dtb, xbytes, hipMemcpyDeviceToDevice, s));       // the head reads the last LN2's output itself
+  else HIP_TRY(c, launch_bw_layernorm(dt, F(v.xfin), T(c, c->lnf_g), dtb, nullptr, dx, F(v.stats), grads[c->lnf_g], grads[c->lnf_b], F(v.part), M, d, m.ln_eps, s));
   for (int l = m.n_layer - 1; l >= 0; --l) {
     const Layer& L = c->layers[l];
     const BwCarve::PerLayer& W = v.layer[l];
     float* dff = F(v.dff);
     float* dqkv = F(v.dqkv);
-    // x_out = x_mid + f W2^T + b2
+    // post-LN: x_out = LN2(y2), dx <- dL/dy2
+    if (m.post_ln) HIP_TRY(c, launch_bw_layernorm(dt, F(W.y2), T(c, L.ln2_g), dx, nullptr, dx, F(v.stats), grads[L.ln2_g], grads[L.ln2_b], F(v.part), M, d, m.ln_eps, s));
+    // x_out (or y2) = x_mid (or x1n) + f W2^T + b2
     if ((st = param_grads(dx, d, ws + W.f, d, ff, grads[L.w2], grads[L.b2])) != ZGR_OK) return st;
     if ((st = input_grad(dx, d, T(c, L.w2), ff, dff)) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_gelu(F(W.u), dff, (int64_t)M * ff, s));
+    HIP_TRY(c, launch_bw_act(relu, F(W.u), dff, (int64_t)M * ff, s));
     // u = h2 W1^T + b1
     if ((st = param_grads(dff, ff, ws + W.h2, ff, d, grads[L.w1], grads[L.b1])) != ZGR_OK) return st;
     if ((st = input_grad(dff, ff, T(c, L.w1), d, dtb)) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xmid), T(c, L.ln2_g), dtb, dx, dx, F(v.stats), grads[L.ln2_g], grads[L.ln2_b], F(v.part), M, d, m.ln_eps, s));
-    // x_mid = x_in + ctx Wo^T + bo
+    if (m.post_ln) {
+      // h2 = x1n = LN1(y1): dL/dx1n = dx + dh2, then dx <- dL/dy1
+      HIP_TRY(c, launch_bw_add(dtb, dx, nx, s));
+      HIP_TRY(c, launch_bw_layernorm(dt, F(W.xmid), T(c, L.ln1_g), dtb, nullptr, dx, F(v.stats), grads[L.ln1_g], grads[L.ln1_b], F(v.part), M, d, m.ln_eps, s));
+    } else {
+      // h2 = LN2(x_mid): dx <- dx + LN2'(dh2)
+      HIP_TRY(c, launch_bw_layernorm(dt, F(W.xmid), T(c, L.ln2_g), dtb, dx, dx, F(v.stats), grads[L.ln2_g], grads[L.ln2_b], F(v.part), M, d, m.ln_eps, s));
+    }
+    // x_mid (or y1) = x_in + ctx Wo^T + bo
     if ((st = param_grads(dx, d, ws + W.ctx, d, d, grads[L.wo], grads[L.bo])) != ZGR_OK) return st;
     if ((st = input_grad(dx, d, T(c, L.wo), d, dtb)) != ZGR_OK) return st;
     HIP_TRY(c, launch_bw_attention(dt, ws + W.qkv, dtb, lengths, B, Tn, d, H, lm ? 1 : 0, F(v.P), F(v.dS), dqkv, s));
@@ -1061,8 +1110,11 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     for (int p = 0; p < 3; ++p)
       if ((st = param_grads(dqkv + (size_t)p * d, 3 * d, ws + W.h1, d, d, grads[wi[p]], grads[bi[p]])) != ZGR_OK) return st;
     if ((st = input_grad(dqkv, 3 * d, T(c, L.wq), d, dtb)) != ZGR_OK) return st;
-    HIP_TRY(c, launch_bw_layernorm(dt, F(W.xin), T(c, L.ln1_g), dtb, dx, dx, F(v.stats), grads[L.ln1_g], grads[L.ln1_b], F(v.part), M, d, m.ln_eps, s));
+    if (m.post_ln) HIP_TRY(c, launch_bw_add(dx, dtb, nx, s));                                    // h1 = x_in
+    else HIP_TRY(c, launch_bw_layernorm(dt, F(W.xin), T(c, L.ln1_g), dtb, dx, dx, F(v.stats), grads[L.ln1_g], grads[L.ln1_b], F(v.part), M, d, m.ln_eps, s));
   }
+  // post-LN: x_0 = LNF(embedding sum)
+  if (m.post_ln) HIP_TRY(c, launch_bw_layernorm(dt, F(v.xfin), T(c, c->lnf_g), dx, nullptr, dx, F(v.stats), grads[c->lnf_g], grads[c->lnf_b], F(v.part), M, d, m.ln_eps, s));
   HIP_TRY(c, launch_bw_embedding(tok, dx, M, Tn, d, m.vocab, grads[c->tok_emb], grads[c->pos_emb], m.max_pos, s));
   HIP_TRY(c, hipMemcpyAsync(c->host_loss, loss_dev, sizeof(double), hipMemcpyDeviceToHost, s));
   HIP_TRY(c, hipStreamSynchronize(s));

@@ -21,12 +21,13 @@ hipError_t launch_bw_colsum(const float* Y, int M, int N, int64_t ld, float* out
 hipError_t launch_bw_fill(float* p, int64_t n, float v, hipStream_t s);
 // logits [rows, n] -> (softmax - onehot(target)) inv_count in place; rows with a target outside [0, n) become zeros
 hipError_t launch_bw_cross_entropy(float* logits, const int32_t* targets, int rows, int n, float inv_count, hipStream_t s);
-// y = LayerNorm(x) g + b: dx_out = (add ? add : 0) + dL/dx, dg, db from dy; stats: 2 M floats of scratch, part: bw_colsum_scratch_floats(d)
+// y = LayerNorm(x) g + b: dx_out = (add ? add : 0) + dL/dx (dx_out may be add or dy), dg, db from dy; stats: 2 M floats of scratch, part: bw_colsum_scratch_floats(d)
 hipError_t launch_bw_layernorm(int dtype, const float* x, const void* g, const float* dy, const float* add, float* dx_out, float* stats, float* dg, float* db,
                                float* part, int M, int d, float eps, hipStream_t s);
-// f = gelu(u) in the storage type; df <- df gelu'(u)
-hipError_t launch_bw_gelu_forward(int dtype, const float* u, void* f, int64_t n, hipStream_t s);
-hipError_t launch_bw_gelu(const float* u, float* df, int64_t n, hipStream_t s);
+// f = act(u) in the storage type (erf-GELU, or ReLU when relu != 0); df <- df act'(u); dst += src
+hipError_t launch_bw_act_forward(int dtype, int relu, const float* u, void* f, int64_t n, hipStream_t s);
+hipError_t launch_bw_act(int relu, const float* u, float* df, int64_t n, hipStream_t s);
+hipError_t launch_bw_add(float* dst, const float* src, int64_t n, hipStream_t s);
 // dqkv [B T, 3 d] from dctx [B T, d]; P, dS: scratch of B n_head T T floats each
 hipError_t launch_bw_attention(int dtype, const void* qkv, const float* dctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal,
                                float* P, float* dS, float* dqkv, hipStream_t s);

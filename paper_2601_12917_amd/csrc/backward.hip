@@ -1,5 +1,5 @@
-// Backward pass of the cloud block of Algorithm 1 ("Perform BP on D_p with W^r; collect gradients to build basis
-// V_r"; Sec. 3.2, "Guided Perturbation Sampling on Cloud"): dL/dtheta of the loss of forward.hip, by the chain rule
+// Backward pass of the cloud block of Algorithm 1 (back-propagation on the public dataset with the current weights,
+// whose gradients build the basis; Sec. 3.2, paragraph on guided perturbation sampling on the cloud): dL/dtheta of the loss of forward.hip, by the chain rule
 // layer by layer, in fp32.  The forward pass that precedes it runs the client's own kernels and keeps every layer's
 // intermediate results; these kernels take them back in reverse order.
 //
@@ -174,10 +174,11 @@ __global__ void __launch_bounds__(256) ce_backward_kernel(float* __restrict__ lo
 
 // ------------------------------------------------------------------ LayerNorm
 // y = xhat g + b, xhat = (x - mu) rstd.  Per row: dx = rstd (dy g - mean(dy g) - xhat mean(dy g xhat)), written as
-// dx_out = (add ? add : 0) + dx; the row's (mu, rstd) go to stats for the parameter gradients.
+// dx_out = (add ? add : 0) + dx (dx_out may be add or dy itself: every sum over the row is taken before the row is
+// written, and an element is written by the thread that read it).
 template <typename T>
-__global__ void __launch_bounds__(256) ln_backward_kernel(const float* __restrict__ x, const T* __restrict__ g, const float* __restrict__ dy,
-                                                          const float* add, float* dx_out, float* __restrict__ stats, int d, float eps) {   // add may be dx_out
+__global__ void __launch_bounds__(256) ln_backward_kernel(const float* __restrict__ x, const T* __restrict__ g, const float* dy,
+                                                          const float* add, float* dx_out, int d, float eps) {   // add or dy may be dx_out
   __shared__ float red[4];
   const size_t o = (size_t)blockIdx.x * d;
   const float* row = x + o;
@@ -201,6 +202,18 @@ __global__ void __launch_bounds__(256) ln_backward_kernel(const float* __restric
     const float r = rstd * (drow[i] * to_f32(g[i]) - s1 - xhat * s2);
     dx_out[o + i] = (add ? add[o + i] : 0.f) + r;
   }
+}
+
+// (mu, rstd) of every row, for the parameter gradients
+__global__ void __launch_bounds__(256) ln_stats_kernel(const float* __restrict__ x, float* __restrict__ stats, int d, float eps) {
+  __shared__ float red[4];
+  const float* row = x + (size_t)blockIdx.x * d;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) s += row[i];
+  const float mu = block_sum(s, red) / d;
+  float v = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) { const float t = row[i] - mu; v += t * t; }
+  const float rstd = 1.0f / sqrtf(block_sum(v, red) / d + eps);
   if (threadIdx.x == 0) { stats[2 * blockIdx.x] = mu; stats[2 * blockIdx.x + 1] = rstd; }
 }
 
@@ -227,22 +240,28 @@ __global__ void __launch_bounds__(256) ln_param_grad_partial_kernel(const float*
   }
 }
 
-// ------------------------------------------------------------------ GELU (erf form)
-template <typename T>
-__global__ void __launch_bounds__(256) gelu_forward_kernel(const float* __restrict__ u, T* __restrict__ f, int64_t n) {
+// ------------------------------------------------------------------ feed-forward activation: erf-GELU or ReLU
+template <typename T, bool RELU>
+__global__ void __launch_bounds__(256) act_forward_kernel(const float* __restrict__ u, T* __restrict__ f, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const float x = u[i];
-    from_f32(0.5f * x * (1.0f + erff(x * 0.70710678118654752f)), f[i]);
+    from_f32(RELU ? fmaxf(x, 0.f) : 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)), f[i]);
   }
 }
-// du = df * (Phi(u) + u phi(u)), in place on df
-__global__ void __launch_bounds__(256) gelu_backward_kernel(const float* __restrict__ u, float* __restrict__ df, int64_t n) {
+// du = df * act'(u), in place on df: GELU' = Phi(u) + u phi(u), ReLU' = [u > 0]
+template <bool RELU>
+__global__ void __launch_bounds__(256) act_backward_kernel(const float* __restrict__ u, float* __restrict__ df, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const float x = u[i];
+    if (RELU) { if (!(x > 0.f)) df[i] = 0.f; continue; }
     const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
     const float pdf = 0.3989422804014327f * expf(-0.5f * x * x);
     df[i] *= cdf + x * pdf;
   }
+}
+
+__global__ void __launch_bounds__(256) add_kernel(float* __restrict__ dst, const float* __restrict__ src, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] += src[i];
 }
 
 // ------------------------------------------------------------------ attention
@@ -388,24 +407,39 @@ hipError_t launch_bw_cross_entropy(float* logits, const int32_t* targets, int ro
 
 hipError_t launch_bw_layernorm(int dtype, const float* x, const void* g, const float* dy, const float* add, float* dx_out, float* stats, float* dg, float* db,
                                float* part, int M, int d, float eps, hipStream_t s) {
-  if (dtype == 1) hipLaunchKernelGGL(ln_backward_kernel<bf16_t>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const bf16_t*>(g), dy, add, dx_out, stats, d, eps);
-  else            hipLaunchKernelGGL(ln_backward_kernel<float>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const float*>(g), dy, add, dx_out, stats, d, eps);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  // the parameter gradients read dy: they go first, so that dx_out may overwrite it
+  hipLaunchKernelGGL(ln_stats_kernel, dim3((unsigned)M), dim3(256), 0, s, x, stats, d, eps);
   hipLaunchKernelGGL(ln_param_grad_partial_kernel, dim3((unsigned)((d + 63) / 64), kColParts), dim3(256), 0, s, x, dy, stats, M, d, part);
   hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s, part, d, dg);
   hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s, part + (size_t)kColParts * d, d, db);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (dtype == 1) hipLaunchKernelGGL(ln_backward_kernel<bf16_t>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const bf16_t*>(g), dy, add, dx_out, d, eps);
+  else            hipLaunchKernelGGL(ln_backward_kernel<float>, dim3((unsigned)M), dim3(256), 0, s, x, reinterpret_cast<const float*>(g), dy, add, dx_out, d, eps);
   return hipGetLastError();
 }
 
-hipError_t launch_bw_gelu_forward(int dtype, const float* u, void* f, int64_t n, hipStream_t s) {
-  if (dtype == 1) hipLaunchKernelGGL(gelu_forward_kernel<bf16_t>, dim3(grid_1d(n)), dim3(256), 0, s, u, reinterpret_cast<bf16_t*>(f), n);
-  else            hipLaunchKernelGGL(gelu_forward_kernel<float>, dim3(grid_1d(n)), dim3(256), 0, s, u, reinterpret_cast<float*>(f), n);
+hipError_t launch_bw_act_forward(int dtype, int relu, const float* u, void* f, int64_t n, hipStream_t s) {
+  const dim3 grid(grid_1d(n));
+  if (dtype == 1) {
+    if (relu) hipLaunchKernelGGL((act_forward_kernel<bf16_t, true>), grid, dim3(256), 0, s, u, reinterpret_cast<bf16_t*>(f), n);
+    else      hipLaunchKernelGGL((act_forward_kernel<bf16_t, false>), grid, dim3(256), 0, s, u, reinterpret_cast<bf16_t*>(f), n);
+  } else {
+    if (relu) hipLaunchKernelGGL((act_forward_kernel<float, true>), grid, dim3(256), 0, s, u, reinterpret_cast<float*>(f), n);
+    else      hipLaunchKernelGGL((act_forward_kernel<float, false>), grid, dim3(256), 0, s, u, reinterpret_cast<float*>(f), n);
+  }
   return hipGetLastError();
 }
 
-hipError_t launch_bw_gelu(const float* u, float* df, int64_t n, hipStream_t s) {
-  hipLaunchKernelGGL(gelu_backward_kernel, dim3(grid_1d(n)), dim3(256), 0, s, u, df, n);
+hipError_t launch_bw_act(int relu, const float* u, float* df, int64_t n, hipStream_t s) {
+  if (relu) hipLaunchKernelGGL(act_backward_kernel<true>, dim3(grid_1d(n)), dim3(256), 0, s, u, df, n);
+  else      hipLaunchKernelGGL(act_backward_kernel<false>, dim3(grid_1d(n)), dim3(256), 0, s, u, df, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_add(float* dst, const float* src, int64_t n, hipStream_t s) {
+  if (n < 1) return hipSuccess;
+  hipLaunchKernelGGL(add_kernel, dim3(grid_1d(n)), dim3(256), 0, s, dst, src, n);
   return hipGetLastError();
 }
 

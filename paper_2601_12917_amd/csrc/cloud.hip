@@ -1,5 +1,5 @@
-// Cloud block of Algorithm 1 ("collect gradients to build basis V_r"; Sec. 3.2, "Guided Perturbation Sampling on
-// Cloud"): the orthonormal basis U [rows, k] of one weight matrix from its stored gradient snapshots G_1 .. G_s
+// Cloud block of Algorithm 1 (the gradients collected on the cloud build the basis; Sec. 3.2, paragraph on guided
+// perturbation sampling on the cloud): the orthonormal basis U [rows, k] of one weight matrix from its stored gradient snapshots G_1 .. G_s
 // (each [rows, cols] fp32, row-major), and the gradient of the least-squares model.
 //
 // U spans the k-dimensional subspace of R^rows that captures the most of the snapshots (the k leading left singular

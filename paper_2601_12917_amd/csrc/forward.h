@@ -6,10 +6,11 @@
 
 namespace zgr {
 
-enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3, EPI_CE = 4 };
+enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_F32 = 3, EPI_CE = 4, EPI_RELU = 5 };
 
 hipError_t launch_embed(int dtype, const int32_t* tok, const void* E, const void* Pe, float* x, int M, int seq, int d, int vocab, hipStream_t s);
-hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s);
+// out (storage type) = LayerNorm(x) g + b; xout, when not NULL, receives the same values in fp32 (it may be x itself)
+hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s, float* xout = nullptr);
 // out = epilogue(A[M,K] W[N,K]^T + bias); bf16 storage needs K % 64 == 0.
 hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias, void* out, int epi, int M, int N, int K, hipStream_t s);
 // bf16 vocabulary projection fused with cross-entropy: row_loss[m] = logsumexp(A[m] W^T) - (A[m] W^T)[targets[m]] (0 where targets[m] < 0).

@@ -63,8 +63,8 @@ __global__ void __launch_bounds__(256) embed_kernel(const int32_t* __restrict__ 
 
 // ------------------------------------------------------------------ LayerNorm (one block per row)
 template <typename T>
-__global__ void __launch_bounds__(256) layernorm_kernel(const float* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
-                                                        T* __restrict__ out, int d, float eps) {
+__global__ void __launch_bounds__(256) layernorm_kernel(const float* x, const T* __restrict__ g, const T* __restrict__ b,
+                                                        T* __restrict__ out, int d, float eps, float* xout) {
   __shared__ float red[4];
   const float* row = x + (size_t)blockIdx.x * d;
   float s = 0.f;
@@ -74,13 +74,18 @@ __global__ void __launch_bounds__(256) layernorm_kernel(const float* __restrict_
   for (int i = threadIdx.x; i < d; i += 256) { const float t = row[i] - mu; v += t * t; }
   const float rstd = 1.0f / sqrtf(block_sum(v, red) / d + eps);
   T* o = out + (size_t)blockIdx.x * d;
-  for (int i = threadIdx.x; i < d; i += 256) from_f32((row[i] - mu) * rstd * to_f32(g[i]) + to_f32(b[i]), o[i]);
+  float* xo = xout ? xout + (size_t)blockIdx.x * d : nullptr;      // may be the row itself: an element is read, then written, by one thread
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float y = (row[i] - mu) * rstd * to_f32(g[i]) + to_f32(b[i]);
+    from_f32(y, o[i]);
+    if (xo) xo[i] = y;
+  }
 }
 
 // Row held in registers (d % 4 == 0, d <= 8192): one read of x, float4 loads, packed stores.
 template <typename T>
-__global__ void __launch_bounds__(256) layernorm_reg_kernel(const float* __restrict__ x, const T* __restrict__ g, const T* __restrict__ b,
-                                                            T* __restrict__ out, int d, float eps) {
+__global__ void __launch_bounds__(256) layernorm_reg_kernel(const float* x, const T* __restrict__ g, const T* __restrict__ b,
+                                                            T* __restrict__ out, int d, float eps, float* xout) {
   __shared__ float red[4];
   constexpr int MAXV = 8;
   const float4* row = reinterpret_cast<const float4*>(x + (size_t)blockIdx.x * d);
@@ -112,11 +117,11 @@ __global__ void __launch_bounds__(256) layernorm_reg_kernel(const float* __restr
       struct alignas(sizeof(T) * 4) V4 { T e[4]; };
       const V4 gg = *reinterpret_cast<const V4*>(g + 4 * i), bb = *reinterpret_cast<const V4*>(b + 4 * i);
       V4 r;
-      from_f32((v[j].x - mu) * rstd * to_f32(gg.e[0]) + to_f32(bb.e[0]), r.e[0]);
-      from_f32((v[j].y - mu) * rstd * to_f32(gg.e[1]) + to_f32(bb.e[1]), r.e[1]);
-      from_f32((v[j].z - mu) * rstd * to_f32(gg.e[2]) + to_f32(bb.e[2]), r.e[2]);
-      from_f32((v[j].w - mu) * rstd * to_f32(gg.e[3]) + to_f32(bb.e[3]), r.e[3]);
+      const float4 y = make_float4((v[j].x - mu) * rstd * to_f32(gg.e[0]) + to_f32(bb.e[0]), (v[j].y - mu) * rstd * to_f32(gg.e[1]) + to_f32(bb.e[1]),
+                                   (v[j].z - mu) * rstd * to_f32(gg.e[2]) + to_f32(bb.e[2]), (v[j].w - mu) * rstd * to_f32(gg.e[3]) + to_f32(bb.e[3]));
+      from_f32(y.x, r.e[0]); from_f32(y.y, r.e[1]); from_f32(y.z, r.e[2]); from_f32(y.w, r.e[3]);
       *reinterpret_cast<V4*>(o + 4 * i) = r;
+      if (xout) reinterpret_cast<float4*>(xout + (size_t)blockIdx.x * d)[i] = y;      // the row is in registers: xout may be x
     }
   }
 }
@@ -124,7 +129,7 @@ __global__ void __launch_bounds__(256) layernorm_reg_kernel(const float* __restr
 // ------------------------------------------------------------------ GEMM  C = A W^T (+bias) with epilogues
 // A [M,K] and W [N,K] are K-contiguous.
 //   EPI_STORE: out T [M,N] = acc + bias
-//   EPI_GELU : out T [M,N] = gelu(acc + bias)
+//   EPI_GELU : out T [M,N] = gelu(acc + bias);  EPI_RELU: out T [M,N] = max(acc + bias, 0)
 //   EPI_RESID: xres fp32 [M,N] += acc + bias
 //   EPI_F32  : outf fp32 [M,N] = acc + bias (bias may be null)
 struct GemmEpi { int mode; void* out; const void* bias; };
@@ -136,6 +141,7 @@ __device__ __forceinline__ void epilogue_store(const GemmEpi& ep, int m, int n, 
   switch (ep.mode) {
     case EPI_STORE: from_f32(v, reinterpret_cast<T*>(ep.out)[o]); break;
     case EPI_GELU:  from_f32(gelu_erf(v), reinterpret_cast<T*>(ep.out)[o]); break;
+    case EPI_RELU:  from_f32(fmaxf(v, 0.f), reinterpret_cast<T*>(ep.out)[o]); break;
     case EPI_RESID: reinterpret_cast<float*>(ep.out)[o] += v; break;
     default:        reinterpret_cast<float*>(ep.out)[o] = v; break;
   }
@@ -208,6 +214,7 @@ template <int MODE>
 __device__ __forceinline__ void epilogue_bf16(void* out, size_t o, float v) {
   if (MODE == EPI_STORE) from_f32(v, reinterpret_cast<bf16_t*>(out)[o]);
   else if (MODE == EPI_GELU) from_f32(gelu_fast(v), reinterpret_cast<bf16_t*>(out)[o]);
+  else if (MODE == EPI_RELU) from_f32(fmaxf(v, 0.f), reinterpret_cast<bf16_t*>(out)[o]);
   else if (MODE == EPI_RESID) reinterpret_cast<float*>(out)[o] += v;
   else reinterpret_cast<float*>(out)[o] = v;
 }
@@ -575,6 +582,7 @@ hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bi
   switch (epi) {
     case EPI_STORE: ZGR_GEMM_LAUNCH(EPI_STORE) break;
     case EPI_GELU:  ZGR_GEMM_LAUNCH(EPI_GELU) break;
+    case EPI_RELU:  ZGR_GEMM_LAUNCH(EPI_RELU) break;
     case EPI_RESID: ZGR_GEMM_LAUNCH(EPI_RESID) break;
     case EPI_CE:    ZGR_GEMM_LAUNCH(EPI_CE) break;
     default:        ZGR_GEMM_LAUNCH(EPI_F32) break;
@@ -852,14 +860,14 @@ hipError_t launch_embed(int dtype, const int32_t* tok, const void* E, const void
   return hipGetLastError();
 }
 
-hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s) {
-  if (d % 4 == 0 && d <= 8192 && (((uintptr_t)g | (uintptr_t)b | (uintptr_t)out) & 15) == 0) {
-    if (dtype == 0) hipLaunchKernelGGL(layernorm_reg_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps);
-    else            hipLaunchKernelGGL(layernorm_reg_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps);
+hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s, float* xout) {
+  if (d % 4 == 0 && d <= 8192 && (((uintptr_t)g | (uintptr_t)b | (uintptr_t)out | (uintptr_t)xout) & 15) == 0) {
+    if (dtype == 0) hipLaunchKernelGGL(layernorm_reg_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps, xout);
+    else            hipLaunchKernelGGL(layernorm_reg_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps, xout);
     return hipGetLastError();
   }
-  if (dtype == 0) hipLaunchKernelGGL(layernorm_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps);
-  else            hipLaunchKernelGGL(layernorm_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps);
+  if (dtype == 0) hipLaunchKernelGGL(layernorm_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps, xout);
+  else            hipLaunchKernelGGL(layernorm_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps, xout);
   return hipGetLastError();
 }
 

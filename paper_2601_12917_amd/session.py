@@ -28,7 +28,7 @@ def _align(x, a=256):
 class Session:
     def __init__(self, arch, dtype, params: Sequence[ParamSpec], seed, eps, alpha, scale_mode=B.ZGR_SCALE_UNIT,
                  gauss_bits=32, n_layer=0, d_model=0, n_head=0, d_ff=0, vocab=0, max_pos=0, n_class=0, ln_eps=1e-5,
-                 max_batch=1, max_seq=2, device="cuda:0", pack_after=(), fuse_lr=None):
+                 max_batch=1, max_seq=2, device="cuda:0", pack_after=(), fuse_lr=None, act="gelu", post_ln=False):
         """pack_after: names of tensors that must start right where the previous one ends
         (Wk, Wv after Wq; bk, bv after bq).  fuse_lr: a learning rate makes step() end with the fused
         restore + update pass (apply_update is then not to be called)."""
@@ -64,7 +64,8 @@ class Session:
             e.k = p.k
             e.ldu = p.U.shape[1] if p.U is not None else 0
             e.role, e.layer = p.role, p.layer
-        self.model = B.zgr_model(arch, n_layer, d_model, n_head, d_ff, vocab, max_pos, n_class, ln_eps)
+        self.model = B.zgr_model(arch, n_layer, d_model, n_head, d_ff, vocab, max_pos, n_class, ln_eps,
+                                 {"gelu": B.ZGR_ACT_GELU, "relu": B.ZGR_ACT_RELU}[act], 1 if post_ln else 0)
         self.config = B.zgr_config(seed, eps, alpha, scale_mode, gauss_bits, 0 if fuse_lr is None else 1,
                                      0.0 if fuse_lr is None else fuse_lr)
         nbytes = self.lib.zgr_workspace_bytes(C.byref(self.model), self.table, len(self.params), max_batch, max_seq)

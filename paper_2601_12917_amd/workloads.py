@@ -32,7 +32,8 @@ def make_session(cfg, specs, values, bases, bits=32, scale_mode=None, arch=None,
                    cfg.scale_mode if scale_mode is None else scale_mode, bits,
                    n_layer=cfg.n_layer, d_model=cfg.d_model, n_head=cfg.n_head, d_ff=cfg.d_ff, vocab=cfg.vocab,
                    max_pos=cfg.max_pos, n_class=cfg.n_class, ln_eps=cfg.ln_eps,
-                   max_batch=max(cfg.batch, 1), max_seq=max(cfg.seq, 2), pack_after=pack, fuse_lr=fuse_lr)
+                   max_batch=max(cfg.batch, 1), max_seq=max(cfg.seq, 2), pack_after=pack, fuse_lr=fuse_lr,
+                   act=cfg.act, post_ln=cfg.post_ln)
 
 
 def session_batch(sess, cfg, arrays):

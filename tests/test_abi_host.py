@@ -87,6 +87,11 @@ def test_init_rejects_bad_arguments_without_touching_the_device(lib):
     lsq_bf16 = B.zgr_model(B.ZGR_ARCH_LINEAR_LSQ, 0, 0, 0, 0, 0, 0, 0, 1e-5)
     st, msg, _ = _init(lib, [_tensor(dtype=1)], model=lsq_bf16)
     assert st == B.ZGR_ERR_DTYPE
+    # the model-family switches: activation in {GELU, ReLU}, post_ln in {0, 1}
+    st, msg, _ = _init(lib, [_tensor()], model=B.zgr_model(B.ZGR_ARCH_DECODER_LM, 1, 16, 2, 32, 50, 8, 0, 1e-5, 7, 0))
+    assert st == B.ZGR_ERR_CONFIG and "activation" in msg
+    st, msg, _ = _init(lib, [_tensor()], model=B.zgr_model(B.ZGR_ARCH_DECODER_LM, 1, 16, 2, 32, 50, 8, 0, 1e-5, B.ZGR_ACT_RELU, 2))
+    assert st == B.ZGR_ERR_CONFIG and "post_ln" in msg
 
 
 def test_workspace_bytes_and_null_context_calls(lib):

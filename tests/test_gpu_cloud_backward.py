@@ -1,5 +1,5 @@
-"""HIP path vs CPU oracle for the cloud's backward pass (cloud block of Algorithm 1: "Perform BP on D_p with W^r; collect
-gradients"): zgr_cloud_backward against oracle.cloud on the same seeded parameters and batches, tensor by tensor.
+"""HIP path vs CPU oracle for the cloud's backward pass (cloud block of Algorithm 1: back-propagation on the public
+dataset, whose gradients build the basis): zgr_cloud_backward against oracle.cloud on the same seeded parameters and batches, tensor by tensor.
 
 Tolerances.  fp32 models: every intermediate result is fp32 on the device and fp64 in the oracle, sums run over at
 most a few thousand terms, so a gradient entry differs by a few 1e-6 of the tensor's largest entry; the bound is
@@ -39,8 +39,8 @@ def _batch(cfg, data_seed):
 
 def _oracle(cfg, P, arrays):
     if cfg.arch == I.ARCH_DECODER_LM:
-        return C.lm_loss_and_gradients(P, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
-    return C.cls_loss_and_gradients(P, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        return C.lm_loss_and_gradients(P, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
+    return C.cls_loss_and_gradients(P, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
 
 
 def _device(sess, cfg, arrays):
@@ -53,9 +53,14 @@ TINY_LM = dict(name="bw_lm", n_layer=2, d_model=64, n_head=4, d_ff=192, vocab=21
 TINY_CLS = dict(name="bw_cls", arch=I.ARCH_ENCODER_CLS, n_class=3, n_layer=2, d_model=64, n_head=2, d_ff=128, vocab=157, max_pos=48, batch=5, seq=41, k=8, k_full=8)
 
 
-@pytest.mark.parametrize("which", ["lm", "cls", "cfg2"])
+VARIANT_KW = {"lm_relu": dict(TINY_LM, name="bw_lm_relu", act="relu"), "cls_postln": dict(TINY_CLS, name="bw_cls_postln", post_ln=True),
+              "lm_relu_postln": dict(TINY_LM, name="bw_lm_relu_postln", act="relu", post_ln=True)}
+
+
+@pytest.mark.parametrize("which", ["lm", "cls", "cfg2", "lm_relu", "cls_postln", "lm_relu_postln"])
 def test_fp32_gradients_match_the_oracle_entry_by_entry(which, say):
-    cfg = I.CONFIGS["cfg2"] if which == "cfg2" else I.shrink(I.CONFIGS["cfg2"], **(TINY_LM if which == "lm" else TINY_CLS))
+    """The default model (pre-LayerNorm, erf-GELU) and the two switches of the paper's model families."""
+    cfg = I.CONFIGS["cfg2"] if which == "cfg2" else I.shrink(I.CONFIGS["cfg2"], **(VARIANT_KW[which] if which in VARIANT_KW else TINY_LM if which == "lm" else TINY_CLS))
     sess, specs, P = _setup(cfg)
     theta_before = [sess.get_theta(i).copy() for i in range(len(specs))]
     arrays = _batch(cfg, 1)
@@ -79,10 +84,11 @@ def test_fp32_gradients_match_the_oracle_entry_by_entry(which, say):
     assert all(np.abs(grads[i]).max() > 0 for i, s in enumerate(specs) if s.role != I.ROLE_BK)
 
 
-@pytest.mark.parametrize("batch,seq", [(4, 48), (3, 37)])
-def test_bf16_gradients_point_where_the_oracle_gradients_point(batch, seq, say):
+@pytest.mark.parametrize("batch,seq,act,post_ln", [(4, 48, "gelu", False), (3, 37, "gelu", False), (4, 48, "relu", True)])
+def test_bf16_gradients_point_where_the_oracle_gradients_point(batch, seq, act, post_ln, say):
     """192 tokens: the backward products run on the matrix cores; 111 tokens (not a multiple of 64): on the fp32 kernel."""
-    cfg = I.shrink(I.CONFIGS["cfg3"], name="bw_bf16", n_layer=2, d_model=128, n_head=2, d_ff=256, vocab=389, max_pos=64, batch=batch, seq=seq, k=8, k_full=8)
+    cfg = I.shrink(I.CONFIGS["cfg3"], name="bw_bf16", n_layer=2, d_model=128, n_head=2, d_ff=256, vocab=389, max_pos=64, batch=batch, seq=seq, k=8, k_full=8,
+                   act=act, post_ln=post_ln)
     sess, specs, P = _setup(cfg, scale=3.0)
     arrays = _batch(cfg, 2)
     say("cloud backward bf16 decoder")

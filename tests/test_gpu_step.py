@@ -23,6 +23,12 @@ SMALL_BF16_LM = I.shrink(I.CONFIGS["cfg3"], name="small_bf16_lm", n_layer=2, d_m
                          max_pos=64, batch=3, seq=40, k=16, k_full=16)
 SMALL_BF16_CLS = I.shrink(I.CONFIGS["cfg4"], name="small_bf16_cls", n_layer=2, d_model=128, n_head=2, d_ff=192, vocab=777,
                           max_pos=64, batch=5, seq=33, k=32, k_full=32)
+# the two model families of the paper's experiments: ReLU feed-forward (decoder), post-LayerNorm blocks (encoder), and both
+VARIANTS = [I.shrink(TINY_LM, name="tiny_lm_relu", act="relu"),
+            I.shrink(TINY_CLS, name="tiny_cls_postln", post_ln=True),
+            I.shrink(TINY_LM, name="tiny_lm_relu_postln", act="relu", post_ln=True),
+            I.shrink(SMALL_BF16_LM, name="small_bf16_lm_relu", act="relu"),
+            I.shrink(SMALL_BF16_CLS, name="small_bf16_cls_postln", post_ln=True)]
 
 
 def _params_dict(specs, values):
@@ -32,14 +38,19 @@ def _params_dict(specs, values):
 def _close_params(got, want, dtype, eps_z=None):
     """fp32: 1e-5 relative to the parameter scale.  bf16: 1e-2 relative to the magnitude the value was
     rounded at, |theta| + eps |Z| (a one-ulp flip of theta + eps Z survives the restore pass), and all
-    but a few elements identical."""
+    but a few elements identical.  One bf16 ulp is between 2^-8 and 2^-7 of the value, so a single flip
+    stays under 1e-2; a value next to a power of two that flips in two of the three passes of a step
+    (the device's Z and the oracle's differ by up to 2 ulp fp32, enough to cross a rounding tie) ends
+    up to 2^-6 away: allowed for at most max(2, 1e-4 n) elements."""
     if dtype == "f32":
         return np.all(np.abs(got - want) <= PARAM_RTOL["f32"] * (np.abs(want) + PARAM_SCALE))
     mag = np.abs(want) + (0.0 if eps_z is None else eps_z)
-    return np.all(np.abs(got - want) <= PARAM_RTOL["bf16"] * mag + 1e-30) and np.sum(got != want) <= max(2, 0.005 * got.size)
+    dev = np.abs(got - want)
+    beyond = int(np.sum(dev > PARAM_RTOL["bf16"] * mag + 1e-30))
+    return bool(np.all(dev <= 2.0 ** -6 * mag + 1e-30)) and beyond <= max(2, 1e-4 * got.size) and np.sum(got != want) <= max(2, 0.005 * got.size)
 
 
-@pytest.mark.parametrize("cfg", [TINY_LM, TINY_CLS, I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TINY_LM, TINY_CLS, I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS] + VARIANTS, ids=lambda c: c.name)
 def test_loss_and_row_losses_match_oracle(cfg):
     specs, values, bases = inputs_of(cfg)
     # a 10x larger init than N(0, 0.02) so that attention and the MLP are far from trivial
@@ -50,10 +61,10 @@ def test_loss_and_row_losses_match_oracle(cfg):
     got = sess.loss(session_batch(sess, cfg, arrays))
     Pd = _params_dict(specs, values)
     if cfg.arch == I.ARCH_DECODER_LM:
-        rows = F.lm_token_losses(Pd, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        rows = F.lm_token_losses(Pd, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
         got_rows = sess.last_row_losses(cfg.batch * cfg.seq).reshape(cfg.batch, cfg.seq)[:, :-1]
     else:
-        rows = F.cls_row_losses(Pd, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        rows = F.cls_row_losses(Pd, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
         got_rows = sess.last_row_losses(cfg.batch)
     want = rows.mean()
     assert abs(got - want) <= LOSS_RTOL[cfg.dtype] * abs(want), (got, want)
@@ -115,7 +126,7 @@ def test_cfg1_trajectory_matches_oracle():
     sess.close()
 
 
-@pytest.mark.parametrize("cfg", [I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS, TINY_CLS], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS, TINY_CLS] + VARIANTS[2:], ids=lambda c: c.name)
 @pytest.mark.parametrize("bits", [32, 16])
 def test_step_and_update_match_oracle(cfg, bits):
     steps = 3 if cfg.name == "cfg2" else 2
