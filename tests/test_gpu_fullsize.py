@@ -65,12 +65,12 @@ def _sequence_loss_check(cfg, n_seq):
     del values
     if cfg.arch == I.ARCH_DECODER_LM:
         rows = sess.last_row_losses(cfg.batch * cfg.seq).reshape(cfg.batch, cfg.seq)[:, :-1]
-        want = F.lm_token_losses(Pd, arrays["x"][:n_seq], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        want = F.lm_token_losses(Pd, arrays["x"][:n_seq], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
         got = rows[:n_seq]
         tol = 6e-2 * np.maximum(np.abs(want), 1.0)
     else:
         rows = sess.last_row_losses(cfg.batch)
-        want = F.cls_row_losses(Pd, arrays["x"][:n_seq], arrays["lengths"][:n_seq], arrays["y"][:n_seq], cfg.n_layer, cfg.n_head, cfg.ln_eps)
+        want = F.cls_row_losses(Pd, arrays["x"][:n_seq], arrays["lengths"][:n_seq], arrays["y"][:n_seq], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
         got = rows[:n_seq]
         tol = 2e-2 * np.maximum(np.abs(want), 1.0)
     assert np.all(np.isfinite(rows)) and np.isfinite(got_mean)
@@ -83,6 +83,13 @@ def _sequence_loss_check(cfg, n_seq):
 
 def test_cfg5_forward_losses_of_sampled_sequences():
     _sequence_loss_check(I.CONFIGS["cfg5"], n_seq=1)
+
+
+def test_forward_losses_of_the_papers_model_families_at_full_size():
+    """The benchmark's decoder with a ReLU feed-forward and the 24-block encoder with post-LayerNorm blocks: the two
+    switches of zgr_model at the sizes of the models they come from, on sampled sequences."""
+    _sequence_loss_check(I.shrink(I.CONFIGS["cfg5"], name="cfg5_relu", act="relu"), n_seq=1)
+    _sequence_loss_check(I.shrink(I.CONFIGS["cfg4"], name="cfg4_postln", post_ln=True), n_seq=2)
 
 
 def test_cfg4_forward_losses_and_perturbation_sampled():
