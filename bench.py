@@ -119,7 +119,7 @@ def cpu_baseline(cfg, specs, budget_note=True):
     t0 = time.perf_counter()
     x = Pd["tok_emb"][tok] + Pd["pos_emb"][:T][None]
     for i in range(nl):
-        x = F.block(x, Pd, i, cfg.n_head, lm, lengths, cfg.ln_eps)
+        x = F.block(x, Pd, i, cfg.n_head, lm, lengths, cfg.ln_eps, cfg.act, cfg.post_ln)
     t_layers = time.perf_counter() - t0
     t0 = time.perf_counter()
     h = F.layer_norm(x, Pd["lnf_g"], Pd["lnf_b"], cfg.ln_eps)
@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--profile-every", type=int, default=5,
                     help="HIP events bracket every kernel launch on one timed step in this many (two event records per "
                          "launch cost about 8 %% of a step, so they are sampled inside the timed region rather than kept on)")
+    ap.add_argument("--act", choices=["gelu", "relu"], default=None, help="feed-forward activation (default: the config's, erf-GELU)")
+    ap.add_argument("--post-ln", action="store_true", help="post-LayerNorm blocks (LayerNorm after each residual sum and on the embeddings)")
     ap.add_argument("--cloud", action="store_true",
                     help="also time the cloud block of Algorithm 1 on the same model and batch: one backward pass, and the basis of one matrix from three gradient snapshots")
     ap.add_argument("--gemm-shapes", action="store_true",
@@ -234,6 +236,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cfg = I.CONFIGS[args.config]
+    if args.act is not None or args.post_ln:
+        cfg = I.shrink(cfg, act=args.act or cfg.act, post_ln=bool(args.post_ln) or cfg.post_ln)
     t0 = time.perf_counter()
     specs, values, bases = inputs_of(cfg)
     if args.non_guided:
@@ -308,7 +312,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {I.CONFIGS[args.config].n_layer}-layer d={cfg.d_model} {'decoder' if cfg.arch == I.ARCH_DECODER_LM else 'encoder classifier'}, batch {cfg.batch} x seq {cfg.seq}, "
-                               f"guided rank k={cfg.k} (basis sent with {cfg.k_full} columns{', 4-bit codes' if args.q4_basis else ''}{', streamed from host memory per layer' if args.stream_bases else ''}), gauss_bits={args.gauss_bits}"
+                               f"{'ReLU feed-forward, ' if cfg.act == 'relu' else ''}{'post-LayerNorm blocks, ' if cfg.post_ln else ''}guided rank k={cfg.k} (basis sent with {cfg.k_full} columns{', 4-bit codes' if args.q4_basis else ''}{', streamed from host memory per layer' if args.stream_bases else ''}), gauss_bits={args.gauss_bits}"
                    if cfg.arch != I.ARCH_LINEAR_LSQ else f"{cfg.name}: linear least squares {cfg.lsq_out}x{cfg.lsq_in}",
                    "params": int(guided_elems + flat_elems), "tokens_per_step": int(cfg.batch * max(cfg.seq, 1))},
         "tokens_per_s": steps_per_s * cfg.batch * max(cfg.seq, 1),
