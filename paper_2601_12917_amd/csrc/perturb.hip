@@ -501,7 +501,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))
   // time the blocks of one XCD work on neighbouring column strips of the same few matrices, walk the same rows and
   // find each other's rows of U in their common L2, and a block's next run lies in other matrices.
   const bool by_xcd = (nblk & 7) == 0;
-  const int n_pass = by_xcd ? kTilePasses : 1;
+  // (a run shorter than a strip of a 2048-row matrix, 16 tiles, would only regenerate R slices more often: short
+  // launches, e.g. one pipeline stage of streamed bases, take fewer runs per block)
+  const int by_len = a.n_tiles / (nblk * 16);
+  const int n_pass = !by_xcd || by_len < 1 ? 1 : (by_len < kTilePasses ? by_len : kTilePasses);
   const int per_xcd = nblk >> 3;
   const int64_t n_runs = (int64_t)nblk * n_pass;          // run r is tiles [r n / R, (r + 1) n / R): lengths differ by at most one
   int prev_tensor = -1;
