@@ -688,7 +688,10 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* _
     for (int j = 0; j < 8; ++j) Vt[(c + j) * ldv + r].bits = ve[j];
   }
   // this wave's queries: B operand of S^T = K Q^T, lane (query l32, k-group half) holds Q[q][16 s + 8 half .. +8]
-  const int q0 = qb * QB + wave * 32;
+  // Under the causal mask a wave's work grows with the position of its queries.  Waves w and w + 4 share a SIMD, so
+  // with eight waves the upper four take their query groups in reverse order: every SIMD then holds the same total.
+  const int qgroup = (NW == 8 && causal && wave >= 4) ? 11 - wave : wave;
+  const int q0 = qb * QB + qgroup * 32;
   const int qi = q0 + l32;
   bf16x8 qf[DH / 16];
 #pragma unroll
@@ -719,32 +722,43 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* _
     }
     // lane: query qi, keys kb*32 + 8*(v/4) + 4*half + v%4; scores in log2 units
     float sv[16], mloc = -INFINITY;
+    if (kb * 32 + 31 < len && (!causal || kb * 32 + 31 <= q0)) {      // every key of the block is visible to every query of the wave
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int key = kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-      const bool ok = key < len && (!causal || key <= qi);
-      sv[v] = ok ? sacc[v] * scale_log2 : -INFINITY;
-      mloc = fmaxf(mloc, sv[v]);
+      for (int v = 0; v < 16; ++v) { sv[v] = sacc[v] * scale_log2; mloc = fmaxf(mloc, sv[v]); }
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        const bool ok = key < len && (!causal || key <= qi);
+        sv[v] = ok ? sacc[v] * scale_log2 : -INFINITY;
+        mloc = fmaxf(mloc, sv[v]);
+      }
     }
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
     const float mnew = fmaxf(mx, mloc);
     const float msafe = mnew == -INFINITY ? 0.f : mnew;
-    const float corr = exp2f(mx - msafe);            // mx = -inf -> 0
+    // v_exp_f32 directly: the arguments are <= 0 (or -inf, which gives 0), so the library routine's range handling is not needed
+    const float corr = __builtin_amdgcn_exp2f(mx - msafe);            // mx = -inf -> 0
     float psum = 0.f;
-    bf16x8 pf[2];
+    union { uint32_t w[4]; bf16x8 v; } pk[2];                          // P^T operand: two probabilities per conversion
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float pv = exp2f(sv[v] - msafe);
-      psum += pv;
-      bf16_t t; from_f32(pv, t);
-      reinterpret_cast<uint16_t*>(&pf[v >> 3])[v & 7] = t.bits;
+    for (int v = 0; v < 16; v += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(sv[v] - msafe), p1 = __builtin_amdgcn_exp2f(sv[v + 1] - msafe);
+      psum += p0 + p1;
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      const f32x2 pp = {p0, p1};
+      pk[v >> 3].w[(v & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
     }
+    const bf16x8 pf[2] = {pk[0].v, pk[1].v};
     lsum = lsum * corr + psum;
     mx = mnew;
+    if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {              // nothing to rescale while no lane's maximum moved
 #pragma unroll
-    for (int f = 0; f < DH / 32; ++f)
+      for (int f = 0; f < DH / 32; ++f)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[f][v] *= corr;
+        for (int v = 0; v < 16; ++v) o[f][v] *= corr;
+    }
     // O^T += V^T P^T: A operand lane (dh row 32 f + l32, half) reads the keys in the accumulator's order
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
