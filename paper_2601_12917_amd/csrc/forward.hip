@@ -126,6 +126,53 @@ __global__ void __launch_bounds__(256) layernorm_reg_kernel(const float* x, cons
   }
 }
 
+// One wave per row (d % 4 == 0, d <= 2048): the row sits in eight float4 per lane, eight 16-byte loads in flight per lane,
+// and both reductions stay inside the wave: no LDS, no workgroup barrier.  Four rows per block.
+template <typename T>
+__global__ void __launch_bounds__(256) layernorm_wave_kernel(const float* x, const T* __restrict__ g, const T* __restrict__ b,
+                                                             T* __restrict__ out, int M, int d, float eps, float* xout) {
+  constexpr int MAXV = 8;
+  const int lane = threadIdx.x & 63;
+  const int row_i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row_i >= M) return;                                          // whole waves leave: no barrier below
+  const float4* row = reinterpret_cast<const float4*>(x + (size_t)row_i * d);
+  const int nv = d >> 2;
+  float4 v[MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int i = lane + 64 * j;
+    v[j] = i < nv ? row[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int i = lane + 64 * j;
+    if (i < nv) {
+      const float a0 = v[j].x - mu, a1 = v[j].y - mu, a2 = v[j].z - mu, a3 = v[j].w - mu;
+      q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
+  T* o = out + (size_t)row_i * d;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int i = lane + 64 * j;
+    if (i < nv) {
+      struct alignas(sizeof(T) * 4) V4 { T e[4]; };
+      const V4 gg = *reinterpret_cast<const V4*>(g + 4 * i), bb = *reinterpret_cast<const V4*>(b + 4 * i);
+      V4 r;
+      const float4 y = make_float4((v[j].x - mu) * rstd * to_f32(gg.e[0]) + to_f32(bb.e[0]), (v[j].y - mu) * rstd * to_f32(gg.e[1]) + to_f32(bb.e[1]),
+                                   (v[j].z - mu) * rstd * to_f32(gg.e[2]) + to_f32(bb.e[2]), (v[j].w - mu) * rstd * to_f32(gg.e[3]) + to_f32(bb.e[3]));
+      from_f32(y.x, r.e[0]); from_f32(y.y, r.e[1]); from_f32(y.z, r.e[2]); from_f32(y.w, r.e[3]);
+      *reinterpret_cast<V4*>(o + 4 * i) = r;
+      if (xout) reinterpret_cast<float4*>(xout + (size_t)row_i * d)[i] = y;          // the row is in registers: xout may be x
+    }
+  }
+}
+
 // ------------------------------------------------------------------ GEMM  C = A W^T (+bias) with epilogues
 // A [M,K] and W [N,K] are K-contiguous.
 //   EPI_STORE: out T [M,N] = acc + bias
@@ -875,6 +922,12 @@ hipError_t launch_embed(int dtype, const int32_t* tok, const void* E, const void
 }
 
 hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void* b, void* out, int M, int d, float eps, hipStream_t s, float* xout) {
+  if (d % 4 == 0 && d <= 2048 && (((uintptr_t)g | (uintptr_t)b | (uintptr_t)out | (uintptr_t)xout) & 15) == 0) {
+    const dim3 grid((unsigned)((M + 3) / 4));
+    if (dtype == 0) hipLaunchKernelGGL(layernorm_wave_kernel<float>, grid, dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, M, d, eps, xout);
+    else            hipLaunchKernelGGL(layernorm_wave_kernel<bf16_t>, grid, dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, M, d, eps, xout);
+    return hipGetLastError();
+  }
   if (d % 4 == 0 && d <= 8192 && (((uintptr_t)g | (uintptr_t)b | (uintptr_t)out | (uintptr_t)xout) & 15) == 0) {
     if (dtype == 0) hipLaunchKernelGGL(layernorm_reg_kernel<float>, dim3(M), dim3(256), 0, s, x, (const float*)g, (const float*)b, (float*)out, d, eps, xout);
     else            hipLaunchKernelGGL(layernorm_reg_kernel<bf16_t>, dim3(M), dim3(256), 0, s, x, (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)out, d, eps, xout);
