@@ -48,15 +48,16 @@ __device__ __forceinline__ float block_max(float v, float* red) {
 }
 
 // ------------------------------------------------------------------ C (+)= alpha A B with general strides
-// C[i][j] = sum_k A[i ars + k acs] B[k brs + j bcs], i < M, j < N, k < K; A fp32 (a gradient), B fp32 or the storage
-// type (a weight or a kept activation).  64 x 64 tile, 16 deep, 4 x 4 outputs per thread.  The two uses:
+// C[i][j] = sum_k A[i ars + k acs] B[k brs + j bcs], i < M, j < N, k < K; A and B fp32 (a gradient) or the storage
+// type (a weight or a kept activation).  64 x 64 tile, 16 deep, 4 x 4 outputs per thread; every output adds its K terms
+// in the order of k.  The two uses on weights:
 //   input gradient   dA [M, K'] = dY [M, N'] W [N', K']      : A = dY (ars = N', acs = 1), B = W  (brs = K', bcs = 1)
 //   weight gradient  dW [N', K'] = dY^T [N', M] A_in [M, K'] : A = dY (ars = 1, acs = N'), B = A_in (brs = K', bcs = 1)
 // Batched over blockIdx.z = z: operand X of batch z starts at X + (z / zdiv) * x_outer + (z % zdiv) * x_inner (elements).
 struct BatchOffsets { int zdiv; int64_t a_outer, a_inner, b_outer, b_inner, c_outer, c_inner; };
 
-template <typename TB>
-__global__ void __launch_bounds__(256) gemm_strided_kernel(const float* __restrict__ A, int64_t ars, int64_t acs, const TB* __restrict__ B, int64_t brs, int64_t bcs,
+template <typename TA, typename TB>
+__global__ void __launch_bounds__(256) gemm_strided_kernel(const TA* __restrict__ A, int64_t ars, int64_t acs, const TB* __restrict__ B, int64_t brs, int64_t bcs,
                                                            float* __restrict__ C, int64_t ldc, int M, int N, int K, float alpha, int accumulate, BatchOffsets bo) {
   __shared__ float As[16][64 + 4], Bs[16][64 + 4];
   {
@@ -72,7 +73,7 @@ __global__ void __launch_bounds__(256) gemm_strided_kernel(const float* __restri
   for (int k0 = 0; k0 < K; k0 += 16) {
     for (int i = threadIdx.x; i < 64 * 16; i += 256) {
       const int ra = a_rows_contig ? (i & 63) : (i >> 4), ka = a_rows_contig ? (i >> 6) : (i & 15);
-      As[ka][ra] = (m0 + ra < M && k0 + ka < K) ? A[(int64_t)(m0 + ra) * ars + (int64_t)(k0 + ka) * acs] : 0.f;
+      As[ka][ra] = (m0 + ra < M && k0 + ka < K) ? to_f32(A[(int64_t)(m0 + ra) * ars + (int64_t)(k0 + ka) * acs]) : 0.f;
       const int cb = b_k_contig ? (i >> 4) : (i & 63), kb = b_k_contig ? (i & 15) : (i >> 6);
       Bs[kb][cb] = (n0 + cb < N && k0 + kb < K) ? to_f32(B[(int64_t)(k0 + kb) * brs + (int64_t)(n0 + cb) * bcs]) : 0.f;
     }
@@ -267,44 +268,28 @@ __global__ void __launch_bounds__(256) add_kernel(float* __restrict__ dst, const
 // ------------------------------------------------------------------ attention
 // qkv [B T, 3 d]: query, key, value of head h at columns h dh, d + h dh, 2 d + h dh.  Key j takes part in query i's
 // softmax when j < length (the sequence's length, or T) and, under the causal mask, j <= i.
-//
-// Per query row (one block per (b, h, i)): p = softmax(q k^T / sqrt dh), dp_j = dctx_i . v_j, ds = p (dp - p . dp);
-// P and dS rows (zeros at masked keys) go to memory for the key-side products, dq_i = sum_j ds_j k_j / sqrt dh.
-template <typename T>
-__global__ void __launch_bounds__(256) attn_backward_query_kernel(const T* __restrict__ qkv, const float* __restrict__ dctx, const int32_t* __restrict__ lengths,
-                                                                  int seq, int d, int n_head, int dh, int causal, float* __restrict__ P, float* __restrict__ dS,
-                                                                  float* __restrict__ dqkv) {
-  extern __shared__ float sm[];          // q [dh], do [dh], ds [seq]
+// Five batched products per head and one row-wise rule between them:
+//   S = Q K^T / sqrt dh and dP = dctx V^T             (into the P and dS buffers)
+//   p = softmax(S) over the visible keys, ds = p (dP - p . dP), zeros at masked keys        (attn_backward_rows_kernel, in place)
+//   dQ = dS K / sqrt dh,   dK = dS^T Q / sqrt dh,   dV = P^T dctx
+// One block per row (b, h, i) of the two [T, T] buffers; a thread holds up to MAXJ of the row's entries (T <= 256 MAXJ).
+__global__ void __launch_bounds__(256) attn_backward_rows_kernel(const int32_t* __restrict__ lengths, int seq, int n_head, int causal,
+                                                                 float* __restrict__ P, float* __restrict__ dS) {
   __shared__ float red[4];
-  float* qs = sm; float* dos = sm + dh; float* dss = sm + 2 * dh;
-  const int i = blockIdx.x % seq, h = (blockIdx.x / seq) % n_head, b = blockIdx.x / (seq * n_head);
-  const size_t ld = (size_t)3 * d;
-  const T* base = qkv + (size_t)b * seq * ld + (size_t)h * dh;
-  const float scale = 1.0f / sqrtf((float)dh);
+  const int i = blockIdx.x % seq, b = blockIdx.x / (seq * n_head);
   int kend = lengths ? lengths[b] : seq;
   kend = kend < seq ? kend : seq;
   if (causal) kend = kend < i + 1 ? kend : i + 1;
-  for (int t = threadIdx.x; t < dh; t += 256) {
-    qs[t] = to_f32(base[(size_t)i * ld + t]);
-    dos[t] = dctx[((size_t)b * seq + i) * d + (size_t)h * dh + t];
-  }
-  __syncthreads();
-  // scores and dp for this thread's keys (seq <= 256 * 8)
-  constexpr int MAXJ = 8;
+  float* prow = P + (size_t)blockIdx.x * seq;
+  float* srow = dS + (size_t)blockIdx.x * seq;
+  constexpr int MAXJ = kBackwardMaxSeq / 256;
   float sc[MAXJ], dp[MAXJ];
   float mx = -INFINITY;
 #pragma unroll
   for (int u = 0; u < MAXJ; ++u) {
     const int j = threadIdx.x + 256 * u;
     sc[u] = -INFINITY; dp[u] = 0.f;
-    if (j < kend) {
-      const T* kr = base + (size_t)j * ld + d;
-      const T* vr = base + (size_t)j * ld + 2 * d;
-      float s = 0.f, p = 0.f;
-      for (int t = 0; t < dh; ++t) { s = __builtin_fmaf(qs[t], to_f32(kr[t]), s); p = __builtin_fmaf(dos[t], to_f32(vr[t]), p); }
-      sc[u] = s * scale; dp[u] = p;
-      mx = fmaxf(mx, sc[u]);
-    }
+    if (j < kend) { sc[u] = prow[j]; dp[u] = srow[j]; mx = fmaxf(mx, sc[u]); }
   }
   mx = block_max(mx, red);
   float den = 0.f;
@@ -316,25 +301,12 @@ __global__ void __launch_bounds__(256) attn_backward_query_kernel(const T* __res
 #pragma unroll
   for (int u = 0; u < MAXJ; ++u) { sc[u] *= inv; dot += sc[u] * dp[u]; }
   dot = block_sum(dot, red);
-  float* prow = P + (((size_t)b * n_head + h) * seq + i) * seq;
-  float* srow = dS + (((size_t)b * n_head + h) * seq + i) * seq;
 #pragma unroll
   for (int u = 0; u < MAXJ; ++u) {
     const int j = threadIdx.x + 256 * u;
-    if (j < seq) {
-      const float ds = sc[u] * (dp[u] - dot);
-      prow[j] = sc[u]; srow[j] = ds; dss[j] = ds;
-    }
-  }
-  __syncthreads();
-  for (int t = threadIdx.x; t < dh; t += 256) {
-    float a = 0.f;
-    for (int j = 0; j < kend; ++j) a = __builtin_fmaf(dss[j], to_f32(base[(size_t)j * ld + d + t]), a);
-    dqkv[((size_t)b * seq + i) * ld + (size_t)h * dh + t] = a * scale;
+    if (j < seq) { prow[j] = sc[u]; srow[j] = sc[u] * (dp[u] - dot); }
   }
 }
-
-// The key side, dK = dS^T Q / sqrt dh and dV = P^T dctx per head, are two batched products of gemm_strided_kernel.
 
 // ------------------------------------------------------------------ embeddings
 // x0[m] = E[tok[m]] + Pe[m mod seq]: one thread per column walks the rows in order (tokens repeat, so the adds into
@@ -357,19 +329,20 @@ __global__ void __launch_bounds__(256) embed_backward_kernel(const int32_t* __re
 
 static unsigned grid_1d(int64_t n) { const int64_t b = (n + 255) / 256; return (unsigned)(b < 1 ? 1 : (b > 4096 ? 4096 : b)); }
 
-static hipError_t launch_bw_gemm_batched(int b_dtype, const float* A, int64_t ars, int64_t acs, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
+template <typename TA>
+static hipError_t launch_bw_gemm_batched(const TA* A, int64_t ars, int64_t acs, int b_dtype, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
                                          int M, int N, int K, float alpha, int accumulate, int batches, const BatchOffsets& bo, hipStream_t s) {
   if (M < 1 || N < 1 || batches < 1) return hipSuccess;
-  if (batches > 65535) return hipErrorInvalidValue;
+  if (batches > 65535 || (M + 63) / 64 > 65535) return hipErrorInvalidValue;
   const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64), (unsigned)batches);
-  if (b_dtype == 1) hipLaunchKernelGGL(gemm_strided_kernel<bf16_t>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const bf16_t*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate, bo);
-  else              hipLaunchKernelGGL(gemm_strided_kernel<float>, grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const float*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate, bo);
+  if (b_dtype == 1) hipLaunchKernelGGL((gemm_strided_kernel<TA, bf16_t>), grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const bf16_t*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate, bo);
+  else              hipLaunchKernelGGL((gemm_strided_kernel<TA, float>), grid, dim3(256), 0, s, A, ars, acs, reinterpret_cast<const float*>(B), brs, bcs, C, ldc, M, N, K, alpha, accumulate, bo);
   return hipGetLastError();
 }
 
 hipError_t launch_bw_gemm(int b_dtype, const float* A, int64_t ars, int64_t acs, const void* B, int64_t brs, int64_t bcs, float* C, int64_t ldc,
                           int M, int N, int K, float alpha, int accumulate, hipStream_t s) {
-  return launch_bw_gemm_batched(b_dtype, A, ars, acs, B, brs, bcs, C, ldc, M, N, K, alpha, accumulate, 1, BatchOffsets{1, 0, 0, 0, 0, 0, 0}, s);
+  return launch_bw_gemm_batched(A, ars, acs, b_dtype, B, brs, bcs, C, ldc, M, N, K, alpha, accumulate, 1, BatchOffsets{1, 0, 0, 0, 0, 0, 0}, s);
 }
 
 hipError_t launch_bw_transpose_bf16(int in_dtype, const void* in, int rows, int cols, int64_t ld_in, void* out, int64_t ld_out, hipStream_t s) {
@@ -445,23 +418,34 @@ hipError_t launch_bw_add(float* dst, const float* src, int64_t n, hipStream_t s)
 
 hipError_t launch_bw_attention(int dtype, const void* qkv, const float* dctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal,
                                float* P, float* dS, float* dqkv, hipStream_t s) {
-  if (seq > kBackwardMaxSeq || d % n_head != 0) return hipErrorInvalidValue;
-  const int dh = d / n_head;
-  const size_t lds = (size_t)(2 * dh + seq) * sizeof(float);
-  if (lds > 48 * 1024) return hipErrorInvalidValue;
-  const unsigned blocks = (unsigned)batch * n_head * seq;
-  if (dtype == 1) hipLaunchKernelGGL(attn_backward_query_kernel<bf16_t>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const bf16_t*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
-  else            hipLaunchKernelGGL(attn_backward_query_kernel<float>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const float*>(qkv), dctx, lengths, seq, d, n_head, dh, causal, P, dS, dqkv);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  // per head z = (b, h): dK [T, dh] = dS^T Q / sqrt dh, dV [T, dh] = P^T dctx; A(j, i) = X[i T + j]
+  if (batch < 1 || seq < 1 || n_head < 1 || seq > kBackwardMaxSeq || d % n_head != 0) return hipErrorInvalidValue;
+  const int dh = d / n_head, heads = batch * n_head;
+  // head z = (b, h): the [T, T] buffers are consecutive in z; q, k, v of the head are the columns h dh, d + h dh, 2 d + h dh of
+  // the [T, 3 d] rows of sequence b, dctx its columns h dh of [T, d] rows
   const int64_t tt = (int64_t)seq * seq, ld = (int64_t)3 * d;
   const float scale = 1.0f / sqrtf((float)dh);
-  BatchOffsets bk{n_head, n_head * tt, tt, (int64_t)seq * ld, dh, (int64_t)seq * ld, dh};
-  e = launch_bw_gemm_batched(dtype, dS, 1, seq, qkv, ld, 1, dqkv + d, ld, seq, dh, seq, scale, 0, batch * n_head, bk, s);
+  const int64_t sq_outer = (int64_t)seq * ld, dc_outer = (int64_t)seq * d, p_outer = n_head * tt;
+  hipError_t e;
+  // S [i][j] = sum_t q[i][t] k[j][t] / sqrt dh
+  const BatchOffsets bs{n_head, sq_outer, dh, sq_outer, dh, p_outer, tt};
+  if (dtype == 1) e = launch_bw_gemm_batched(reinterpret_cast<const bf16_t*>(qkv), ld, 1, dtype, reinterpret_cast<const bf16_t*>(qkv) + d, 1, ld, P, seq, seq, seq, dh, scale, 0, heads, bs, s);
+  else            e = launch_bw_gemm_batched(reinterpret_cast<const float*>(qkv), ld, 1, dtype, reinterpret_cast<const float*>(qkv) + d, 1, ld, P, seq, seq, seq, dh, scale, 0, heads, bs, s);
   if (e != hipSuccess) return e;
-  BatchOffsets bv{n_head, n_head * tt, tt, (int64_t)seq * d, dh, (int64_t)seq * ld, dh};
-  return launch_bw_gemm_batched(0, P, 1, seq, dctx, d, 1, dqkv + 2 * d, ld, seq, dh, seq, 1.0f, 0, batch * n_head, bv, s);
+  // dP [i][j] = sum_t dctx[i][t] v[j][t]
+  const void* v0 = dtype == 1 ? (const void*)(reinterpret_cast<const bf16_t*>(qkv) + 2 * d) : (const void*)(reinterpret_cast<const float*>(qkv) + 2 * d);
+  e = launch_bw_gemm_batched(dctx, (int64_t)d, 1, dtype, v0, 1, ld, dS, seq, seq, seq, dh, 1.0f, 0, heads, BatchOffsets{n_head, dc_outer, dh, sq_outer, dh, p_outer, tt}, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_backward_rows_kernel, dim3((unsigned)heads * seq), dim3(256), 0, s, lengths, seq, n_head, causal, P, dS);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // dQ [i][t] = sum_j dS[i][j] k[j][t] / sqrt dh
+  const void* k0 = dtype == 1 ? (const void*)(reinterpret_cast<const bf16_t*>(qkv) + d) : (const void*)(reinterpret_cast<const float*>(qkv) + d);
+  e = launch_bw_gemm_batched(dS, (int64_t)seq, 1, dtype, k0, ld, 1, dqkv, ld, seq, dh, seq, scale, 0, heads, BatchOffsets{n_head, p_outer, tt, sq_outer, dh, sq_outer, dh}, s);
+  if (e != hipSuccess) return e;
+  // dK [j][t] = sum_i dS[i][j] q[i][t] / sqrt dh,  dV [j][t] = sum_i P[i][j] dctx[i][t]
+  e = launch_bw_gemm_batched(dS, 1, (int64_t)seq, dtype, qkv, ld, 1, dqkv + d, ld, seq, dh, seq, scale, 0, heads, BatchOffsets{n_head, p_outer, tt, sq_outer, dh, sq_outer, dh}, s);
+  if (e != hipSuccess) return e;
+  return launch_bw_gemm_batched(P, 1, (int64_t)seq, 0, dctx, (int64_t)d, 1, dqkv + 2 * d, ld, seq, dh, seq, 1.0f, 0, heads, BatchOffsets{n_head, p_outer, tt, dc_outer, dh, sq_outer, dh}, s);
 }
 
 hipError_t launch_bw_embedding(const int32_t* tok, const float* dx, int M, int seq, int d, int vocab, float* dE, float* dPe, int max_pos, hipStream_t s) {
