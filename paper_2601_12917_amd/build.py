@@ -10,14 +10,17 @@ SOURCES = ["api.hip", "perturb.hip", "forward.hip", "ceilings.hip", "cloud.hip",
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
+STEP_KERNEL_SOURCES = ("perturb.hip", "forward.hip", "forward.h", "rng.h", "internal.h")
+
 
 def source_digest() -> str:
-    """sha256 over the kernel sources (everything under csrc/ but the host runtime api.hip): identifies the
-    device code that hardware-counter figures were taken on."""
+    """sha256 over the sources of the client step's kernels (perturbation passes and forward pass, with the headers
+    they include): identifies the device code that hardware-counter figures were taken on.  The host runtime, the
+    cloud-side kernels and the micro-benchmarks are not part of it."""
     import hashlib
     h = hashlib.sha256()
     for name in sorted(os.listdir(CSRC)):
-        if name.endswith((".hip", ".h")) and name != "api.hip":
+        if name in STEP_KERNEL_SOURCES:
             h.update(name.encode())
             h.update(open(os.path.join(CSRC, name), "rb").read())
     return h.hexdigest()

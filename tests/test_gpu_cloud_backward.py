@@ -54,10 +54,14 @@ TINY_CLS = dict(name="bw_cls", arch=I.ARCH_ENCODER_CLS, n_class=3, n_layer=2, d_
 
 
 VARIANT_KW = {"lm_relu": dict(TINY_LM, name="bw_lm_relu", act="relu"), "cls_postln": dict(TINY_CLS, name="bw_cls_postln", post_ln=True),
-              "lm_relu_postln": dict(TINY_LM, name="bw_lm_relu_postln", act="relu", post_ln=True)}
+              "lm_relu_postln": dict(TINY_LM, name="bw_lm_relu_postln", act="relu", post_ln=True),
+              # sequences past 256 tokens: a thread of the row-wise softmax rule holds two entries of a row, the [T, T] buffers span
+              # five 64-wide tiles with a ragged last one
+              "lm_long": dict(TINY_LM, name="bw_lm_long", n_layer=1, d_model=32, n_head=2, d_ff=64, vocab=101, max_pos=320, batch=2, seq=300),
+              "cls_long": dict(TINY_CLS, name="bw_cls_long", n_layer=1, d_model=32, n_head=2, d_ff=64, vocab=101, max_pos=320, batch=3, seq=290)}
 
 
-@pytest.mark.parametrize("which", ["lm", "cls", "cfg2", "lm_relu", "cls_postln", "lm_relu_postln"])
+@pytest.mark.parametrize("which", ["lm", "cls", "cfg2", "lm_relu", "cls_postln", "lm_relu_postln", "lm_long", "cls_long"])
 def test_fp32_gradients_match_the_oracle_entry_by_entry(which, say):
     """The default model (pre-LayerNorm, erf-GELU) and the two switches of the paper's model families."""
     cfg = I.CONFIGS["cfg2"] if which == "cfg2" else I.shrink(I.CONFIGS["cfg2"], **(VARIANT_KW[which] if which in VARIANT_KW else TINY_LM if which == "lm" else TINY_CLS))
