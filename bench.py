@@ -213,6 +213,8 @@ def main():
                          "launch cost about 8 %% of a step, so they are sampled inside the timed region rather than kept on)")
     ap.add_argument("--act", choices=["gelu", "relu"], default=None, help="feed-forward activation (default: the config's, erf-GELU)")
     ap.add_argument("--post-ln", action="store_true", help="post-LayerNorm blocks (LayerNorm after each residual sum and on the embeddings)")
+    ap.add_argument("--batch", type=int, default=None, help="sequences per batch (default: the config's)")
+    ap.add_argument("--seq", type=int, default=None, help="tokens per sequence (default: the config's; at most the model's max_pos)")
     ap.add_argument("--cloud", action="store_true",
                     help="also time the cloud block of Algorithm 1 on the same model and batch: one backward pass, and the basis of one matrix from three gradient snapshots")
     ap.add_argument("--gemm-shapes", action="store_true",
@@ -238,6 +240,11 @@ def main():
     cfg = I.CONFIGS[args.config]
     if args.act is not None or args.post_ln:
         cfg = I.shrink(cfg, act=args.act or cfg.act, post_ln=bool(args.post_ln) or cfg.post_ln)
+    if args.batch is not None or args.seq is not None:
+        cfg = I.shrink(cfg, batch=args.batch or cfg.batch, seq=args.seq or cfg.seq)
+        if cfg.batch < 1 or cfg.seq < 2 or cfg.seq > cfg.max_pos:
+            print("bench.py: --batch / --seq outside the model's limits (seq <= max_pos = %d)" % cfg.max_pos, file=sys.stderr)
+            sys.exit(2)
     t0 = time.perf_counter()
     specs, values, bases = inputs_of(cfg)
     if args.non_guided:

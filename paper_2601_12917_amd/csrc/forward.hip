@@ -693,13 +693,15 @@ __global__ void __launch_bounds__(256) attention_kernel(const T* __restrict__ qk
 }
 
 // MFMA attention for bf16 storage and head size 64.  One block = 128 queries of one (batch, head):
-// K [keys][64] and V^T [64][keys] are staged in LDS once; each wave owns 32 queries and walks the keys in
+// K [keys][64] and V^T [64][keys] are staged in LDS (all keys at once up to AT_KCH of them, chunk after chunk of
+// AT_KCH beyond: the online softmax carries over); each wave owns 32 queries and walks the keys in
 // blocks of 32, computing S^T = K Q^T and O^T += V^T P^T with v_mfma_f32_32x32x16_bf16.  In the S^T
 // result a lane holds one query column and 16 keys in registers, so the softmax reductions run over
 // registers plus one exchange with the partner lane (lane ^ 32); P goes straight from the accumulator
 // registers into the B operand of the second product (the contraction order of that product is the
 // accumulator's key order, which the V^T operand is read in as well).
 constexpr int AT_LDK = 64 + 8;          // K row stride (bf16): 144 B
+constexpr int AT_KCH = 512;             // keys staged at a time: 72 KB of K rows + 65 KB of V^T
 // NW waves per block, 32 queries each: with NW = 8 one block covers 256 queries of a head, so K and V^T of a
 // 256-token sequence are staged once per head instead of once per 128 queries.
 template <int DH, int NW>
@@ -721,19 +723,6 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* _
   int kend = len;
   if (causal) kend = min(kend, qb * QB + QB);
   const int kblocks = (kend + 31) / 32;
-  // stage K and V^T (zero beyond seq so masked products stay finite)
-  for (int i = tid; i < kblocks * 32 * 8; i += NT) {
-    const int r = i >> 3, c = (i & 7) * 8;
-    uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-    if (r < seq) {
-      kv = *reinterpret_cast<const uint4*>(base + (size_t)r * ld + d + c);
-      vv = *reinterpret_cast<const uint4*>(base + (size_t)r * ld + 2 * d + c);
-    }
-    *reinterpret_cast<uint4*>(Ks + r * AT_LDK + c) = kv;
-    const uint16_t* ve = reinterpret_cast<const uint16_t*>(&vv);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) Vt[(c + j) * ldv + r].bits = ve[j];
-  }
   // this wave's queries: B operand of S^T = K Q^T, lane (query l32, k-group half) holds Q[q][16 s + 8 half .. +8]
   // Under the causal mask a wave's work grows with the position of its queries.  Waves w and w + 4 share a SIMD, so
   // with eight waves the upper four take their query groups in reverse order: every SIMD then holds the same total.
@@ -747,7 +736,6 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* _
     if (qi < seq) t = *reinterpret_cast<const uint4*>(base + (size_t)qi * ld + s4 * 16 + half * 8);
     qf[s4] = *reinterpret_cast<bf16x8*>(&t);
   }
-  __syncthreads();
   f32x16 o[DH / 32];
 #pragma unroll
   for (int f = 0; f < DH / 32; ++f)
@@ -758,63 +746,82 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* _
   int wave_kblocks = kblocks;
   if (causal) wave_kblocks = min(kblocks, (q0 + 31) / 32 + 1);
   if (q0 >= seq) wave_kblocks = 0;
-  for (int kb = 0; kb < wave_kblocks; ++kb) {
-    f32x16 sacc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
-#pragma unroll
-    for (int s4 = 0; s4 < DH / 16; ++s4) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + l32) * AT_LDK + s4 * 16 + half * 8);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s4], sacc, 0, 0, 0);
-    }
-    // lane: query qi, keys kb*32 + 8*(v/4) + 4*half + v%4; scores in log2 units
-    float sv[16], mloc = -INFINITY;
-    if (kb * 32 + 31 < len && (!causal || kb * 32 + 31 <= q0)) {      // every key of the block is visible to every query of the wave
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { sv[v] = sacc[v] * scale_log2; mloc = fmaxf(mloc, sv[v]); }
-    } else {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        const bool ok = key < len && (!causal || key <= qi);
-        sv[v] = ok ? sacc[v] * scale_log2 : -INFINITY;
-        mloc = fmaxf(mloc, sv[v]);
+  for (int c0 = 0; c0 < kblocks; c0 += AT_KCH / 32) {                 // key chunks: the same trip count for every wave of the block
+    const int c_end = min(kblocks, c0 + AT_KCH / 32);
+    if (c0 > 0) __syncthreads();                                         // every wave is done with the previous chunk
+    // stage K and V^T of key blocks [c0, c_end) (zero beyond seq so masked products stay finite)
+    for (int i = tid; i < (c_end - c0) * 32 * 8; i += NT) {
+      const int r = i >> 3, c = (i & 7) * 8, key = c0 * 32 + r;
+      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (key < seq) {
+        kv = *reinterpret_cast<const uint4*>(base + (size_t)key * ld + d + c);
+        vv = *reinterpret_cast<const uint4*>(base + (size_t)key * ld + 2 * d + c);
       }
+      *reinterpret_cast<uint4*>(Ks + r * AT_LDK + c) = kv;
+      const uint16_t* ve = reinterpret_cast<const uint16_t*>(&vv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) Vt[(c + j) * ldv + r].bits = ve[j];
     }
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    const float mnew = fmaxf(mx, mloc);
-    const float msafe = mnew == -INFINITY ? 0.f : mnew;
-    // v_exp_f32 directly: the arguments are <= 0 (or -inf, which gives 0), so the library routine's range handling is not needed
-    const float corr = __builtin_amdgcn_exp2f(mx - msafe);            // mx = -inf -> 0
-    float psum = 0.f;
-    union { uint32_t w[4]; bf16x8 v; } pk[2];                          // P^T operand: two probabilities per conversion
+    __syncthreads();
+    for (int kb = c0; kb < min(c_end, wave_kblocks); ++kb) {
+      const int kl = (kb - c0) * 32;                                      // the block's first key within the staged chunk
+      f32x16 sacc;
 #pragma unroll
-    for (int v = 0; v < 16; v += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(sv[v] - msafe), p1 = __builtin_amdgcn_exp2f(sv[v + 1] - msafe);
-      psum += p0 + p1;
-      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-      typedef float f32x2 __attribute__((ext_vector_type(2)));
-      const f32x2 pp = {p0, p1};
-      pk[v >> 3].w[(v & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-    }
-    const bf16x8 pf[2] = {pk[0].v, pk[1].v};
-    lsum = lsum * corr + psum;
-    mx = mnew;
-    if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {              // nothing to rescale while no lane's maximum moved
+      for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
-      for (int f = 0; f < DH / 32; ++f)
+      for (int s4 = 0; s4 < DH / 16; ++s4) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kl + l32) * AT_LDK + s4 * 16 + half * 8);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s4], sacc, 0, 0, 0);
+      }
+      // lane: query qi, keys kb*32 + 8*(v/4) + 4*half + v%4; scores in log2 units
+      float sv[16], mloc = -INFINITY;
+      if (kb * 32 + 31 < len && (!causal || kb * 32 + 31 <= q0)) {      // every key of the block is visible to every query of the wave
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[f][v] *= corr;
-    }
-    // O^T += V^T P^T: A operand lane (dh row 32 f + l32, half) reads the keys in the accumulator's order
+        for (int v = 0; v < 16; ++v) { sv[v] = sacc[v] * scale_log2; mloc = fmaxf(mloc, sv[v]); }
+      } else {
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
+        for (int v = 0; v < 16; ++v) {
+          const int key = kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+          const bool ok = key < len && (!causal || key <= qi);
+          sv[v] = ok ? sacc[v] * scale_log2 : -INFINITY;
+          mloc = fmaxf(mloc, sv[v]);
+        }
+      }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      const float mnew = fmaxf(mx, mloc);
+      const float msafe = mnew == -INFINITY ? 0.f : mnew;
+      // v_exp_f32 directly: the arguments are <= 0 (or -inf, which gives 0), so the library routine's range handling is not needed
+      const float corr = __builtin_amdgcn_exp2f(mx - msafe);            // mx = -inf -> 0
+      float psum = 0.f;
+      union { uint32_t w[4]; bf16x8 v; } pk[2];                          // P^T operand: two probabilities per conversion
 #pragma unroll
-      for (int f = 0; f < DH / 32; ++f) {
-        const bf16_t* vr = Vt + (f * 32 + l32) * ldv + kb * 32 + st * 16 + 4 * half;
-        const uint2 lo = *reinterpret_cast<const uint2*>(vr), hi = *reinterpret_cast<const uint2*>(vr + 8);
-        uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&t), pf[st], o[f], 0, 0, 0);
+      for (int v = 0; v < 16; v += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(sv[v] - msafe), p1 = __builtin_amdgcn_exp2f(sv[v + 1] - msafe);
+        psum += p0 + p1;
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        const f32x2 pp = {p0, p1};
+        pk[v >> 3].w[(v & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+      }
+      const bf16x8 pf[2] = {pk[0].v, pk[1].v};
+      lsum = lsum * corr + psum;
+      mx = mnew;
+      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {              // nothing to rescale while no lane's maximum moved
+#pragma unroll
+        for (int f = 0; f < DH / 32; ++f)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[f][v] *= corr;
+      }
+      // O^T += V^T P^T: A operand lane (dh row 32 f + l32, half) reads the keys in the accumulator's order
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+#pragma unroll
+        for (int f = 0; f < DH / 32; ++f) {
+          const bf16_t* vr = Vt + (f * 32 + l32) * ldv + kl + st * 16 + 4 * half;
+          const uint2 lo = *reinterpret_cast<const uint2*>(vr), hi = *reinterpret_cast<const uint2*>(vr + 8);
+          uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&t), pf[st], o[f], 0, 0, 0);
+        }
       }
     }
   }
@@ -988,8 +995,8 @@ static hipError_t launch_attention_t(const T* qkv, T* ctx, const int32_t* length
 }
 
 hipError_t launch_attention(int dtype, const void* qkv, void* ctx, const int32_t* lengths, int batch, int seq, int d, int n_head, int causal, hipStream_t s) {
-  if (dtype == 1 && d / n_head == 64 && seq <= 512 && d % 8 == 0) {
-    const int kpad = (seq + 31) / 32 * 32;
+  if (dtype == 1 && d / n_head == 64 && d % 8 == 0) {
+    const int kpad = seq < AT_KCH ? (seq + 31) / 32 * 32 : AT_KCH;          // keys resident in LDS at a time
     const size_t lds = sizeof(bf16_t) * ((size_t)kpad * AT_LDK + (size_t)64 * (kpad + 8));
     static bool attr_set = false;
     if (!attr_set) {

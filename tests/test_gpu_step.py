@@ -23,6 +23,10 @@ SMALL_BF16_LM = I.shrink(I.CONFIGS["cfg3"], name="small_bf16_lm", n_layer=2, d_m
                          max_pos=64, batch=3, seq=40, k=16, k_full=16)
 SMALL_BF16_CLS = I.shrink(I.CONFIGS["cfg4"], name="small_bf16_cls", n_layer=2, d_model=128, n_head=2, d_ff=192, vocab=777,
                           max_pos=64, batch=5, seq=33, k=32, k_full=32)
+# sequences past the 512 keys the matrix-core attention kernel holds in LDS at a time: three key chunks with a ragged last one
+# (decoder, causal), two chunks with padded sequences that end in the first or the second (encoder)
+LONG_BF16_LM = I.shrink(SMALL_BF16_LM, name="long_bf16_lm", max_pos=1100, batch=1, seq=1100)
+LONG_BF16_CLS = I.shrink(SMALL_BF16_CLS, name="long_bf16_cls", max_pos=700, batch=4, seq=700)
 # the two model families of the paper's experiments: ReLU feed-forward (decoder), post-LayerNorm blocks (encoder), and both
 VARIANTS = [I.shrink(TINY_LM, name="tiny_lm_relu", act="relu"),
             I.shrink(TINY_CLS, name="tiny_cls_postln", post_ln=True),
@@ -57,13 +61,15 @@ def _bf16_margin(got, want, eps_z=None):
     return worst, int(np.sum(dev > PARAM_RTOL["bf16"] * mag + 1e-30)), int(np.sum(got != want))
 
 
-@pytest.mark.parametrize("cfg", [TINY_LM, TINY_CLS, I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS] + VARIANTS, ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TINY_LM, TINY_CLS, I.CONFIGS["cfg2"], SMALL_BF16_LM, SMALL_BF16_CLS, LONG_BF16_LM, LONG_BF16_CLS] + VARIANTS, ids=lambda c: c.name)
 def test_loss_and_row_losses_match_oracle(cfg):
     specs, values, bases = inputs_of(cfg)
     # a 10x larger init than N(0, 0.02) so that attention and the MLP are far from trivial
     values = [v if s.role in (I.ROLE_LN1_G, I.ROLE_LN2_G, I.ROLE_LNF_G) else (P.bf16_round(v * np.float32(8)) if cfg.dtype == "bf16" else v * np.float32(8))
               for s, v in zip(specs, values)]
     arrays = make_batch_arrays(cfg)
+    if cfg.name == "long_bf16_cls":
+        arrays["lengths"] = np.array([700, 513, 300, 640], dtype=np.int32)      # ends in the second key chunk, one key into it, in the first
     sess = make_session(cfg, specs, values, bases)
     got = sess.loss(session_batch(sess, cfg, arrays))
     Pd = _params_dict(specs, values)
@@ -86,6 +92,8 @@ def test_loss_and_row_losses_match_oracle(cfg):
     (TINY_LM, dict(batch=1, seq=13)),           # odd length, a single sequence
     (SMALL_BF16_LM, dict(batch=1, seq=2)),
     (SMALL_BF16_LM, dict(batch=2, seq=37)),     # not a multiple of any tile
+    (SMALL_BF16_LM, dict(batch=2, seq=512)),    # exactly one full key chunk of the matrix-core attention kernel
+    (SMALL_BF16_LM, dict(batch=1, seq=513)),    # one key into the second chunk
     (TINY_CLS, dict(batch=1, seq=1)),           # one token: attention over a single key
     (SMALL_BF16_CLS, dict(batch=3, seq=5)),
 ], ids=lambda x: x.name if hasattr(x, "name") else "-".join(f"{k}{v}" for k, v in x.items()))
