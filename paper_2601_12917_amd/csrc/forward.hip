@@ -714,7 +714,12 @@ __global__ void __launch_bounds__(64 * NW) attention_mfma_kernel(const bf16_t* _
   bf16_t* Vt = Ks + (size_t)kpad * AT_LDK;                      // [DH][kpad + 8]
   const int ldv = kpad + 8;
   const int qblocks = (seq + QB - 1) / QB;
-  const int qb = blockIdx.x % qblocks, h = (blockIdx.x / qblocks) % n_head, b = blockIdx.x / (qblocks * n_head);
+  // Under the causal mask a query block's work grows with its position: the blocks are handed out longest first (all heads'
+  // last query blocks, then the ones before, ...), so that the short ones fill the gaps at the end of the launch.
+  const int heads = gridDim.x / qblocks;
+  const int qb = (causal && qblocks > 1) ? qblocks - 1 - (int)blockIdx.x / heads : (int)blockIdx.x % qblocks;
+  const int bh = (causal && qblocks > 1) ? (int)blockIdx.x % heads : (int)blockIdx.x / qblocks;
+  const int h = bh % n_head, b = bh / n_head;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
   const int len = lengths ? min(lengths[b], seq) : seq;
   const size_t ld = (size_t)3 * d;
