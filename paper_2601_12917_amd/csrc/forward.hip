@@ -967,7 +967,7 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
     if (t192 >= 256 && N % 192 == 0) return launch_gemm_bf16_t<256, 192, 4, 2, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
     if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
     if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
-    return launch_gemm_bf16_t<128, 128, 2, 2, 64, 4>(a, w, b, out, epi, M, N, K, s);
+    return launch_gemm_bf16_t<128, 128, 2, 4, 64, 4>(a, w, b, out, epi, M, N, K, s);
   }
   return hipGetLastError();
 }
