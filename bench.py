@@ -144,9 +144,11 @@ def gemm_shapes(args, torch, I, B):
     product has no debug entry; it is timed inside the step only."""
     import ctypes as C
     cfg = I.CONFIGS[args.config]
-    if cfg.dtype != "bf16" or cfg.arch == I.ARCH_LINEAR_LSQ:
-        print("bench.py --gemm-shapes: needs a bf16 transformer config", file=sys.stderr)
+    if cfg.arch == I.ARCH_LINEAR_LSQ:
+        print("bench.py --gemm-shapes: needs a transformer config", file=sys.stderr)
         sys.exit(2)
+    dt = args.gemm_dtype or cfg.dtype            # the config's shapes in either storage type
+    tdt, code = (torch.bfloat16, 1) if dt == "bf16" else (torch.float32, 0)
     if not os.path.exists(B.LIB_PATH):
         from paper_2601_12917_amd.build import build
         build()
@@ -159,12 +161,12 @@ def gemm_shapes(args, torch, I, B):
     rows = []
     # two rounds over the shapes, the second one kept: the first launches of a fresh process run while the clock ramps
     for rnd, (name, m, n, k, epi) in [(r, sh) for r in range(2) for sh in shapes]:
-        A = (torch.randn(m, k, generator=g) * 0.5).bfloat16().to(dev)
-        W = (torch.randn(n, k, generator=g) * 0.05).bfloat16().to(dev)
-        bias = (torch.randn(n, generator=g) * 0.1).bfloat16().to(dev)
-        out = torch.zeros(m, n, device=dev, dtype=torch.float32 if epi == 2 else torch.bfloat16)
+        A = (torch.randn(m, k, generator=g) * 0.5).to(tdt).to(dev)
+        W = (torch.randn(n, k, generator=g) * 0.05).to(tdt).to(dev)
+        bias = (torch.randn(n, generator=g) * 0.1).to(tdt).to(dev)
+        out = torch.zeros(m, n, device=dev, dtype=torch.float32 if epi == 2 else tdt)
         def run():
-            B.check(lib.zgr_debug_gemm(1, A.data_ptr(), W.data_ptr(), bias.data_ptr(), out.data_ptr(), epi, m, n, k, st))
+            B.check(lib.zgr_debug_gemm(code, A.data_ptr(), W.data_ptr(), bias.data_ptr(), out.data_ptr(), epi, m, n, k, st))
         def timed(fn, reps=max(args.steps, 20)):
             for _ in range(max(args.warmup, 3)):
                 fn()
@@ -185,8 +187,8 @@ def gemm_shapes(args, torch, I, B):
             rows.append(row)
     tot_us = sum(r["us"] * r["launches_per_forward"] for r in rows)
     tot_fl = sum(2.0 * r["M"] * r["N"] * r["K"] * r["launches_per_forward"] for r in rows)
-    print(json.dumps({"metric": "forward GEMM shapes", "config": {"workload": cfg.name}, "dtype": "bf16", "data": "synthetic (random operands)",
-                      "shapes": rows, "weighted_tflops": tot_fl / tot_us / 1e6, "peak_tflops": MFMA_PEAK_TFLOPS["bf16"]}))
+    print(json.dumps({"metric": "forward GEMM shapes", "config": {"workload": cfg.name}, "dtype": dt, "data": "synthetic (random operands)",
+                      "shapes": rows, "weighted_tflops": tot_fl / tot_us / 1e6, "peak_tflops": MFMA_PEAK_TFLOPS[dt]}))
 
 
 def main():
@@ -219,6 +221,7 @@ def main():
                     help="also time the cloud block of Algorithm 1 on the same model and batch: one backward pass, and the basis of one matrix from three gradient snapshots")
     ap.add_argument("--gemm-shapes", action="store_true",
                     help="instead of the step: time each forward GEMM shape of the config on its own (random bf16 operands, HIP events) and print one JSON line")
+    ap.add_argument("--gemm-dtype", choices=["bf16", "f32"], default=None, help="with --gemm-shapes: storage type of the operands (default: the config's)")
     ap.add_argument("--with-library", action="store_true", help="with --gemm-shapes: also time torch.matmul (the vendor library) on the same operands, as context")
     args = ap.parse_args()
     if args.gpus != 1:

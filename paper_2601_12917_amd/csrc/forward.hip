@@ -226,6 +226,122 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
     }
 }
 
+// fp32 path on the matrix cores: v_mfma_f32_32x32x2_f32.  Block tile 64 F x 64 F (F = 1 or 2), BK = 16, four waves
+// in 2 x 2, each owning F x F accumulator fragments of 32 x 32.  An fp32 MFMA keeps the matrix pipe busy for 64
+// cycles with two floats per lane, so the operands are no bottleneck: the next k-tile travels global -> registers
+// while the current one is multiplied and is written to the other LDS buffer afterwards, one barrier per k-tile.
+// Four consecutive lanes fetch the 64 contiguous bytes a row contributes to a k-tile.  LDS keeps the rows as they
+// are, [row][16 + 4 pad]; the contraction index is split so that a lane's eight values of a k-tile are contiguous
+// (the half-wave h takes k = 8 h .. 8 h + 7, in both operands alike): two 16-byte reads per fragment and k-tile,
+// conflict-free at a row stride of 20 floats.
+// Any M, N; K % 4 == 0 and 16-byte aligned rows (the 64 x 64 kernel above takes what is left).
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// At least two waves per SIMD, i.e. at most 256 registers per lane: the accumulators then live in ordinary vector registers,
+// which the MFMA reads and writes directly.  (Allowed 512, the compiler multiplies in the accumulation registers, carries
+// the sums round the loop in vector registers and moves all 64 of them back and forth in every k-tile.)
+template <int F, int BK>
+__global__ void __launch_bounds__(256, 2) gemm_f32_mfma_kernel(const float* __restrict__ A, const float* __restrict__ W, int M, int N, int K, GemmEpi ep) {
+  constexpr int BT = 64 * F, LD = BK + 4, KQ = BK / 4, NV = BT * KQ / 256, HK = BK / 2;
+  __shared__ __attribute__((aligned(16))) float As[2][BT][LD], Ws[2][BT][LD];
+  const int m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int wm = (wave >> 1) * 32 * F, wn = (wave & 1) * 32 * F;
+  // a thread moves NV float4 of each operand per k-tile: row r = idx / KQ, k columns 4 (idx % KQ) .. + 3.  Rows past the
+  // matrix are read from its last row (their products are never stored), so only the last, partial k-tile needs a mask.
+  float4 ra[NV], rw[NV];
+  const float* pa[NV];
+  const float* pw[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int idx = tid + 256 * i, r = idx / KQ, kq = idx % KQ;
+    pa[i] = A + (size_t)min(m0 + r, M - 1) * K + 4 * kq;
+    pw[i] = W + (size_t)min(n0 + r, N - 1) * K + 4 * kq;
+  }
+  auto fetch = [&](int k0) {
+    if (k0 + BK <= K) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) { ra[i] = *reinterpret_cast<const float4*>(pa[i] + k0); rw[i] = *reinterpret_cast<const float4*>(pw[i] + k0); }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const bool kin = k0 + 4 * ((tid + 256 * i) % KQ) < K;
+        ra[i] = kin ? *reinterpret_cast<const float4*>(pa[i] + k0) : make_float4(0.f, 0.f, 0.f, 0.f);
+        rw[i] = kin ? *reinterpret_cast<const float4*>(pw[i] + k0) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  };
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int idx = tid + 256 * i, r = idx / KQ, kq = idx % KQ;
+      *reinterpret_cast<float4*>(&As[buf][r][4 * kq]) = ra[i];
+      *reinterpret_cast<float4*>(&Ws[buf][r][4 * kq]) = rw[i];
+    }
+  };
+  f32x16 acc[F][F];
+#pragma unroll
+  for (int f = 0; f < F; ++f)
+#pragma unroll
+    for (int g = 0; g < F; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[f][g][v] = 0.f;
+  // fragments of one k-tile: a lane's HK values of each of its F + F fragment rows
+  auto read_frags = [&](int buf, float (&a)[F][HK], float (&w)[F][HK]) {
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+      for (int q = 0; q < HK / 4; ++q) {
+        const float4 av = *reinterpret_cast<const float4*>(&As[buf][wm + 32 * f + l32][HK * half + 4 * q]);
+        const float4 wv = *reinterpret_cast<const float4*>(&Ws[buf][wn + 32 * f + l32][HK * half + 4 * q]);
+        a[f][4 * q] = av.x; a[f][4 * q + 1] = av.y; a[f][4 * q + 2] = av.z; a[f][4 * q + 3] = av.w;
+        w[f][4 * q] = wv.x; w[f][4 * q + 1] = wv.y; w[f][4 * q + 2] = wv.z; w[f][4 * q + 3] = wv.w;
+      }
+  };
+  auto multiply = [&](const float (&a)[F][HK], const float (&w)[F][HK], int ks0, int ks1) {
+#pragma unroll
+    for (int ks = ks0; ks < ks1; ++ks)
+#pragma unroll
+      for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int g = 0; g < F; ++g) acc[f][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[f][ks], w[g][ks], acc[f][g], 0, 0, 0);
+  };
+  // Three k-tiles are in flight: t in fragment registers (being multiplied), t + 1 in LDS (its fragments are read between
+  // the two halves of t's MFMAs), t + 2 on its way from global memory (written to the buffer of t, which every wave left
+  // before the previous barrier, behind t's MFMAs).  Everything but the MFMAs is issued in their shadow.
+  const int ktiles = (K + BK - 1) / BK;
+  float fa[2][F][HK], fw[2][F][HK];
+  fetch(0);
+  stage(0);
+  if (ktiles > 1) fetch(BK);
+  __syncthreads();
+  read_frags(0, fa[0], fw[0]);
+  if (ktiles > 1) stage(1);
+  __syncthreads();
+  auto step = [&](int kt, float (&ca)[F][HK], float (&cw)[F][HK], float (&na)[F][HK], float (&nw)[F][HK]) {
+    if (kt + 2 < ktiles) fetch((kt + 2) * BK);
+    multiply(ca, cw, 0, HK / 2);
+    if (kt + 1 < ktiles) read_frags((kt + 1) & 1, na, nw);
+    multiply(ca, cw, HK / 2, HK);
+    if (kt + 2 < ktiles) stage(kt & 1);
+    __syncthreads();
+  };
+  for (int kt = 0; kt < ktiles; kt += 2) {
+    step(kt, fa[0], fw[0], fa[1], fw[1]);
+    if (kt + 1 < ktiles) step(kt + 1, fa[1], fw[1], fa[0], fw[0]);
+  }
+  // lane (l32, half) holds column n = l32 of a fragment and its rows 8 (v / 4) + 4 half + v % 4
+#pragma unroll
+  for (int f = 0; f < F; ++f)
+#pragma unroll
+    for (int g = 0; g < F; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm + 32 * f + 8 * (v >> 2) + 4 * half + (v & 3), n = n0 + wn + 32 * g + l32;
+        if (m < M && n < N) epilogue_store<float>(ep, m, n, N, acc[f][g][v]);
+      }
+}
+
 // bf16 path: MFMA 32x32x16.  Block tile BM x BN, BK = 64, WM x WN waves, each owning (BM / WM) x (BN / WN) of
 // the output as FM x FN accumulator fragments of 32 x 32.  Operands go from global memory straight into LDS
 // (no register staging).  Two main loops: the ping-pong pipeline (PP = 1, eight waves, large tiles) and a plain
@@ -953,7 +1069,14 @@ hipError_t launch_layernorm(int dtype, const float* x, const void* g, const void
 hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias, void* out, int epi, int M, int N, int K, hipStream_t s) {
   GemmEpi ep{epi, out, bias};
   if (dtype == 0) {
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, s, (const float*)A, (const float*)W, M, N, K, ep);
+    const bool mfma_ok = K % 4 == 0 && (((uintptr_t)A | (uintptr_t)W) & 15) == 0;
+    const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (mfma_ok && t128 >= 512)   // enough 128 x 128 tiles for two blocks on every CU
+      hipLaunchKernelGGL((gemm_f32_mfma_kernel<2, 16>), dim3((N + 127) / 128, (M + 127) / 128), dim3(256), 0, s, (const float*)A, (const float*)W, M, N, K, ep);
+    else if (mfma_ok)
+      hipLaunchKernelGGL((gemm_f32_mfma_kernel<1, 16>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, s, (const float*)A, (const float*)W, M, N, K, ep);
+    else
+      hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, s, (const float*)A, (const float*)W, M, N, K, ep);
   } else {
     if (K % GB_K != 0) return hipErrorInvalidValue;
     const bf16_t* a = (const bf16_t*)A; const bf16_t* w = (const bf16_t*)W; const bf16_t* b = (const bf16_t*)bias;

@@ -75,3 +75,46 @@ def test_gemm_matches_linear_layer(M, N, K, what, epi):
         tol = 2e-6 * scale + 1e-6 * np.abs(want)
     bad = np.abs(g - want) > tol
     assert not bad.any(), (what, int(bad.sum()), float(np.abs(g - want).max()))
+
+
+#            M     N     K   what it reaches
+F32_SHAPES = [
+    (2048, 2100, 72, "128x128 matrix-core tiles, ragged N, a k-tile of 8 at the end"),
+    (2000, 2304, 768, "128x128 matrix-core tiles, ragged M, the depth of a real layer"),
+    (300, 200, 40, "64x64 matrix-core tiles, ragged both, k-tail"),
+    (64, 64, 4, "one tile, a single quarter-filled k-tile"),
+    (130, 70, 37, "K no multiple of 4: the vector-ALU kernel"),
+]
+
+
+@pytest.mark.parametrize("M,N,K,what", F32_SHAPES)
+@pytest.mark.parametrize("epi", [EPI_STORE, EPI_GELU, EPI_RESID, EPI_F32])
+def test_fp32_gemm_matches_linear_layer(M, N, K, what, epi):
+    """The fp32 projection kernels (v_mfma_f32_32x32x2_f32 tiles, and the plain kernel for what they do not take)
+    against out = act(A W^T + b) in fp64, every output entry."""
+    import torch
+    from paper_2601_12917_amd import binding as B
+    lib = B.lib()
+    dev = "cuda:0"
+    rng = np.random.default_rng(5000 + 1000 * epi + M + N + K)
+    A = (rng.standard_normal((M, K)) * 0.5).astype(np.float32)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    res = (rng.standard_normal((M, N)) * 0.3).astype(np.float32)
+    Ad, Wd, bd = torch.from_numpy(A).to(dev), torch.from_numpy(W).to(dev), torch.from_numpy(bias).to(dev)
+    out = torch.from_numpy(res).to(dev) if epi == EPI_RESID else torch.full((M, N), 7.0, device=dev, dtype=torch.float32)
+    st = torch.cuda.current_stream().cuda_stream
+    B.check(lib.zgr_debug_gemm(0, Ad.data_ptr(), Wd.data_ptr(), bd.data_ptr(), out.data_ptr(), epi, M, N, K, st))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    A64, W64 = A.astype(np.float64), W.astype(np.float64)
+    want = A64 @ W64.T + bias.astype(np.float64)
+    if epi == EPI_GELU:
+        want = F.gelu(want)
+    if epi == EPI_RESID:
+        want = want + res.astype(np.float64)
+    # fp32 products and sums of K terms: a few 2^-24 of sum |a w|; the result's own rounding: 2^-24 |want|
+    scale = np.abs(A64) @ np.abs(W64).T + 0.1
+    tol = 2e-6 * scale + 2e-7 * np.abs(want)
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (what, int(bad.sum()), float(np.abs(got - want).max()))
