@@ -52,3 +52,38 @@ def test_random_model_step_matches_oracle(i, say):
         eps_z = np.float32(cfg.eps) * np.abs(o.z_of(t, 1))
         assert _close_params(sess.get_theta(j), t.theta, cfg.dtype, eps_z), t.name
     sess.close()
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_random_model_cloud_gradients_match_oracle(i, say):
+    """The cloud's backward pass on the same random shapes: fp32 models entry by entry (2e-4 of a tensor's largest entry),
+    bf16 models by direction and norm of every tensor's gradient (their forward half keeps bf16-rounded activations)."""
+    from oracle import cloud as C
+    cfg = _random_config(i)
+    say(f"{cfg.name}: cloud backward, {cfg.dtype}, seq={cfg.seq}, d={cfg.d_model}, {cfg.act}{' post-LN' if cfg.post_ln else ''}")
+    specs, values, bases = inputs_of(cfg)
+    # matrices scaled up so that attention and the activation leave their linear regime
+    gains = (I.ROLE_LN1_G, I.ROLE_LN2_G, I.ROLE_LNF_G)
+    values = [v if s.role in gains else (v * np.float32(4)) for s, v in zip(specs, values)]
+    arrays = make_batch_arrays(cfg)
+    sess = make_session(cfg, specs, values, [None] * len(specs))
+    loss, grads = sess.cloud_backward(session_batch(sess, cfg, arrays))
+    grads = [g.cpu().numpy().astype(np.float64) for g in grads]
+    P = {s.name: v.astype(np.float64) for s, v in zip(specs, values)}
+    if cfg.arch == I.ARCH_DECODER_LM:
+        loss_or, grads_or = C.lm_loss_and_gradients(P, arrays["x"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
+    else:
+        loss_or, grads_or = C.cls_loss_and_gradients(P, arrays["x"], arrays["lengths"], arrays["y"], cfg.n_layer, cfg.n_head, cfg.ln_eps, cfg.act, cfg.post_ln)
+    assert abs(loss - loss_or) <= LOSS_RTOL[cfg.dtype] * max(1.0, abs(loss_or)), (loss, loss_or)
+    top = max(np.abs(g).max() for g in grads_or.values())
+    for j, s in enumerate(specs):
+        want = grads_or[s.name]
+        assert grads[j].shape == want.shape, s.name
+        if cfg.dtype == "f32":
+            err = np.abs(grads[j] - want).max()
+            assert err <= 2e-4 * np.abs(want).max() + 1e-6 * top, (s.name, err, np.abs(want).max())
+        elif s.role != I.ROLE_BK and np.linalg.norm(want) > 1e-3 * top:       # the key bias has an identically zero gradient
+            cos = float((grads[j] * want).sum() / (np.linalg.norm(grads[j]) * np.linalg.norm(want)))
+            ratio = float(np.linalg.norm(grads[j]) / np.linalg.norm(want))
+            assert cos >= 0.99 and abs(ratio - 1.0) <= 0.05, (s.name, cos, ratio)
+    sess.close()
