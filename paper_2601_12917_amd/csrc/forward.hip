@@ -7,6 +7,7 @@
 // Storage type T of weights and GEMM inputs is fp32 or bf16; accumulation, the
 // residual stream, LayerNorm, softmax and the loss are fp32, the final mean fp64.
 #include "forward.h"
+#include <atomic>
 
 namespace zgr {
 
@@ -733,7 +734,7 @@ hipError_t launch_gemm_bf16_t(const bf16_t* A, const bf16_t* W, const bf16_t* bi
   const int grid = ((stm * stn + 7) / 8 * 8) * 32;
 #define ZGR_GEMM_LAUNCH(MODE)                                                                                           \
   {                                                                                                                     \
-    static bool attr_set = false;                                                                                       \
+    static std::atomic<bool> attr_set{false};   /* set twice by racing threads at worst: the call is idempotent */         \
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, BK, STAGES, MODE, PP>;                                                             \
     if (!attr_set) {                                                                                                    \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -1132,7 +1133,7 @@ hipError_t launch_attention(int dtype, const void* qkv, void* ctx, const int32_t
   if (dtype == 1 && d / n_head == 64 && d % 8 == 0) {
     const int kpad = seq < AT_KCH ? (seq + 31) / 32 * 32 : AT_KCH;          // keys resident in LDS at a time
     const size_t lds = sizeof(bf16_t) * ((size_t)kpad * AT_LDK + (size_t)64 * (kpad + 8));
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};     // set twice by racing threads at worst: the calls are idempotent
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_mfma_kernel<64, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;

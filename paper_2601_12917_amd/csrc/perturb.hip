@@ -11,6 +11,7 @@
 //         contracts U R in registers and fuses G, the mix and the axpy.
 #include "internal.h"
 
+#include <atomic>
 #include <mutex>
 
 namespace zgr {
@@ -700,18 +701,27 @@ int resident_blocks_per_cu(K kern, size_t dyn_lds, int cap) {
   return nb < cap ? nb : cap;
 }
 
-// Launch set-up of one tile-kernel variant, done once per LDS size: the dynamic-LDS limit and the occupancy.
+// Launch set-up of one tile-kernel variant: the dynamic-LDS limit (only ever raised, so that contexts with different
+// ranks can take turns) and the occupancy at the LDS size asked for (the last answer is kept).
 struct TileLaunchCache {
+  size_t lds_limit = 0;       // what the kernel's attribute was last set to
   size_t lds = 0;
   int per_cu = 0;
 };
 template <typename K>
-hipError_t tile_launch_setup(K kern, size_t lds, int cap, TileLaunchCache& cache) {
-  if (cache.per_cu > 0 && cache.lds == lds) return hipSuccess;
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  cache.lds = lds;
-  cache.per_cu = resident_blocks_per_cu(kern, lds, cap);
+hipError_t tile_launch_setup(K kern, size_t lds, int cap, TileLaunchCache& cache, int* per_cu) {
+  static std::mutex mu;                                  // the caches are shared by every context of the process
+  std::lock_guard<std::mutex> lock(mu);
+  if (lds > cache.lds_limit) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    cache.lds_limit = lds;
+  }
+  if (!(cache.per_cu > 0 && cache.lds == lds)) {
+    cache.lds = lds;
+    cache.per_cu = resident_blocks_per_cu(kern, lds, cap);
+  }
+  *per_cu = cache.per_cu;
   return hipSuccess;
 }
 
@@ -734,9 +744,10 @@ hipError_t launch_flat_t(const PerturbArgs& a_in, float c, float* zout, hipStrea
     return hipGetLastError();
   }
   auto kern = a.n_q > 0 ? perturb_flat_kernel<T, P, true> : perturb_flat_kernel<T, P, false>;
-  static int per[2] = {0, 0};
-  int& nb = per[a.n_q > 0 ? 1 : 0];
-  if (nb == 0) nb = resident_blocks_per_cu(kern, 0, 8);
+  static std::atomic<int> per[2];                        // zero-initialised; racing threads compute the same value
+  std::atomic<int>& slot = per[a.n_q > 0 ? 1 : 0];
+  int nb = slot.load(std::memory_order_relaxed);
+  if (nb == 0) { nb = resident_blocks_per_cu(kern, 0, 8); slot.store(nb, std::memory_order_relaxed); }
   const int grid = split_grid(a, a.n_flat, n_cu * nb);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, a, a.descs, a.flat, c, tab);
   return hipGetLastError();
@@ -751,18 +762,20 @@ hipError_t launch_tile_t(const PerturbArgs& a_in, float c, float* zout, hipStrea
     const int variant = zout ? 1 : (a.n_q > 0 ? 2 : 0);
     auto km = zout ? perturb_tile_mfma_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_tile_mfma_kernel<T, P, false, true> : perturb_tile_mfma_kernel<T, P, false, false>);
     static TileLaunchCache cache_m[3];
-    hipError_t e = tile_launch_setup(km, lds_m, 8, cache_m[variant]);
+    int per_cu = 1;
+    hipError_t e = tile_launch_setup(km, lds_m, 8, cache_m[variant], &per_cu);
     if (e != hipSuccess) return e;
-    const int grid_m = split_grid(a, a.n_tiles, n_cu * cache_m[variant].per_cu);
+    const int grid_m = split_grid(a, a.n_tiles, n_cu * per_cu);
     hipLaunchKernelGGL(km, dim3(grid_m), dim3(256), lds_m, s, a, a.descs, a.tiles, c, tab, zout, kp);
     return hipGetLastError();
   }
   const int variant = zout ? 1 : (a.n_q > 0 ? 2 : 0);
   auto kern = zout ? perturb_tile_kernel<T, P, true, false> : (a.n_q > 0 ? perturb_tile_kernel<T, P, false, true> : perturb_tile_kernel<T, P, false, false>);
   static TileLaunchCache cache_v[3];
-  hipError_t e = tile_launch_setup(kern, lds, 4, cache_v[variant]);
+  int per_cu = 1;
+  hipError_t e = tile_launch_setup(kern, lds, 4, cache_v[variant], &per_cu);
   if (e != hipSuccess) return e;
-  const int grid = split_grid(a, a.n_tiles, n_cu * cache_v[variant].per_cu);
+  const int grid = split_grid(a, a.n_tiles, n_cu * per_cu);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, a.descs, a.tiles, c, tab, zout, kp);
   return hipGetLastError();
 }
