@@ -966,7 +966,7 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
     return std::isfinite(*loss_out) ? ZGR_OK : fail(c, ZGR_ERR_NONFINITE, "loss is not finite");
   }
   const int B = b->batch, Tn = b->seq, M = B * Tn, d = m.d_model, ff = m.d_ff, H = m.n_head;
-  if (Tn > kBackwardMaxSeq || (size_t)(2 * (d / H) + Tn) * 4 > 48 * 1024) return fail(c, ZGR_ERR_SHAPE, "seq = %d is beyond what the backward attention rule holds", Tn);
+  if (Tn > kBackwardMaxSeq) return fail(c, ZGR_ERR_SHAPE, "seq = %d is beyond the %d keys the backward softmax rule holds per row", Tn, kBackwardMaxSeq);
   const bool lm = m.arch == ZGR_ARCH_DECODER_LM;
   const int32_t* tok = reinterpret_cast<const int32_t*>(b->x);
   const int32_t* lengths = lm ? nullptr : b->lengths;
