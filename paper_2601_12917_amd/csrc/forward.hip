@@ -1123,11 +1123,12 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, const void* bias
     if (t256 >= 256) return launch_gemm_bf16_t<256, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
     if (t128x256 >= 200) return launch_gemm_bf16_t<128, 256, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
     // small problems.  More 128 x 128 tiles than CUs: the ping-pong loop on a short ring (64 KB, two blocks per CU, one block's
-    // epilogue under the other's loop).  Fewer than half the CUs would get such a tile: 64 x 128 tiles with the plain loop.
+    // epilogue under the other's loop).  Fewer than half the CUs would get such a tile: 64 x 64 tiles with the plain loop
+    // (four times the blocks, two of them per CU; 64 x 128 tiles were a few per cent slower).
     // In between (about one tile per CU): the ping-pong loop on the full ring.
     const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
     if (t128 > 256) return launch_gemm_bf16_t<128, 128, 2, 4, 64, 8, 1>(a, w, b, out, epi, M, N, K, s);
-    if (t128 <= 128) return launch_gemm_bf16_t<64, 128, 2, 2, 64, 4>(a, w, b, out, epi, M, N, K, s);
+    if (t128 <= 128) return launch_gemm_bf16_t<64, 64, 2, 2, 64, 4>(a, w, b, out, epi, M, N, K, s);
     return launch_gemm_bf16_t<128, 128, 2, 4, 64, 20, 1>(a, w, b, out, epi, M, N, K, s);
   }
   return hipGetLastError();

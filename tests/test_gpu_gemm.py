@@ -1,6 +1,6 @@
 """The bf16 projection kernels against the oracle's definition of a linear layer, out = act(A W^T + b), in fp64.
 Shapes are chosen to reach every block-tile variant and main loop of the launcher (256 x 256 and 128 x 256 with the
-ping-pong pipeline, 256 x 192 with one wave per SIMD, 128 x 128 with the ping-pong loop on a long and on a short ring, 64 x 128 with the plain loop), with ragged last tiles in M and in N, a single k-tile,
+ping-pong pipeline, 256 x 192 with one wave per SIMD, 128 x 128 with the ping-pong loop on a long and on a short ring, 64 x 64 with the plain loop), with ragged last tiles in M and in N, a single k-tile,
 an odd number of k-tiles, and the depth of the real layers (K = 2048).  Inputs are bf16-representable, so the only
 differences are fp32 accumulation order and the bf16 rounding of stored results."""
 import numpy as np
@@ -21,7 +21,7 @@ SHAPES = [
     (4096, 6144, 2048, "256x192 tiles at the QKV shape"),
     (3300, 2048, 320, "128x256 tiles, ragged M, five k-tiles"),
     (4096, 2000, 2048, "128x256 tiles, ragged N, full depth"),
-    (1000, 600, 128, "64x128 tiles, plain loop, ragged both"),
+    (1000, 600, 128, "64x64 tiles, plain loop, ragged both"),
     (1990, 1500, 192, "128x128 tiles, ping-pong loop on the long ring (at most one tile per CU), ragged both"),
     (2048, 1536, 1024, "128x128 tiles, ping-pong loop on the long ring, 16 k-tiles"),
     (2000, 2200, 320, "128x128 tiles, ping-pong loop on the short ring (more tiles than CUs), ragged both, five k-tiles"),
