@@ -251,12 +251,12 @@ zgr_status zgr_cloud_lsq_gradient(const float* W, const float* X, const float* Y
  * DEVICE pointers, caller-owned, each rows_i * cols_i fp32 row-major, overwritten) = dL/dtheta_i for every tensor the
  * context was created with, in fp32 whatever the storage type; theta itself is left untouched.  The forward half runs
  * the client's own kernels (so a bf16 model's intermediate results are bf16-rounded exactly as in zgr_loss, except
- * that the activation is evaluated from the fp32 pre-activation, GELU by its erf form); both activations and both
- * LayerNorm placements of zgr_model are covered and keeps every layer's results in
- * `workspace` (DEVICE, 256-byte aligned, zgr_cloud_backward_workspace(ctx, batch, seq) bytes: it grows with
- * n_layer * batch * seq * (d_model + d_ff)); the backward half is deterministic (no atomics).  Runs on the context's
- * stream and returns after it has finished.  seq <= 2048.  Errors: ZGR_ERR_NULL, ZGR_ERR_SHAPE (batch outside the
- * context's limits, n_grads != n_t, seq too long), ZGR_ERR_WORKSPACE, ZGR_ERR_STATE (a context without a model),
+ * that the activation is evaluated from the fp32 pre-activation, GELU by its erf form) and keeps every layer's results
+ * in `workspace` (DEVICE, 256-byte aligned, zgr_cloud_backward_workspace(ctx, batch, seq) bytes: it grows with
+ * n_layer * batch * seq * (d_model + d_ff)); both activations and both LayerNorm placements of zgr_model are covered.
+ * The backward half is deterministic (no atomics).  Runs on the context's stream and returns after it has finished.
+ * seq <= 2048, batch * n_head <= 65535.  Errors: ZGR_ERR_NULL, ZGR_ERR_SHAPE (batch outside the context's limits,
+ * n_grads != n_t, seq too long, too many heads), ZGR_ERR_WORKSPACE, ZGR_ERR_STATE (a context without a model),
  * ZGR_ERR_NONFINITE (gradients are then undefined), ZGR_ERR_DEVICE.                                            */
 size_t     zgr_cloud_backward_workspace(const zgr_ctx* ctx, int32_t batch, int32_t seq);
 zgr_status zgr_cloud_backward(zgr_ctx* ctx, const zgr_batch* batch, float* const* grads, int32_t n_grads, double* loss_out,

@@ -967,6 +967,7 @@ zgr_status zgr_cloud_backward(zgr_ctx* c, const zgr_batch* b, float* const* grad
   }
   const int B = b->batch, Tn = b->seq, M = B * Tn, d = m.d_model, ff = m.d_ff, H = m.n_head;
   if (Tn > kBackwardMaxSeq) return fail(c, ZGR_ERR_SHAPE, "seq = %d is beyond the %d keys the backward softmax rule holds per row", Tn, kBackwardMaxSeq);
+  if ((int64_t)B * H > 65535) return fail(c, ZGR_ERR_SHAPE, "batch x heads = %lld is beyond the 65535 heads one batched product of the backward attention takes", (long long)B * H);
   const bool lm = m.arch == ZGR_ARCH_DECODER_LM;
   const int32_t* tok = reinterpret_cast<const int32_t*>(b->x);
   const int32_t* lengths = lm ? nullptr : b->lengths;
