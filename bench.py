@@ -55,7 +55,7 @@ def measured_ceilings(torch, B, dtype_code):
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     cpi, ghz, rate = Cl.issue_rate(lib, B, torch, 0, 1, 8, n_cu=n_cu)
     gbs, _ = Cl.stream_rate(lib, B, torch, 1 << 30, dtype_code, 0, n_cu * 8)
-    _, mghz, mrate = Cl.issue_rate(lib, B, torch, len(Cl.OPS) - 1, 4, 1, iters=4096, n_cu=n_cu)
+    _, mghz, mrate = Cl.issue_rate(lib, B, torch, Cl.N_VECTOR_OPS, 4, 1, iters=4096, n_cu=n_cu)
     return {"simple_issue_T_lane_instr_per_s": rate * 64 / 1e12, "simple_issue_cycles_per_instruction": cpi, "shader_ghz": ghz, "rmw_stream_GBs": gbs,
             "mfma_bf16_alone_TFLOPs": mrate * Cl.MFMA_FLOPS / 1e12, "mfma_bf16_alone_ghz": mghz}
 

@@ -376,7 +376,8 @@ zgr_status zgr_debug_rmw(void* buf, size_t bytes, int32_t dtype, float c, int32_
  * kind op (0 v_fma_f32, 1 v_xor_b32, 2 v_bitop3_b32, 3 v_mad_u64_u32, 4 v_mul_hi_u32, 5 v_mul_lo_u32, 6 v_cvt_f32_u32,
  * 7 v_rsq_f32, 8 v_add_u32, 9 v_lshrrev_b32, 10 v_cndmask_b32, 11 v_mul_f32, 12 v_add_f32, 13 v_log_f32,
  * 14 v_cvt_pk_bf16_f32, 15 v_sqrt_f32, 16 v_mov_b32, 17 the matrix-core instruction v_mfma_f32_32x32x16_bf16 on random
- * bf16 register operands, 32768 flops each) in ilp (1, 2 or 4) independent dependent-chains.  out: DEVICE,
+ * bf16 register operands, 32768 flops each, 18 v_mfma_f32_32x32x2_f32 on random fp32 register operands, 4096 flops
+ * each) in ilp (1, 2 or 4) independent dependent-chains.  out: DEVICE,
  * 4 uint64 per wave (4 * blocks waves): shader cycles of the wave's own run, the 100 MHz real-time counter at its
  * start and at its end, a checksum.  The waves of a SIMD do not advance in step: rates come from the span over all
  * waves (first start to last end).                                                                            */

@@ -13,8 +13,10 @@ import sys
 import numpy as np
 
 OPS = ["v_fma_f32", "v_xor_b32", "v_bitop3_b32", "v_mad_u64_u32", "v_mul_hi_u32", "v_mul_lo_u32", "v_cvt_f32_u32", "v_rsq_f32",
-       "v_add_u32", "v_lshrrev_b32", "v_cndmask_b32", "v_mul_f32", "v_add_f32", "v_log_f32", "v_cvt_pk_bf16_f32", "v_sqrt_f32", "v_mov_b32", "v_mfma_f32_32x32x16_bf16"]
+       "v_add_u32", "v_lshrrev_b32", "v_cndmask_b32", "v_mul_f32", "v_add_f32", "v_log_f32", "v_cvt_pk_bf16_f32", "v_sqrt_f32", "v_mov_b32", "v_mfma_f32_32x32x16_bf16", "v_mfma_f32_32x32x2_f32"]
+N_VECTOR_OPS = 17                     # the entries before the two matrix instructions
 MFMA_FLOPS = 2.0 * 32 * 32 * 16
+MFMA_F32_FLOPS = 2.0 * 32 * 32 * 2
 
 
 def issue_rate(lib, B, torch, op, ilp, waves_per_simd, iters=512, n_cu=None):
@@ -98,7 +100,7 @@ def main():
                     print(f"| {dname} | {nbytes} | {mname} | {blocks} | {ms:.3f} | {gbs:.0f} |")
     print("\n## Vector-instruction issue rate (cycles per wave64 instruction and SIMD; shader cycle counter s_memtime, clock from the 100 MHz s_memrealtime)\n")
     print("| instruction | chains per wave | waves per SIMD | cycles / instruction | shader clock GHz | T wave-instr/s (chip) |\n|---|---:|---:|---:|---:|---:|")
-    for op, name in enumerate(OPS[:-1]):
+    for op, name in enumerate(OPS[:N_VECTOR_OPS]):
         for ilp, wps in ((1, 1), (4, 1), (1, 4), (4, 4), (1, 8), (4, 8)):
             if name not in ("v_fma_f32", "v_xor_b32", "v_mad_u64_u32") and (ilp, wps) not in ((1, 1), (4, 8), (1, 8)):
                 continue
@@ -109,9 +111,16 @@ def main():
     print("| accumulators per wave | waves per SIMD | cycles / instruction | shader clock GHz | TFLOP/s (chip) |\n|---:|---:|---:|---:|---:|")
     res["mfma"] = []
     for ilp, wps in ((1, 1), (4, 1), (2, 2), (4, 2)):
-        cpi, ghz, rate = issue_rate(lib, B, torch, len(OPS) - 1, ilp, wps, iters=4096, n_cu=n_cu)
+        cpi, ghz, rate = issue_rate(lib, B, torch, N_VECTOR_OPS, ilp, wps, iters=4096, n_cu=n_cu)
         res["mfma"].append({"ilp": ilp, "waves_per_simd": wps, "cycles_per_instruction": cpi, "shader_ghz": ghz, "tflops": rate * MFMA_FLOPS / 1e12})
         print(f"| {ilp} | {wps} | {cpi:.2f} | {ghz:.2f} | {rate * MFMA_FLOPS / 1e12:.0f} |")
+    print("\n## The fp32 matrix instruction alone (v_mfma_f32_32x32x2_f32 on register operands of random fp32; dense peak quoted at 2.4 GHz: 157.3 TFLOP/s)\n")
+    print("| accumulators per wave | waves per SIMD | cycles / instruction | shader clock GHz | TFLOP/s (chip) |\n|---:|---:|---:|---:|---:|")
+    res["mfma_f32"] = []
+    for ilp, wps in ((1, 1), (4, 1), (4, 2), (4, 3)):
+        cpi, ghz, rate = issue_rate(lib, B, torch, N_VECTOR_OPS + 1, ilp, wps, iters=2048, n_cu=n_cu)
+        res["mfma_f32"].append({"ilp": ilp, "waves_per_simd": wps, "cycles_per_instruction": cpi, "shader_ghz": ghz, "tflops": rate * MFMA_F32_FLOPS / 1e12})
+        print(f"| {ilp} | {wps} | {cpi:.2f} | {ghz:.2f} | {rate * MFMA_F32_FLOPS / 1e12:.0f} |")
     print("\n## The Gaussian generator's parts alone (cycles per call and SIMD; a call is one lane's work for 4 Gaussians, 64 lanes per wave)\n")
     print("| part | waves per SIMD | cycles / call | shader clock GHz |\n|---|---:|---:|---:|")
     res["generator"] = []

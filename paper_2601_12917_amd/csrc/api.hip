@@ -1389,7 +1389,7 @@ zgr_status zgr_debug_rmw(void* buf, size_t bytes, int32_t dtype, float c, int32_
 
 zgr_status zgr_debug_issue_rate(int32_t op, int32_t ilp, int32_t blocks, int32_t iters, uint64_t* out, void* hip_stream) {
   if (!out) return fail(nullptr, ZGR_ERR_NULL, "out is NULL");
-  if (op < 0 || op > 17 || (ilp != 1 && ilp != 2 && ilp != 4) || blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20))
+  if (op < 0 || op > 18 || (ilp != 1 && ilp != 2 && ilp != 4) || blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20))
     return fail(nullptr, ZGR_ERR_CONFIG, "bad instruction kind, chain count, grid or iteration count");
   HIP_TRY(nullptr, launch_debug_issue(op, ilp, blocks, iters, reinterpret_cast<unsigned long long*>(out), reinterpret_cast<hipStream_t>(hip_stream)));
   return ZGR_OK;

@@ -147,6 +147,46 @@ __global__ void __launch_bounds__(256) mfma_kernel(int iters, unsigned long long
 #endif
 }
 
+// The same for the fp32 matrix instruction, v_mfma_f32_32x32x2_f32 (4096 flops each), on random fp32 register operands.
+// At least two waves per SIMD are allowed for, so that the accumulators stay in ordinary vector registers.
+template <int ILP>
+__global__ void __launch_bounds__(256, 2) mfma_f32_kernel(int iters, unsigned long long* __restrict__ out) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  float a[ILP], b[ILP];
+  cf32x16 acc[ILP];
+  uint32_t h = (blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int i = 0; i < ILP; ++i) {
+    // random sign and mantissa, exponent of 1.0
+    h = h * 1664525u + 1013904223u;  a[i] = __uint_as_float((h & 0x807fffffu) | 0x3f800000u);
+    h = h * 1664525u + 1013904223u;  b[i] = __uint_as_float((h & 0x807fffffu) | 0x3f800000u);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  }
+  __builtin_amdgcn_s_barrier();
+  const unsigned long long c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 64 / ILP; ++r)
+#pragma unroll
+      for (int i = 0; i < ILP; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[i], acc[i], 0, 0, 0);
+  }
+  const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+  float f = 0.f;
+#pragma unroll
+  for (int i = 0; i < ILP; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) f += acc[i][j];
+  if ((threadIdx.x & 63) == 0) {
+    const size_t w = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    out[4 * w] = c1 - c0;
+    out[4 * w + 1] = r0;
+    out[4 * w + 2] = r1;
+    out[4 * w + 3] = __float_as_uint(f);
+  }
+#endif
+}
+
 // The generator's own parts at full occupancy of the vector unit and nothing else: part 0 one Philox4x32-10 call,
 // 1 two radii, 2 two (cos, sin) pairs, 3 two Box-Muller pairs (on cheap pseudo-random integers), 4 the whole
 // generator of four Gaussians (Philox call + two Box-Muller pairs), 5 its two table look-ups alone.
@@ -233,6 +273,13 @@ hipError_t launch_debug_issue(int op, int ilp, int blocks, int iters, unsigned l
     if (ilp == 1) hipLaunchKernelGGL(mfma_kernel<1>, dim3(blocks), dim3(256), 0, s, iters, out);
     else if (ilp == 2) hipLaunchKernelGGL(mfma_kernel<2>, dim3(blocks), dim3(256), 0, s, iters, out);
     else if (ilp == 4) hipLaunchKernelGGL(mfma_kernel<4>, dim3(blocks), dim3(256), 0, s, iters, out);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
+  if (op == 18) {
+    if (ilp == 1) hipLaunchKernelGGL(mfma_f32_kernel<1>, dim3(blocks), dim3(256), 0, s, iters, out);
+    else if (ilp == 2) hipLaunchKernelGGL(mfma_f32_kernel<2>, dim3(blocks), dim3(256), 0, s, iters, out);
+    else if (ilp == 4) hipLaunchKernelGGL(mfma_f32_kernel<4>, dim3(blocks), dim3(256), 0, s, iters, out);
     else return hipErrorInvalidValue;
     return hipGetLastError();
   }
