@@ -812,7 +812,8 @@ zgr_status zgr_quantize_basis(const float* U, int64_t rows, int32_t k, int32_t l
 
 size_t zgr_cloud_basis_workspace(int64_t rows, int64_t cols, int32_t k) {
   if (rows < 1 || cols < 1 || k < 1 || k > kMaxK) return 0;
-  return 2 * align_up((size_t)rows * k * 4) + align_up((size_t)cols * k * 4) + 256;
+  const size_t longer = (size_t)(rows > cols ? rows : cols);
+  return 2 * align_up((size_t)rows * k * 4) + align_up((size_t)cols * k * 4) + 256 + align_up((size_t)kCloudMaxParts * longer * k * 4);
 }
 
 zgr_status zgr_cloud_basis(const float* const* snapshots, int32_t n_snap, int64_t rows, int64_t cols, int32_t k, const float* omega, int32_t n_iter,
@@ -828,14 +829,15 @@ zgr_status zgr_cloud_basis(const float* const* snapshots, int32_t n_snap, int64_
   float* Y = reinterpret_cast<float*>(ws + yb);          // the block being built by a sweep
   float* T = reinterpret_cast<float*>(ws + 2 * yb);      // G_t^T Q of one snapshot
   int* dep = reinterpret_cast<int*>(ws + 2 * yb + align_up((size_t)cols * k * 4));
+  float* part = reinterpret_cast<float*>(ws + 2 * yb + align_up((size_t)cols * k * 4) + 256);   // partial sums of the split products
   // Q = orth(sum_t G_t Omega)
-  for (int t = 0; t < n_snap; ++t) HIP_TRY(nullptr, launch_cloud_g_t(snapshots[t], rows, cols, omega, k, Q, t > 0, s));
+  for (int t = 0; t < n_snap; ++t) HIP_TRY(nullptr, launch_cloud_g_t(snapshots[t], rows, cols, omega, k, Q, t > 0, s, part));
   HIP_TRY(nullptr, launch_cloud_orth(Q, rows, k, dep, s));
   // sweeps Q <- orth(sum_t G_t (G_t^T Q))
   for (int it = 0; it < n_iter; ++it) {
     for (int t = 0; t < n_snap; ++t) {
-      HIP_TRY(nullptr, launch_cloud_gt_q(snapshots[t], rows, cols, cols, Q, k, k, T, k, 1.0f, 0, s));
-      HIP_TRY(nullptr, launch_cloud_g_t(snapshots[t], rows, cols, T, k, Y, t > 0, s));
+      HIP_TRY(nullptr, launch_cloud_gt_q(snapshots[t], rows, cols, cols, Q, k, k, T, k, 1.0f, 0, s, part));
+      HIP_TRY(nullptr, launch_cloud_g_t(snapshots[t], rows, cols, T, k, Y, t > 0, s, part));
     }
     float* tmp = Q; Q = Y; Y = tmp;
     HIP_TRY(nullptr, launch_cloud_orth(Q, rows, k, dep, s));

@@ -24,16 +24,20 @@ constexpr int kChunk = 32;     // the other dimension, staged per step
 
 // T[c][j] (+)= sum_r G[r][c] Q[r][j],  c < cols, j < n: G [rows, cols] (row stride ldg), Q [rows, n] (row stride ldq).
 // Block = 64 columns c x 64 columns j (blockIdx.y tiles j); thread (c = tid % 64, jg = tid / 64) holds 16 values of j.
+// blockIdx.z = part of the sum: rows [z row_part, (z + 1) row_part) go to T + z t_part (partial sums that sum_parts_kernel adds in order).
 __global__ void __launch_bounds__(256) gt_q_kernel(const float* __restrict__ G, int64_t rows, int64_t cols, int64_t ldg, const float* __restrict__ Q, int n, int64_t ldq,
-                                                   float* __restrict__ T, int64_t ldt, float scale, int accumulate) {
+                                                   float* __restrict__ T, int64_t ldt, float scale, int accumulate, int64_t row_part, int64_t t_part) {
   __shared__ float Gs[kChunk][kTile + 1], Qs[kChunk][kTile + 1];
   const int tid = threadIdx.x, cl = tid & 63, jg = tid >> 6;
   const int64_t c0 = (int64_t)blockIdx.x * kTile;
   const int j0 = blockIdx.y * kTile;
+  const int64_t r_begin = (int64_t)blockIdx.z * row_part;
+  rows = rows < r_begin + row_part ? rows : r_begin + row_part;
+  T += (int64_t)blockIdx.z * t_part;
   float acc[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-  for (int64_t r0 = 0; r0 < rows; r0 += kChunk) {
+  for (int64_t r0 = r_begin; r0 < rows; r0 += kChunk) {
     __syncthreads();
     for (int i = tid; i < kChunk * kTile; i += 256) {
       const int rr = i >> 6, cc = i & 63;
@@ -57,23 +61,27 @@ __global__ void __launch_bounds__(256) gt_q_kernel(const float* __restrict__ G, 
 }
 
 // Y[r][j] (+)= sum_c G[r][c] T[c][j],  r < rows, j < k <= 64.  Block = 64 rows; thread (r = tid % 64, jg = tid / 64).
+// blockIdx.y = part of the sum: columns [y col_part, (y + 1) col_part) go to Y + y y_part.
 __global__ void __launch_bounds__(256) g_t_kernel(const float* __restrict__ G, int64_t rows, int64_t cols, const float* __restrict__ T, int k,
-                                                  float* __restrict__ Y, int accumulate) {
+                                                  float* __restrict__ Y, int accumulate, int64_t col_part, int64_t y_part) {
   __shared__ float Gs[kTile][kChunk + 1], Ts[kChunk][kTile + 1];
   const int tid = threadIdx.x, rl = tid & 63, jg = tid >> 6;
   const int64_t r0 = (int64_t)blockIdx.x * kTile;
+  const int64_t c_begin = (int64_t)blockIdx.y * col_part;
+  const int64_t c_end = cols < c_begin + col_part ? cols : c_begin + col_part;
+  Y += (int64_t)blockIdx.y * y_part;
   float acc[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-  for (int64_t c0 = 0; c0 < cols; c0 += kChunk) {
+  for (int64_t c0 = c_begin; c0 < c_end; c0 += kChunk) {
     __syncthreads();
     for (int i = tid; i < kTile * kChunk; i += 256) {
       const int rr = i >> 5, cc = i & 31;                 // consecutive threads read consecutive columns of G
-      Gs[rr][cc] = (r0 + rr < rows && c0 + cc < cols) ? G[(r0 + rr) * cols + c0 + cc] : 0.f;
+      Gs[rr][cc] = (r0 + rr < rows && c0 + cc < c_end) ? G[(r0 + rr) * cols + c0 + cc] : 0.f;
     }
     for (int i = tid; i < kChunk * kTile; i += 256) {
       const int cc = i >> 6, jj = i & 63;
-      Ts[cc][jj] = (c0 + cc < cols && jj < k) ? T[(c0 + cc) * k + jj] : 0.f;
+      Ts[cc][jj] = (c0 + cc < c_end && jj < k) ? T[(c0 + cc) * k + jj] : 0.f;
     }
     __syncthreads();
 #pragma unroll 4
@@ -161,6 +169,15 @@ __global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Y, int64
   if (tid == 0) *dependent = n_dep;
 }
 
+// out[i] = (accumulate ? out[i] : 0) + scale (part[0][i] + part[1][i] + ...): the parts of a split sum, added in their order
+__global__ void __launch_bounds__(256) sum_parts_kernel(const float* __restrict__ part, int n_parts, int64_t stride, int64_t n, float* __restrict__ out, float scale, int accumulate) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float v = 0.f;
+    for (int z = 0; z < n_parts; ++z) v += part[(int64_t)z * stride + i];
+    out[i] = (accumulate ? out[i] : 0.f) + scale * v;
+  }
+}
+
 __global__ void __launch_bounds__(256) copy_basis_kernel(const float* __restrict__ Q, int64_t rows, int k, float* __restrict__ U, int ldu) {
   const int64_t n = rows * k;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) U[(i / k) * ldu + (i % k)] = Q[i];
@@ -173,16 +190,50 @@ __global__ void __launch_bounds__(256) residual_kernel(float* __restrict__ R, co
 
 }  // namespace
 
-hipError_t launch_cloud_gt_q(const float* G, int64_t rows, int64_t cols, int64_t ldg, const float* Q, int n, int64_t ldq, float* T, int64_t ldt, float scale,
-                             int accumulate, hipStream_t s) {
-  const dim3 grid((unsigned)((cols + kTile - 1) / kTile), (unsigned)((n + kTile - 1) / kTile));
-  hipLaunchKernelGGL(gt_q_kernel, grid, dim3(256), 0, s, G, rows, cols, ldg, Q, n, ldq, T, ldt, scale, accumulate);
+// How many parts to split a sum over `span` terms into, so that `blocks` blocks become about one per CU-slot: at most kCloudMaxParts,
+// each part a whole number of staged chunks.
+static int cloud_sum_parts(int64_t blocks, int64_t span) {
+  int64_t z = blocks > 0 ? 512 / blocks : 1;
+  const int64_t chunks = (span + kChunk - 1) / kChunk;
+  if (z > chunks) z = chunks;
+  if (z > kCloudMaxParts) z = kCloudMaxParts;
+  return z < 1 ? 1 : (int)z;
+}
+
+static hipError_t launch_sum_parts(const float* part, int n_parts, int64_t stride, int64_t n, float* out, float scale, int accumulate, hipStream_t s) {
+  hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)(n / 256 + 1 < 1024 ? n / 256 + 1 : 1024)), dim3(256), 0, s, part, n_parts, stride, n, out, scale, accumulate);
   return hipGetLastError();
 }
 
-hipError_t launch_cloud_g_t(const float* G, int64_t rows, int64_t cols, const float* T, int k, float* Y, int accumulate, hipStream_t s) {
-  hipLaunchKernelGGL(g_t_kernel, dim3((unsigned)((rows + kTile - 1) / kTile)), dim3(256), 0, s, G, rows, cols, T, k, Y, accumulate);
-  return hipGetLastError();
+// part: scratch of kCloudMaxParts * cols * n floats (ldt == n), or NULL for a single pass over all the rows
+hipError_t launch_cloud_gt_q(const float* G, int64_t rows, int64_t cols, int64_t ldg, const float* Q, int n, int64_t ldq, float* T, int64_t ldt, float scale,
+                             int accumulate, hipStream_t s, float* part) {
+  const unsigned gx = (unsigned)((cols + kTile - 1) / kTile), gy = (unsigned)((n + kTile - 1) / kTile);
+  const int z = (part && ldt == n) ? cloud_sum_parts((int64_t)gx * gy, rows) : 1;
+  if (z <= 1) {
+    hipLaunchKernelGGL(gt_q_kernel, dim3(gx, gy), dim3(256), 0, s, G, rows, cols, ldg, Q, n, ldq, T, ldt, scale, accumulate, rows, (int64_t)0);
+    return hipGetLastError();
+  }
+  const int64_t chunks = (rows + kChunk - 1) / kChunk, row_part = (chunks + z - 1) / z * kChunk, stride = cols * (int64_t)n;
+  hipLaunchKernelGGL(gt_q_kernel, dim3(gx, gy, (unsigned)z), dim3(256), 0, s, G, rows, cols, ldg, Q, n, ldq, part, (int64_t)n, 1.0f, 0, row_part, stride);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_sum_parts(part, z, stride, stride, T, scale, accumulate, s);
+}
+
+// part: scratch of kCloudMaxParts * rows * k floats, or NULL for a single pass over all the columns
+hipError_t launch_cloud_g_t(const float* G, int64_t rows, int64_t cols, const float* T, int k, float* Y, int accumulate, hipStream_t s, float* part) {
+  const unsigned gx = (unsigned)((rows + kTile - 1) / kTile);
+  const int z = part ? cloud_sum_parts(gx, cols) : 1;
+  if (z <= 1) {
+    hipLaunchKernelGGL(g_t_kernel, dim3(gx), dim3(256), 0, s, G, rows, cols, T, k, Y, accumulate, cols, (int64_t)0);
+    return hipGetLastError();
+  }
+  const int64_t chunks = (cols + kChunk - 1) / kChunk, col_part = (chunks + z - 1) / z * kChunk, stride = rows * (int64_t)k;
+  hipLaunchKernelGGL(g_t_kernel, dim3(gx, (unsigned)z), dim3(256), 0, s, G, rows, cols, T, k, part, 0, col_part, stride);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_sum_parts(part, z, stride, stride, Y, 1.0f, accumulate, s);
 }
 
 hipError_t launch_cloud_orth(float* Y, int64_t rows, int k, int* dependent, hipStream_t s) {

@@ -94,10 +94,13 @@ hipError_t launch_debug_rmw(void* p, size_t bytes, int dtype, float c, int mode,
 hipError_t launch_debug_issue(int op, int ilp, int blocks, int iters, unsigned long long* out, hipStream_t s);
 hipError_t launch_debug_generator(int part, int blocks, int iters, unsigned long long* out, hipStream_t s);
 
-// cloud side (cloud.hip): tall-skinny products with the gradient snapshots, orthonormalisation, least-squares residual
+// cloud side (cloud.hip): tall-skinny products with the gradient snapshots, orthonormalisation, least-squares residual.
+// part (optional scratch): the sum over the long dimension is split into up to kCloudMaxParts parts over more blocks and the
+// parts are added in their order; kCloudMaxParts * cols * n floats for gt_q (needs ldt == n), kCloudMaxParts * rows * k for g_t.
+constexpr int kCloudMaxParts = 16;
 hipError_t launch_cloud_gt_q(const float* G, int64_t rows, int64_t cols, int64_t ldg, const float* Q, int n, int64_t ldq, float* T, int64_t ldt, float scale,
-                             int accumulate, hipStream_t s);
-hipError_t launch_cloud_g_t(const float* G, int64_t rows, int64_t cols, const float* T, int k, float* Y, int accumulate, hipStream_t s);
+                             int accumulate, hipStream_t s, float* part = nullptr);
+hipError_t launch_cloud_g_t(const float* G, int64_t rows, int64_t cols, const float* T, int k, float* Y, int accumulate, hipStream_t s, float* part = nullptr);
 hipError_t launch_cloud_orth(float* Y, int64_t rows, int k, int* dependent, hipStream_t s);
 hipError_t launch_cloud_copy_basis(const float* Q, int64_t rows, int k, float* U, int ldu, hipStream_t s);
 hipError_t launch_cloud_residual(float* R, const float* Y, int64_t n, hipStream_t s);
