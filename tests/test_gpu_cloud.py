@@ -44,6 +44,9 @@ def _check_basis(snaps, k, n_iter, ldu=None, seed=0):
     (300, 136, 2, 16, None),     # ragged in both directions
     (2048, 264, 2, 16, 64),      # several row and column tiles, k' = 16 of 64 columns as in the largest workload
     (70, 50, 1, 64, None),       # maximum rank, more columns asked than the other dimension... minus a few
+    (70, 3000, 2, 8, None),      # one row tile, a long sum over the columns: split into 16 ragged parts
+    (5000, 100, 2, 8, None),     # the other way round: many row tiles, the sum over the rows split
+    (96, 544, 1, 8, None),       # 17 column chunks on 16 parts of two: the last parts start past the end and add nothing
 ])
 def test_basis_of_snapshots_with_a_spectral_gap(rows, cols, s, k, ldu):
     if k > min(rows, cols * s):
