@@ -14,6 +14,7 @@
 // the caller picks n_iter for the gap it expects.  This runs every gamma rounds on the cloud, not on the client's
 // step: it is written to be correct and bandwidth-shaped, not tuned.
 #include "internal.h"
+#include <atomic>
 
 namespace zgr {
 
@@ -103,11 +104,21 @@ __global__ void __launch_bounds__(256) g_t_kernel(const float* __restrict__ G, i
 // Householder for any column that is not dependent to working precision), then y_j /= ||y_j||.  Dot products are
 // accumulated in fp64.  A column that the earlier ones already span (norm below 1e-6 of what it started with)
 // is stored as zeros and counted in *dependent.
-__global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Y, int64_t rows, int k, int* __restrict__ dependent) {
+// IN_LDS: the block is copied into LDS first (row stride k + 1, so that threads on consecutive rows hit different banks) and
+// written back at the end: the 3 k sweeps over the rows then cost LDS latency instead of L2 latency.  Same arithmetic, same order.
+template <bool IN_LDS>
+__global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Yg, int64_t rows, int k, int* __restrict__ dependent) {
   __shared__ double red[16][kMaxK];
   __shared__ double coef[kMaxK];
   __shared__ int n_dep;
+  extern __shared__ float orth_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ld = IN_LDS ? k + 1 : k;
+  float* Y = IN_LDS ? orth_lds : Yg;
+  if (IN_LDS) {
+    for (int64_t i = tid; i < rows * k; i += 1024) Y[(i / k) * ld + (i % k)] = Yg[i];
+    __syncthreads();
+  }
   if (tid == 0) n_dep = 0;
   for (int j = 0; j < k; ++j) {
     double norm0 = 0.0;
@@ -119,7 +130,7 @@ __global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Y, int64
 #pragma unroll
         for (int i = 0; i < 8; ++i) part[i] = 0.0;
         for (int64_t r = tid; r < rows; r += 1024) {
-          const float* row = Y + r * k;
+          const float* row = Y + r * ld;
           const double yj = (double)row[j];
 #pragma unroll
           for (int i = 0; i < 8; ++i)
@@ -142,7 +153,7 @@ __global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Y, int64
       if (pass < 2) {
         if (pass == 0) {                                           // remember the column's size before anything is taken out
           double n0 = 0.0;
-          for (int64_t r = tid; r < rows; r += 1024) { const double y = (double)Y[r * k + j]; n0 += y * y; }
+          for (int64_t r = tid; r < rows; r += 1024) { const double y = (double)Y[r * ld + j]; n0 += y * y; }
           for (int o = 32; o > 0; o >>= 1) n0 += __shfl_xor(n0, o, 64);
           __syncthreads();
           if (lane == 0) red[wave][kMaxK - 1] = n0;
@@ -150,7 +161,7 @@ __global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Y, int64
           for (int w = 0; w < 16; ++w) norm0 += red[w][kMaxK - 1];
         }
         for (int64_t r = tid; r < rows; r += 1024) {
-          float* row = Y + r * k;
+          float* row = Y + r * ld;
           double y = (double)row[j];
           for (int i = 0; i < j; ++i) y -= coef[i] * (double)row[i];
           row[j] = (float)y;
@@ -160,11 +171,15 @@ __global__ void __launch_bounds__(1024) orth_kernel(float* __restrict__ Y, int64
         const double nrm2 = coef[0];
         const bool dep = !(nrm2 > 1e-12 * norm0) || !(nrm2 > 0.0);
         const double inv = dep ? 0.0 : 1.0 / sqrt(nrm2);
-        for (int64_t r = tid; r < rows; r += 1024) Y[r * k + j] = (float)((double)Y[r * k + j] * inv);
+        for (int64_t r = tid; r < rows; r += 1024) Y[r * ld + j] = (float)((double)Y[r * ld + j] * inv);
         if (tid == 0 && dep) n_dep += 1;
         __syncthreads();
       }
     }
+  }
+  if (IN_LDS) {
+    __syncthreads();
+    for (int64_t i = tid; i < rows * k; i += 1024) Yg[i] = Y[(i / k) * ld + (i % k)];
   }
   if (tid == 0) *dependent = n_dep;
 }
@@ -237,7 +252,19 @@ hipError_t launch_cloud_g_t(const float* G, int64_t rows, int64_t cols, const fl
 }
 
 hipError_t launch_cloud_orth(float* Y, int64_t rows, int k, int* dependent, hipStream_t s) {
-  hipLaunchKernelGGL(orth_kernel, dim3(1), dim3(1024), 0, s, Y, rows, k, dependent);
+  // the block in LDS when it fits beside the kernel's own 9 KB (rows (k + 1) floats: 2048 x 16 does, 8192 x 16 does not)
+  const size_t lds = (size_t)rows * (size_t)(k + 1) * sizeof(float);
+  if (lds <= 144 * 1024) {
+    static std::atomic<bool> attr_set{false};              // set twice by racing threads at worst: the call is idempotent
+    if (!attr_set) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(orth_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(orth_kernel<true>, dim3(1), dim3(1024), lds, s, Y, rows, k, dependent);
+  } else {
+    hipLaunchKernelGGL(orth_kernel<false>, dim3(1), dim3(1024), 0, s, Y, rows, k, dependent);
+  }
   return hipGetLastError();
 }
 
